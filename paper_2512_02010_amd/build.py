@@ -1,0 +1,46 @@
+"""Compile the HIP library in-tree: ``paper_2512_02010_amd/libnvfp4_46.so`` (gfx950 only)."""
+from __future__ import annotations
+
+import os
+import shutil
+import subprocess
+from pathlib import Path
+
+PKG = Path(__file__).resolve().parent
+ROOT = PKG.parent
+SRC = PKG / "csrc" / "nvfp4_46.hip"
+SO = PKG / "libnvfp4_46.so"
+
+# -ffp-contract=off: the method's arithmetic is one rounding per operation.
+# -packed-fp32-ops off: never let the compiler form v_pk_*_f32 from scalar float code.
+HIPCC_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wno-unused-function",
+]
+
+# which narrow-format conversions use the gfx950 instructions (see csrc/codec.hpp)
+DEFAULT_DEFINES = {"NVFP4_46_HW_FP4": 0, "NVFP4_46_HW_FP8": 0, "NVFP4_46_HW_BF16": 0}
+
+
+def hipcc() -> str:
+    for cand in (os.environ.get("HIPCC"), shutil.which("hipcc"), "/opt/rocm/bin/hipcc"):
+        if cand and Path(cand).exists():
+            return cand
+    raise RuntimeError("hipcc not found")
+
+
+def build(out: Path | None = None, defines: dict | None = None, extra: list | None = None) -> Path:
+    out = Path(out) if out else SO
+    d = dict(DEFAULT_DEFINES)
+    d.update(defines or {})
+    tmp = out.with_suffix(f".tmp{os.getpid()}.so")
+    cmd = [hipcc(), *HIPCC_FLAGS, *[f"-D{k}={v}" for k, v in d.items()], *(extra or []),
+           f"-I{ROOT / 'include'}", f"-I{PKG / 'csrc'}", str(SRC), "-o", str(tmp)]
+    subprocess.run(cmd, check=True)
+    os.replace(tmp, out)
+    return out
+
+
+if __name__ == "__main__":
+    print(build())

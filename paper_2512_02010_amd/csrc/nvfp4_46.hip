@@ -1,0 +1,767 @@
+// Kernels and C ABI of libnvfp4_46.so (gfx950).  See include/nvfp4_46.h for the
+// contract of every entry point.
+//
+// Data movement
+//   rowwise   A row-major tensor whose rows are multiples of 16 is one flat
+//             stream of 16-element blocks, and so are its outputs: block k reads
+//             32 bytes at 32k, writes 8 code bytes at 8k and 1 scale byte at k.
+//             One lane owns one block (two 128-bit loads, all 16 values in
+//             registers, no cross-lane traffic); a wave's 64 lanes cover 2 KiB of
+//             contiguous input, 512 B of codes and 64 B of scales.
+//   columnwise / both
+//             A workgroup stages a 128x128 tile of x in LDS (coalesced 128-bit
+//             loads), every lane then reads two adjacent columns x 16 rows from
+//             LDS, and the results go back through LDS so that each column's 64
+//             code bytes leave as one contiguous run.  When both orientations
+//             are wanted the rowwise half is produced from the registers of the
+//             staging loads, so x is read from HBM once.
+#include <hip/hip_runtime.h>
+
+#include "block.hpp"
+#include "nvfp4_46.h"
+
+namespace nvfp4_46 {
+
+constexpr int kThreads = 256;
+enum : int { kOutCodes = 0, kOutFake = 1, kOutAmax = 2 };
+
+NV_DEV void unpack16(const uint4 &w0, const uint4 &w1, float (&v)[16]) {
+  const uint32_t w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    v[2 * j] = bf16_lo(w[j]);
+    v[2 * j + 1] = bf16_hi(w[j]);
+  }
+}
+
+NV_DEV float wave_max(float m) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+  return m;
+}
+
+// Largest magnitude of a non-negative-float bit pattern set: unsigned order
+// equals value order, so an integer atomic max is exact and order-free.
+NV_DEV void publish_amax(float m, uint32_t *amax_bits) {
+  m = wave_max(m);
+  if ((threadIdx.x & 63) == 0) atomicMax(amax_bits, f2u(m));
+}
+
+// ------------------------------------------------------------ tensor scale
+
+__global__ void k_store_u32(uint32_t *p, uint32_t v) { *p = v; }
+
+// Eq. (1): alpha = amax / (6 * fp8_max); an all-zero tensor gets alpha = 1.
+__global__ void k_finish_alpha(float *alpha, float fp8_max) {
+  float amax = *alpha;
+  *alpha = (amax == 0.0f) ? 1.0f : amax / (6.0f * fp8_max);
+}
+
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
+// max|x| without the transform: compare BF16 magnitudes as 15-bit integers.
+__global__ __launch_bounds__(kThreads) void k_amax_plain(const uint4 *__restrict__ x, int64_t n16,
+                                                         uint32_t *amax_bits) {
+  u16x2 acc = {0, 0};
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += stride) {
+    uint4 w = x[i];
+    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      uint32_t m = ww[j] & 0x7fff7fffu;
+      acc = __builtin_elementwise_max(acc, *reinterpret_cast<u16x2 *>(&m));
+    }
+  }
+  uint32_t top = acc.x > acc.y ? acc.x : acc.y;
+  publish_amax(u2f(top << 16), amax_bits);
+}
+
+// -------------------------------------------------------- rowwise (flat)
+
+template <int ROUNDING, int SELECT, bool RHT, int OUT>
+__global__ __launch_bounds__(kThreads) void k_flat(
+    const uint4 *__restrict__ x, const float *__restrict__ alpha_p, uint2 *__restrict__ codes,
+    uint8_t *__restrict__ scales, uint8_t *__restrict__ choice, uint4 *__restrict__ out_bf16,
+    uint32_t *amax_bits, int64_t nblocks, uint32_t nb_per_row, uint64_t sr_seed,
+    uint64_t rht_seed) {
+  __shared__ ScaleTable tab;
+  float c6 = 0.0f, c4 = 0.0f;
+  if (OUT != kOutAmax) {
+    const float alpha = *alpha_p;
+    build_scale_table(tab, alpha);
+    c6 = alpha * 6.0f;
+    c4 = alpha * 4.0f;
+  }
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  uint32_t B = 0, B_step = 0;
+  if (RHT) {
+    B = (uint32_t)(k % nb_per_row);
+    B_step = (uint32_t)(stride % nb_per_row);
+  }
+  float amax = 0.0f;
+  for (; k < nblocks; k += stride) {
+    float v[16], u[16];
+    unpack16(x[2 * k], x[2 * k + 1], v);
+    if (RHT) {
+      rht16(v, rht_sign_word(rht_seed, B));
+      B += B_step;
+      if (B >= nb_per_row) B -= nb_per_row;
+    }
+    if (OUT == kOutAmax) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(v[i]));
+      continue;
+    }
+    if (ROUNDING == kSR) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) sr_uniforms4(sr_seed, (uint64_t)k * 4u + j, &u[4 * j]);
+    }
+    BlockResult r = quantize_block<ROUNDING, SELECT>(v, u, c6, c4, tab);
+    if (OUT == kOutCodes) {
+      codes[k] = make_uint2(r.lo, r.hi);
+      scales[k] = (uint8_t)r.scale;
+      if (choice) choice[k] = (uint8_t)r.four;
+    } else {
+      float D0[8], D1[8];
+      dequant8(r.lo, r.dec, D0);
+      dequant8(r.hi, r.dec, D1);
+      out_bf16[2 * k] = make_uint4(pack_bf16x2(D0[0], D0[1]), pack_bf16x2(D0[2], D0[3]),
+                                   pack_bf16x2(D0[4], D0[5]), pack_bf16x2(D0[6], D0[7]));
+      out_bf16[2 * k + 1] = make_uint4(pack_bf16x2(D1[0], D1[1]), pack_bf16x2(D1[2], D1[3]),
+                                       pack_bf16x2(D1[4], D1[5]), pack_bf16x2(D1[6], D1[7]));
+    }
+  }
+  if (OUT == kOutAmax) publish_amax(amax, amax_bits);
+}
+
+// One lane per 8 elements: 4 code bytes + the block's scale -> 8 BF16.
+__global__ __launch_bounds__(kThreads) void k_dequant_flat(const uint32_t *__restrict__ codes,
+                                                           const uint8_t *__restrict__ scales,
+                                                           const float *__restrict__ alpha_p,
+                                                           uint4 *__restrict__ out, int64_t n8) {
+  const float alpha = *alpha_p;
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x; t < n8; t += stride) {
+    float dec = e4m3_decode_sw(scales[t >> 1]) * alpha;
+    float D[8];
+    dequant8(codes[t], dec, D);
+    out[t] = make_uint4(pack_bf16x2(D[0], D[1]), pack_bf16x2(D[2], D[3]), pack_bf16x2(D[4], D[5]),
+                        pack_bf16x2(D[6], D[7]));
+  }
+}
+
+// ------------------------------------------------ columnwise / both (tiled)
+
+constexpr int TR = 128;  // tile rows
+constexpr int TC = 128;  // tile columns
+
+struct TileCoord {
+  int64_t r0, c0;
+  bool valid;
+};
+
+// Workgroups are handed to the 8 XCDs round-robin by their index, and each XCD
+// has its own L2.  Tiles that are vertical neighbours complete the same output
+// cache lines of the columnwise arrays, so all tiles of one tile-column go to
+// one XCD, in top-to-bottom order.
+NV_DEV TileCoord tile_of_workgroup(int64_t rows, int64_t cols) {
+  const uint32_t nt_r = (uint32_t)((rows + TR - 1) / TR), nt_c = (uint32_t)((cols + TC - 1) / TC);
+  const uint32_t xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;
+  const uint32_t tcg = slot / nt_r, tr = slot - tcg * nt_r;
+  const uint32_t tc = tcg * 8u + xcd;
+  return TileCoord{(int64_t)tr * TR, (int64_t)tc * TC, tc < nt_c};
+}
+
+template <int ROUNDING, int SELECT, bool RHT, bool WANT_ROW, int OUT>
+__global__ __launch_bounds__(kThreads) void k_tile(
+    const uint16_t *__restrict__ x, const float *__restrict__ alpha_p,
+    uint8_t *__restrict__ codes_row, uint8_t *__restrict__ scales_row,
+    uint8_t *__restrict__ choice_row, uint8_t *__restrict__ codes_col,
+    uint8_t *__restrict__ scales_col, uint8_t *__restrict__ choice_col,
+    uint16_t *__restrict__ out_bf16, uint32_t *amax_bits, int64_t rows, int64_t cols,
+    uint64_t sr_seed, uint64_t rht_seed) {
+  __shared__ ScaleTable tab;
+  __shared__ __align__(16) uint32_t tile[TR * TC / 2];  // BF16 pairs, row-major, 32 KiB
+  // columnwise results wait here until a whole column segment can leave at once
+  __shared__ uint2 stage_codes[OUT == kOutCodes ? TC * 8 : 1];     // [TC][8]  8 KiB
+  __shared__ uint8_t stage_scale[OUT == kOutCodes ? TC * 8 : 1];   // [TC][8]  1 KiB
+  __shared__ uint8_t stage_choice[OUT == kOutCodes ? TC * 8 : 1];  // [TC][8]  1 KiB
+
+  const TileCoord tcd = tile_of_workgroup(rows, cols);
+  if (!tcd.valid) return;  // uniform over the workgroup
+  const int64_t r0 = tcd.r0, c0 = tcd.c0;
+  const int t = threadIdx.x;
+
+  float c6 = 0.0f, c4 = 0.0f;
+  if (OUT != kOutAmax) {
+    const float alpha = *alpha_p;
+    build_scale_table(tab, alpha);
+    c6 = alpha * 6.0f;
+    c4 = alpha * 4.0f;
+  }
+
+  // ---- phase 1: global -> LDS (and the rowwise outputs on the way)
+  {
+    uint4 w[4][2];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int unit = t + j * kThreads;          // 1024 row-blocks of the tile
+      const int row = unit >> 3, rbk = unit & 7;
+      const int64_t gr = r0 + row, gc = c0 + rbk * 16;
+      const uint4 *src = reinterpret_cast<const uint4 *>(x + gr * cols + gc);
+      w[j][0] = w[j][1] = make_uint4(0, 0, 0, 0);   // outside the tensor: zeros
+      if (gr < rows && gc < cols) w[j][0] = src[0];
+      if (gr < rows && gc + 8 < cols) w[j][1] = src[1];
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int unit = t + j * kThreads;
+      uint4 *dst = reinterpret_cast<uint4 *>(tile) + unit * 2;
+      dst[0] = w[j][0];
+      dst[1] = w[j][1];
+    }
+    if (WANT_ROW) {
+      // the lane's own four row-blocks, taken back from LDS one at a time (keeps the
+      // register footprint of the quantizer to a single block)
+      const int64_t nb_per_row = cols / 16;
+#pragma unroll 1
+      for (int j = 0; j < 4; ++j) {
+        const int unit = t + j * kThreads;
+        const int row = unit >> 3, rbk = unit & 7;
+        const int64_t gr = r0 + row, gc = c0 + rbk * 16;
+        if (gr < rows && gc < cols) {
+          float v[16], u[16];
+          const uint4 *own = reinterpret_cast<const uint4 *>(tile) + unit * 2;
+          unpack16(own[0], own[1], v);
+          const int64_t k = gr * nb_per_row + (gc >> 4);
+          if (ROUNDING == kSR) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) sr_uniforms4(sr_seed, (uint64_t)k * 4u + q, &u[4 * q]);
+          }
+          BlockResult r = quantize_block<ROUNDING, SELECT>(v, u, c6, c4, tab);
+          reinterpret_cast<uint2 *>(codes_row)[k] = make_uint2(r.lo, r.hi);
+          scales_row[k] = (uint8_t)r.scale;
+          if (choice_row) choice_row[k] = (uint8_t)r.four;
+        }
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- phase 2: every lane takes two adjacent columns x 16 rows, twice.  A (column
+  // pair, row block) unit is read and, for the fake-quant output, rewritten in place by
+  // its owner lane only, so no barrier is needed inside this phase.
+  float amax = 0.0f;
+#pragma unroll 1
+  for (int j = 0; j < 2; ++j) {
+    const int pu = t + j * kThreads;              // 512 (column pair, row block) units
+    const int cp = pu & 63, rb = pu >> 6;
+    const int64_t gr = r0 + rb * 16;              // first row of the block
+    const int64_t gc = c0 + 2 * cp;               // even column of the pair
+    if (gr >= rows || gc >= cols) continue;       // (cols is even, so the pair is in or out together)
+    float va[16], vb[16], ua[16], ub[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const uint32_t pair = tile[(rb * 16 + i) * (TC / 2) + cp];
+      va[i] = bf16_lo(pair);
+      vb[i] = bf16_hi(pair);
+    }
+    if (RHT) {
+      const uint32_t sw = rht_sign_word(rht_seed, (uint64_t)(gr >> 4));
+      rht16(va, sw);
+      rht16(vb, sw);
+    }
+    if (OUT == kOutAmax) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fmaxf(fabsf(va[i]), fabsf(vb[i])));
+      continue;
+    }
+    if (ROUNDING == kSR) {
+      // element (row, col) has flat index g = row*cols + col; the pair (gc, gc+1) shares a
+      // Philox call because gc is even and cols is a multiple of 4
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const uint64_t g = (uint64_t)(gr + i) * (uint64_t)cols + (uint64_t)gc;
+        float uu[4];
+        sr_uniforms4(sr_seed, g >> 2, uu);
+        ua[i] = (g & 2u) ? uu[2] : uu[0];
+        ub[i] = (g & 2u) ? uu[3] : uu[1];
+      }
+    }
+    BlockResult ra = quantize_block<ROUNDING, SELECT>(va, ua, c6, c4, tab);
+    BlockResult rbk = quantize_block<ROUNDING, SELECT>(vb, ub, c6, c4, tab);
+    if (OUT == kOutCodes) {
+      const int ia = (2 * cp) * 8 + rb, ib = (2 * cp + 1) * 8 + rb;
+      stage_codes[ia] = make_uint2(ra.lo, ra.hi);
+      stage_codes[ib] = make_uint2(rbk.lo, rbk.hi);
+      stage_scale[ia] = (uint8_t)ra.scale;
+      stage_scale[ib] = (uint8_t)rbk.scale;
+      stage_choice[ia] = (uint8_t)ra.four;
+      stage_choice[ib] = (uint8_t)rbk.four;
+    } else {
+      float Da[16], Db[16];
+      {
+        float h[8];
+        dequant8(ra.lo, ra.dec, h);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) Da[i] = h[i];
+        dequant8(ra.hi, ra.dec, h);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) Da[8 + i] = h[i];
+        dequant8(rbk.lo, rbk.dec, h);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) Db[i] = h[i];
+        dequant8(rbk.hi, rbk.dec, h);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) Db[8 + i] = h[i];
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) tile[(rb * 16 + i) * (TC / 2) + cp] = pack_bf16x2(Da[i], Db[i]);
+    }
+  }
+  if (OUT == kOutAmax) {
+    publish_amax(amax, amax_bits);
+    return;
+  }
+  __syncthreads();
+
+  // ---- phase 3: LDS -> global, contiguous runs
+  if (OUT == kOutCodes) {
+    const int64_t col_codes = rows / 2, col_scales = rows / 16;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int it = t + j * kThreads;            // 1024 (column, row block) items
+      const int cl = it >> 3, rb = it & 7;
+      const int64_t gc = c0 + cl, gr = r0 + rb * 16;
+      if (gc < cols && gr < rows) {
+        *reinterpret_cast<uint2 *>(codes_col + gc * col_codes + (gr >> 1)) = stage_codes[it];
+        scales_col[gc * col_scales + (gr >> 4)] = stage_scale[it];
+        if (choice_col) choice_col[gc * col_scales + (gr >> 4)] = stage_choice[it];
+      }
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int idx = t + j * kThreads;           // 2048 128-bit pieces of the tile
+      const int row = idx >> 4, seg = idx & 15;
+      const int64_t gr = r0 + row, gc = c0 + seg * 8;
+      if (gr < rows && gc < cols)
+        *reinterpret_cast<uint4 *>(out_bf16 + gr * cols + gc) =
+            reinterpret_cast<const uint4 *>(tile)[idx];
+    }
+  }
+}
+
+// Columnwise codes/scales -> row-major BF16, through a 128x128 LDS tile.
+__global__ __launch_bounds__(kThreads) void k_dequant_col(const uint8_t *__restrict__ codes,
+                                                          const uint8_t *__restrict__ scales,
+                                                          const float *__restrict__ alpha_p,
+                                                          uint16_t *__restrict__ out, int64_t rows,
+                                                          int64_t cols) {
+  __shared__ __align__(16) uint16_t tile16[TR * TC];
+  const TileCoord tcd = tile_of_workgroup(rows, cols);
+  if (!tcd.valid) return;
+  const int64_t r0 = tcd.r0, c0 = tcd.c0;
+  const int t = threadIdx.x;
+  const float alpha = *alpha_p;
+  const int64_t col_codes = rows / 2, col_scales = rows / 16;
+#pragma unroll 1
+  for (int j = 0; j < 4; ++j) {
+    const int it = t + j * kThreads;
+    const int cl = it >> 3, rb = it & 7;
+    const int64_t gc = c0 + cl, gr = r0 + rb * 16;
+    if (gc < cols && gr < rows) {
+      const uint2 c = *reinterpret_cast<const uint2 *>(codes + gc * col_codes + (gr >> 1));
+      const float dec = e4m3_decode_sw(scales[gc * col_scales + (gr >> 4)]) * alpha;
+      float D[8];
+      dequant8(c.x, dec, D);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) tile16[(rb * 16 + i) * TC + cl] = (uint16_t)pack_bf16x2(D[i], 0.0f);
+      dequant8(c.y, dec, D);
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        tile16[(rb * 16 + 8 + i) * TC + cl] = (uint16_t)pack_bf16x2(D[i], 0.0f);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int idx = t + j * kThreads;
+    const int row = idx >> 4, seg = idx & 15;
+    const int64_t gr = r0 + row, gc = c0 + seg * 8;
+    if (gr < rows && gc < cols)
+      *reinterpret_cast<uint4 *>(out + gr * cols + gc) =
+          reinterpret_cast<const uint4 *>(tile16)[idx];
+  }
+}
+
+// ------------------------------------------------------------ debug kernels
+
+__global__ void k_dbg_e2m1_rtn(uint32_t first, int64_t n, uint8_t *out) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+    float y = u2f(first + (uint32_t)i);
+#if NVFP4_46_HW_FP4
+    out[i] = (uint8_t)(hw_pk_fp4<0>(0u, y, 0.0f) & 15u);
+#else
+    out[i] = (uint8_t)e2m1_rtn_sw(y);
+#endif
+  }
+}
+
+__global__ void k_dbg_e4m3(uint32_t first, int64_t n, uint8_t *out) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+    out[i] = (uint8_t)e4m3_encode(u2f(first + (uint32_t)i));
+}
+
+__global__ void k_dbg_tables(float *out) {
+  const int t = threadIdx.x;
+  if (t < 16) {
+    float D[8];
+    dequant8((uint32_t)t, 1.0f, D);     // code t in nibble 0
+    out[t] = D[0];
+  }
+  if (t < 256) out[16 + t] = e4m3_decode_sw((uint32_t)t & 0x7fu);
+}
+
+__global__ void k_dbg_bf16(uint32_t first, uint32_t stride_bits, int64_t n, uint16_t *out) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+    out[i] = (uint16_t)pack_bf16x2(u2f(first + (uint32_t)i * stride_bits), 0.0f);
+}
+
+__global__ void k_dbg_e2m1_sr(const float *y, const float *u, int64_t n, uint8_t *out) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+    out[i] = (uint8_t)e2m1_code_of_grid_value(e2m1_sr_value(y[i], u[i]));
+}
+
+__global__ void k_dbg_philox(const uint32_t *ctr, uint32_t k0, uint32_t k1, int64_t n,
+                             uint32_t *out) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+    Philox4 p = philox4x32_10(ctr[4 * i], ctr[4 * i + 1], ctr[4 * i + 2], ctr[4 * i + 3], k0, k1);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) out[4 * i + j] = p.w[j];
+  }
+}
+
+// ---------------------------------------------------------------- launchers
+
+static int grid_for(int64_t work_items, int per_cu) {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      cus = prop.multiProcessorCount;
+    if (cus <= 0) cus = 256;
+  }
+  int64_t need = (work_items + kThreads - 1) / kThreads;
+  int64_t cap = (int64_t)cus * per_cu;
+  if (need < 1) need = 1;
+  return (int)(need < cap ? need : cap);
+}
+
+static int launch_status() { return hipGetLastError() == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP; }
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct FlatArgs {
+  const uint4 *x;
+  const float *alpha;
+  uint2 *codes;
+  uint8_t *scales, *choice;
+  uint4 *out;
+  uint32_t *amax;
+  int64_t nblocks;
+  uint32_t nb_per_row;
+  uint64_t sr_seed, rht_seed;
+  hipStream_t stream;
+};
+
+template <int ROUNDING, int SELECT, bool RHT, int OUT>
+static void launch_flat(const FlatArgs &a) {
+  const int grid = grid_for(a.nblocks, 8);
+  hipLaunchKernelGGL((k_flat<ROUNDING, SELECT, RHT, OUT>), dim3(grid), dim3(kThreads), 0, a.stream,
+                     a.x, a.alpha, a.codes, a.scales, a.choice, a.out, a.amax, a.nblocks,
+                     a.nb_per_row, a.sr_seed, a.rht_seed);
+}
+
+template <int ROUNDING, int SELECT, bool RHT>
+static void launch_flat_out(const FlatArgs &a, int out) {
+  if (out == kOutCodes)
+    launch_flat<ROUNDING, SELECT, RHT, kOutCodes>(a);
+  else
+    launch_flat<ROUNDING, SELECT, RHT, kOutFake>(a);
+}
+
+template <int ROUNDING, int SELECT>
+static void launch_flat_rht(const FlatArgs &a, bool rht, int out) {
+  if (rht)
+    launch_flat_out<ROUNDING, SELECT, true>(a, out);
+  else
+    launch_flat_out<ROUNDING, SELECT, false>(a, out);
+}
+
+template <int ROUNDING>
+static void launch_flat_sel(const FlatArgs &a, uint32_t select, bool rht, int out) {
+  if (select == NVFP4_SEL_46_MSE)
+    launch_flat_rht<ROUNDING, kSel46>(a, rht, out);
+  else if (select == NVFP4_SEL_FORCE6)
+    launch_flat_rht<ROUNDING, kSelForce6>(a, rht, out);
+  else
+    launch_flat_rht<ROUNDING, kSelForce4>(a, rht, out);
+}
+
+static void dispatch_flat(const FlatArgs &a, uint32_t rounding, uint32_t select, bool rht, int out) {
+  if (rounding == NVFP4_SR)
+    launch_flat_sel<kSR>(a, select, rht, out);
+  else
+    launch_flat_sel<kRTN>(a, select, rht, out);
+}
+
+struct TileArgs {
+  const uint16_t *x;
+  const float *alpha;
+  uint8_t *codes_row, *scales_row, *choice_row, *codes_col, *scales_col, *choice_col;
+  uint16_t *out;
+  uint32_t *amax;
+  int64_t rows, cols;
+  uint64_t sr_seed, rht_seed;
+  hipStream_t stream;
+};
+
+static int tile_grid(int64_t rows, int64_t cols) {
+  const int64_t nt_r = (rows + TR - 1) / TR, nt_c = (cols + TC - 1) / TC;
+  return (int)(8 * ((nt_c + 7) / 8) * nt_r);
+}
+
+template <int ROUNDING, int SELECT, bool RHT, bool WANT_ROW, int OUT>
+static void launch_tile(const TileArgs &a) {
+  hipLaunchKernelGGL((k_tile<ROUNDING, SELECT, RHT, WANT_ROW, OUT>), dim3(tile_grid(a.rows, a.cols)),
+                     dim3(kThreads), 0, a.stream, a.x, a.alpha, a.codes_row, a.scales_row,
+                     a.choice_row, a.codes_col, a.scales_col, a.choice_col, a.out, a.amax, a.rows,
+                     a.cols, a.sr_seed, a.rht_seed);
+}
+
+// variant: 0 = columnwise codes, 1 = columnwise codes + rht, 2 = both orientations,
+//          3 = columnwise fake-quant, 4 = columnwise fake-quant + rht
+template <int ROUNDING, int SELECT>
+static void launch_tile_variant(const TileArgs &a, int variant) {
+  switch (variant) {
+    case 0: launch_tile<ROUNDING, SELECT, false, false, kOutCodes>(a); break;
+    case 1: launch_tile<ROUNDING, SELECT, true, false, kOutCodes>(a); break;
+    case 2: launch_tile<ROUNDING, SELECT, false, true, kOutCodes>(a); break;
+    case 3: launch_tile<ROUNDING, SELECT, false, false, kOutFake>(a); break;
+    default: launch_tile<ROUNDING, SELECT, true, false, kOutFake>(a); break;
+  }
+}
+
+static void dispatch_tile(const TileArgs &a, uint32_t rounding, uint32_t select, int variant) {
+  if (rounding == NVFP4_SR) {
+    if (select == NVFP4_SEL_46_MSE) launch_tile_variant<kSR, kSel46>(a, variant);
+    else if (select == NVFP4_SEL_FORCE6) launch_tile_variant<kSR, kSelForce6>(a, variant);
+    else launch_tile_variant<kSR, kSelForce4>(a, variant);
+  } else {
+    if (select == NVFP4_SEL_46_MSE) launch_tile_variant<kRTN, kSel46>(a, variant);
+    else if (select == NVFP4_SEL_FORCE6) launch_tile_variant<kRTN, kSelForce6>(a, variant);
+    else launch_tile_variant<kRTN, kSelForce4>(a, variant);
+  }
+}
+
+// Checks shared by the entry points that take the parameter block.
+static int check_params(const void *x, const nvfp4_46_params *p, bool one_layout_only) {
+  if (!x || !p) return NVFP4_ERR_NULL;
+  if (p->rows <= 0 || p->cols <= 0) return NVFP4_ERR_SHAPE;
+  if (p->layout < 1u || p->layout > 3u) return NVFP4_ERR_PARAM;
+  if (one_layout_only && p->layout == 3u) return NVFP4_ERR_PARAM;
+  if (p->rounding > NVFP4_SR || p->select > NVFP4_SEL_FORCE4 || p->rht > 1u || p->reserved != 0u)
+    return NVFP4_ERR_PARAM;
+  if (!(p->fp8_max > 0.0f) || !(p->fp8_max <= 448.0f)) return NVFP4_ERR_PARAM;
+  if ((p->layout & NVFP4_ROWWISE) && (p->cols % 16) != 0) return NVFP4_ERR_SHAPE;
+  if ((p->layout & NVFP4_COLWISE) && ((p->rows % 16) != 0 || (p->cols % 8) != 0))
+    return NVFP4_ERR_SHAPE;
+  if (p->rows > (int64_t)1 << 31 || p->cols > (int64_t)1 << 31 ||
+      p->rows * p->cols > (int64_t)1 << 40)
+    return NVFP4_ERR_SHAPE;
+  if (!aligned16(x)) return NVFP4_ERR_ALIGN;
+  if (p->rht && p->layout == 3u) return NVFP4_ERR_UNSUPPORTED;
+  return NVFP4_OK;
+}
+
+}  // namespace nvfp4_46
+
+using namespace nvfp4_46;
+
+extern "C" {
+
+int nvfp4_46_tensor_scale(const void *x_bf16, const nvfp4_46_params *p, float *alpha,
+                          void *stream) {
+  if (!alpha) return NVFP4_ERR_NULL;
+  int rc = check_params(x_bf16, p, false);
+  if (rc != NVFP4_OK) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  uint32_t *amax = reinterpret_cast<uint32_t *>(alpha);
+  hipLaunchKernelGGL(k_store_u32, dim3(1), dim3(1), 0, s, amax, 0u);
+  const int64_t n = p->rows * p->cols;
+  if (!p->rht) {
+    const int64_t n16 = n / 8;  // 128-bit pieces (n is a multiple of 8 by the shape checks)
+    hipLaunchKernelGGL(k_amax_plain, dim3(grid_for(n16, 8)), dim3(kThreads), 0, s,
+                       static_cast<const uint4 *>(x_bf16), n16, amax);
+  } else if (p->layout == NVFP4_ROWWISE) {
+    FlatArgs a{static_cast<const uint4 *>(x_bf16), nullptr, nullptr, nullptr, nullptr, nullptr, amax,
+               n / 16, (uint32_t)(p->cols / 16), 0, p->rht_seed, s};
+    launch_flat<kRTN, kSel46, true, kOutAmax>(a);
+  } else {
+    TileArgs a{static_cast<const uint16_t *>(x_bf16), nullptr, nullptr, nullptr, nullptr, nullptr,
+               nullptr, nullptr, nullptr, amax, p->rows, p->cols, 0, p->rht_seed, s};
+    launch_tile<kRTN, kSel46, true, false, kOutAmax>(a);
+  }
+  hipLaunchKernelGGL(k_finish_alpha, dim3(1), dim3(1), 0, s, alpha, p->fp8_max);
+  return launch_status();
+}
+
+int nvfp4_46_quantize(const void *x_bf16, const nvfp4_46_params *p, const float *alpha,
+                      void *codes_row, void *scales_row, void *codes_col, void *scales_col,
+                      void *choice_row, void *choice_col, void *stream) {
+  if (!alpha) return NVFP4_ERR_NULL;
+  int rc = check_params(x_bf16, p, false);
+  if (rc != NVFP4_OK) return rc;
+  const bool want_row = p->layout & NVFP4_ROWWISE, want_col = p->layout & NVFP4_COLWISE;
+  if (want_row && (!codes_row || !scales_row)) return NVFP4_ERR_NULL;
+  if (want_col && (!codes_col || !scales_col)) return NVFP4_ERR_NULL;
+  if (!want_row && (codes_row || scales_row || choice_row)) return NVFP4_ERR_PARAM;
+  if (!want_col && (codes_col || scales_col || choice_col)) return NVFP4_ERR_PARAM;
+  if (!aligned16(codes_row) || !aligned16(scales_row) || !aligned16(codes_col) ||
+      !aligned16(scales_col) || !aligned16(choice_row) || !aligned16(choice_col))
+    return NVFP4_ERR_ALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!want_col) {
+    FlatArgs a{static_cast<const uint4 *>(x_bf16), alpha, static_cast<uint2 *>(codes_row),
+               static_cast<uint8_t *>(scales_row), static_cast<uint8_t *>(choice_row), nullptr,
+               nullptr, p->rows * p->cols / 16, (uint32_t)(p->cols / 16), p->sr_seed, p->rht_seed, s};
+    dispatch_flat(a, p->rounding, p->select, p->rht != 0, kOutCodes);
+  } else {
+    TileArgs a{static_cast<const uint16_t *>(x_bf16), alpha, static_cast<uint8_t *>(codes_row),
+               static_cast<uint8_t *>(scales_row), static_cast<uint8_t *>(choice_row),
+               static_cast<uint8_t *>(codes_col), static_cast<uint8_t *>(scales_col),
+               static_cast<uint8_t *>(choice_col), nullptr, nullptr, p->rows, p->cols, p->sr_seed,
+               p->rht_seed, s};
+    dispatch_tile(a, p->rounding, p->select, want_row ? 2 : (p->rht ? 1 : 0));
+  }
+  return launch_status();
+}
+
+int nvfp4_46_dequantize(const void *codes, const void *scales, const float *alpha, int64_t rows,
+                        int64_t cols, uint32_t layout, void *out_bf16, void *stream) {
+  if (!codes || !scales || !alpha || !out_bf16) return NVFP4_ERR_NULL;
+  if (rows <= 0 || cols <= 0) return NVFP4_ERR_SHAPE;
+  if (layout != NVFP4_ROWWISE && layout != NVFP4_COLWISE) return NVFP4_ERR_PARAM;
+  if (layout == NVFP4_ROWWISE && (cols % 16) != 0) return NVFP4_ERR_SHAPE;
+  if (layout == NVFP4_COLWISE && ((rows % 16) != 0 || (cols % 8) != 0)) return NVFP4_ERR_SHAPE;
+  if (rows > (int64_t)1 << 31 || cols > (int64_t)1 << 31 || rows * cols > (int64_t)1 << 40)
+    return NVFP4_ERR_SHAPE;
+  if (!aligned16(codes) || !aligned16(scales) || !aligned16(out_bf16)) return NVFP4_ERR_ALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (layout == NVFP4_ROWWISE) {
+    const int64_t n8 = rows * cols / 8;
+    hipLaunchKernelGGL(k_dequant_flat, dim3(grid_for(n8, 16)), dim3(kThreads), 0, s,
+                       static_cast<const uint32_t *>(codes), static_cast<const uint8_t *>(scales),
+                       alpha, static_cast<uint4 *>(out_bf16), n8);
+  } else {
+    hipLaunchKernelGGL(k_dequant_col, dim3(tile_grid(rows, cols)), dim3(kThreads), 0, s,
+                       static_cast<const uint8_t *>(codes), static_cast<const uint8_t *>(scales),
+                       alpha, static_cast<uint16_t *>(out_bf16), rows, cols);
+  }
+  return launch_status();
+}
+
+int nvfp4_46_fake_quant(const void *x_bf16, const nvfp4_46_params *p, const float *alpha,
+                        void *out_bf16, void *stream) {
+  if (!alpha || !out_bf16) return NVFP4_ERR_NULL;
+  int rc = check_params(x_bf16, p, true);
+  if (rc != NVFP4_OK) return rc;
+  if (!aligned16(out_bf16)) return NVFP4_ERR_ALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (p->layout == NVFP4_ROWWISE) {
+    FlatArgs a{static_cast<const uint4 *>(x_bf16), alpha, nullptr, nullptr, nullptr,
+               static_cast<uint4 *>(out_bf16), nullptr, p->rows * p->cols / 16,
+               (uint32_t)(p->cols / 16), p->sr_seed, p->rht_seed, s};
+    dispatch_flat(a, p->rounding, p->select, p->rht != 0, kOutFake);
+  } else {
+    TileArgs a{static_cast<const uint16_t *>(x_bf16), alpha, nullptr, nullptr, nullptr, nullptr,
+               nullptr, nullptr, static_cast<uint16_t *>(out_bf16), nullptr, p->rows, p->cols,
+               p->sr_seed, p->rht_seed, s};
+    dispatch_tile(a, p->rounding, p->select, p->rht ? 4 : 3);
+  }
+  return launch_status();
+}
+
+const char *nvfp4_46_status_string(int status) {
+  switch (status) {
+    case NVFP4_OK: return "ok";
+    case NVFP4_ERR_NULL: return "a required pointer is NULL";
+    case NVFP4_ERR_SHAPE: return "bad shape (dims must be positive, blocked axis a multiple of 16)";
+    case NVFP4_ERR_ALIGN: return "buffer not 16-byte aligned";
+    case NVFP4_ERR_PARAM: return "invalid parameter value";
+    case NVFP4_ERR_UNSUPPORTED: return "unsupported combination of options";
+    case NVFP4_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int nvfp4_46_debug_e2m1_rtn_range(uint32_t first_bits, int64_t n, void *out_u8, void *stream) {
+  if (!out_u8) return NVFP4_ERR_NULL;
+  if (n <= 0) return NVFP4_ERR_SHAPE;
+  hipLaunchKernelGGL(k_dbg_e2m1_rtn, dim3(grid_for(n, 8)), dim3(kThreads), 0,
+                     static_cast<hipStream_t>(stream), first_bits, n, static_cast<uint8_t *>(out_u8));
+  return launch_status();
+}
+
+int nvfp4_46_debug_e4m3_range(uint32_t first_bits, int64_t n, void *out_u8, void *stream) {
+  if (!out_u8) return NVFP4_ERR_NULL;
+  if (n <= 0) return NVFP4_ERR_SHAPE;
+  hipLaunchKernelGGL(k_dbg_e4m3, dim3(grid_for(n, 8)), dim3(kThreads), 0,
+                     static_cast<hipStream_t>(stream), first_bits, n, static_cast<uint8_t *>(out_u8));
+  return launch_status();
+}
+
+int nvfp4_46_debug_decode_tables(void *out_f32, void *stream) {
+  if (!out_f32) return NVFP4_ERR_NULL;
+  hipLaunchKernelGGL(k_dbg_tables, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<float *>(out_f32));
+  return launch_status();
+}
+
+int nvfp4_46_debug_bf16_range(uint32_t first_bits, uint32_t stride, int64_t n, void *out_u16,
+                              void *stream) {
+  if (!out_u16) return NVFP4_ERR_NULL;
+  if (n <= 0) return NVFP4_ERR_SHAPE;
+  hipLaunchKernelGGL(k_dbg_bf16, dim3(grid_for(n, 8)), dim3(kThreads), 0,
+                     static_cast<hipStream_t>(stream), first_bits, stride, n,
+                     static_cast<uint16_t *>(out_u16));
+  return launch_status();
+}
+
+int nvfp4_46_debug_e2m1_sr(const float *y, const float *u, int64_t n, void *out_u8, void *stream) {
+  if (!y || !u || !out_u8) return NVFP4_ERR_NULL;
+  if (n <= 0) return NVFP4_ERR_SHAPE;
+  hipLaunchKernelGGL(k_dbg_e2m1_sr, dim3(grid_for(n, 8)), dim3(kThreads), 0,
+                     static_cast<hipStream_t>(stream), y, u, n, static_cast<uint8_t *>(out_u8));
+  return launch_status();
+}
+
+int nvfp4_46_debug_philox(const uint32_t *ctr, uint32_t key0, uint32_t key1, int64_t n,
+                          uint32_t *out, void *stream) {
+  if (!ctr || !out) return NVFP4_ERR_NULL;
+  if (n <= 0) return NVFP4_ERR_SHAPE;
+  hipLaunchKernelGGL(k_dbg_philox, dim3(grid_for(n, 8)), dim3(kThreads), 0,
+                     static_cast<hipStream_t>(stream), ctr, key0, key1, n, out);
+  return launch_status();
+}
+
+}  // extern "C"

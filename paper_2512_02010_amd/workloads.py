@@ -194,7 +194,7 @@ def adversarial(kind: str, rows: int = 32, cols: int = 64) -> torch.Tensor:
         x = mids[idx]
         x[:, ::16] = 6.0
     elif kind == "bf16_small":
-        x = _normal((rows, cols), g) * 1.0e-30
+        x = _normal((rows, cols), g) * 1.0e-24
     elif kind == "bf16_large":
         x = _normal((rows, cols), g) * 1.0e30
     else:

@@ -1,0 +1,229 @@
+"""GPU: the HIP library against the CPU oracle, element by element, through the C ABI.
+
+Bar: codes, scale bytes, per-block 4-vs-6 choices and the tensor scale are bit-exact;
+dequantized / fake-quantized BF16 values are identical to 0 ULP (compared as bit
+patterns, so the sign of zero counts too)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2512_02010_amd import binding as B
+from paper_2512_02010_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+SR_SEED, RHT_SEED = wl.C5_SR_SEED, wl.C5_RHT_SEED
+
+
+def _log(msg):
+    print(msg, flush=True)
+
+
+def _np(t):
+    return None if t is None else t.cpu().numpy()
+
+
+def _bits(t):
+    return t.cpu().view(torch.int16).numpy().view(np.uint16)
+
+
+def _alpha_bits(a):
+    return np.array([a], np.float32).view(np.uint32)[0]
+
+
+def check_case(x: torch.Tensor, layout=B.ROWWISE, rounding=B.RTN, select=B.SEL_46_MSE, rht=0,
+               fp8_max=256.0, alpha_value=None, tag=""):
+    """Run tensor_scale -> quantize -> dequantize -> fake_quant on the GPU and compare every
+    output with the oracle on the same bits."""
+    rows, cols = x.shape
+    _log(f"case {tag} shape={rows}x{cols} layout={layout} rounding={rounding} select={select} "
+         f"rht={rht} fp8_max={fp8_max}")
+    xb = wl.bf16_bits(x)
+    xd = x.cuda()
+    kw = dict(rounding=rounding, select=select, rht=rht, sr_seed=SR_SEED, rht_seed=RHT_SEED)
+    layouts = [l for l in (B.ROWWISE, B.COLWISE) if layout & l]
+
+    # tensor scale (one orientation at a time; without the transform both agree)
+    alphas = {}
+    for l in layouts:
+        a_ref = ref.tensor_scale(xb, layout=l, rht=rht, rht_seed=RHT_SEED, fp8_max=fp8_max)
+        a_gpu = B.nvfp4_46_tensor_scale(xd, layout=l, rht=rht, rht_seed=RHT_SEED, fp8_max=fp8_max)
+        assert _alpha_bits(a_gpu.item()) == _alpha_bits(a_ref), (tag, l, a_gpu.item(), a_ref)
+        alphas[l] = a_gpu
+    if alpha_value is not None:
+        alphas = {l: torch.tensor([alpha_value], dtype=torch.float32, device="cuda") for l in layouts}
+    alpha = alphas[layouts[0]]
+    a_host = float(alpha.item())
+    if len(layouts) == 2:
+        assert _alpha_bits(alphas[B.ROWWISE].item()) == _alpha_bits(alphas[B.COLWISE].item())
+
+    out = B.nvfp4_46_quantize(xd, alpha, layout=layout, fp8_max=fp8_max, **kw)
+    torch.cuda.synchronize()
+    for l in layouts:
+        sfx = "row" if l == B.ROWWISE else "col"
+        c_ref, s_ref, f_ref, d_ref = ref.quantize(xb, a_host, layout=l, want_deq=True, **kw)
+        for name, want in (("scales", s_ref), ("choice", f_ref), ("codes", c_ref)):
+            got = _np(out[f"{name}_{sfx}"])
+            if not np.array_equal(got, want):
+                bad = np.argwhere(got != want)
+                raise AssertionError(f"{tag}: {name}_{sfx} differs at {len(bad)} places, first "
+                                     f"{bad[:4].tolist()} gpu {got[tuple(bad[0])]} "
+                                     f"oracle {want[tuple(bad[0])]}")
+        deq = B.nvfp4_46_dequantize(out[f"codes_{sfx}"], out[f"scales_{sfx}"], alpha, rows, cols,
+                                    layout=l)
+        assert np.array_equal(_bits(deq), d_ref), f"{tag}: dequantize_{sfx}"
+        assert np.array_equal(ref.dequantize(c_ref, s_ref, a_host, rows, cols, layout=l), d_ref)
+        fq = B.nvfp4_46_fake_quant(xd, alpha, layout=l, fp8_max=fp8_max, **kw)
+        assert np.array_equal(_bits(fq), d_ref), f"{tag}: fake_quant_{sfx}"
+    return out
+
+
+# ------------------------------------------------------------------ small, many options
+
+SHAPES_ROW = [(16, 16), (48, 176), (144, 272), (1, 4096), (257, 48)]
+SHAPES_COL = [(16, 8), (48, 176), (144, 264), (272, 136), (4096, 8), (128, 128)]
+
+
+@pytest.mark.parametrize("shape", SHAPES_ROW)
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c5"])
+def test_rowwise_rtn_small(name, shape):
+    check_case(wl.make(name, *shape), tag=f"{name}-row")
+
+
+@pytest.mark.parametrize("shape", SHAPES_COL)
+@pytest.mark.parametrize("name", ["c1", "c3", "c4"])
+def test_columnwise_rtn_small(name, shape):
+    check_case(wl.make(name, *shape), layout=B.COLWISE, tag=f"{name}-col")
+
+
+@pytest.mark.parametrize("shape", [(16, 16), (48, 176), (144, 272), (256, 384)])
+def test_both_layouts_one_pass_small(shape):
+    check_case(wl.make("c4", *shape), layout=B.BOTH, tag="c4-both")
+
+
+@pytest.mark.parametrize("layout", [B.ROWWISE, B.COLWISE])
+@pytest.mark.parametrize("select", [B.SEL_46_MSE, B.SEL_FORCE6, B.SEL_FORCE4])
+@pytest.mark.parametrize("rounding", [B.RTN, B.SR])
+@pytest.mark.parametrize("rht", [0, 1])
+def test_option_matrix(layout, select, rounding, rht):
+    check_case(wl.make("c5", 160, 304), layout=layout, rounding=rounding, select=select, rht=rht,
+               tag="c5-matrix")
+
+
+@pytest.mark.parametrize("rounding", [B.RTN, B.SR])
+def test_both_layouts_with_sr(rounding):
+    check_case(wl.make("c3", 144, 272), layout=B.BOTH, rounding=rounding, tag="c3-both")
+
+
+@pytest.mark.parametrize("name", ["c1", "c2"])
+def test_standard_tensor_scale_448(name):
+    # with 448 in Eq. (1) the M=4 scale of the block that holds the maximum saturates
+    check_case(wl.make(name, 64, 256), fp8_max=448.0, tag=f"{name}-448")
+    check_case(wl.make(name, 64, 256), fp8_max=448.0, select=B.SEL_FORCE4, tag=f"{name}-448-f4")
+
+
+@pytest.mark.parametrize("kind", wl.ADVERSARIAL_KINDS)
+@pytest.mark.parametrize("layout", [B.ROWWISE, B.COLWISE, B.BOTH])
+def test_adversarial_tensors(kind, layout):
+    check_case(wl.adversarial(kind), layout=layout, tag=f"adv-{kind}")
+
+
+def test_adversarial_with_sr_and_rht():
+    for kind in wl.ADVERSARIAL_KINDS:
+        check_case(wl.adversarial(kind), rounding=B.SR, rht=1, tag=f"adv-{kind}-sr-rht")
+
+
+def test_caller_supplied_alpha_replays_table3():
+    # Table 3's blocks with the tensor scale written as 1: [10,20,30,40] -> 4, [15,30,120,180] -> 6
+    x = torch.zeros((16, 32), dtype=torch.float32)
+    x[0, 0:4] = torch.tensor([10.0, 20.0, 30.0, 40.0])
+    x[0, 16:20] = torch.tensor([15.0, 30.0, 120.0, 180.0])
+    out = check_case(x.to(torch.bfloat16), alpha_value=1.0, tag="table3")
+    assert _np(out["choice_row"])[0].tolist() == [1, 0]
+    assert _np(out["scales_row"])[0].tolist() == [ref.e4m3_encode(10.0), ref.e4m3_encode(30.0)]
+    assert _np(out["codes_row"])[0, :2].tolist() == [0x42, 0x65]       # [1,2,3,4]
+    assert _np(out["codes_row"])[0, 8:10].tolist() == [0x21, 0x76]     # [.5,1,4,6]
+
+
+def test_exact_error_ties_keep_six():
+    # every block is exactly representable under both scalings -> E4 == E6 == 0 -> 6
+    x = wl.adversarial("grid_exact")
+    out = check_case(x, alpha_value=0.25 / 8, tag="ties")
+    assert int(_np(out["choice_row"]).sum()) == 0
+
+
+def test_optional_choice_and_preallocated_outputs():
+    x = wl.make("c1", 64, 256)
+    xd = x.cuda()
+    alpha = B.nvfp4_46_tensor_scale(xd)
+    full = B.nvfp4_46_quantize(xd, alpha, layout=B.BOTH)
+    lean = B.nvfp4_46_quantize(xd, alpha, layout=B.BOTH, want_choice=False)
+    assert lean["choice_row"] is None and lean["choice_col"] is None
+    for k in ("codes_row", "scales_row", "codes_col", "scales_col"):
+        assert torch.equal(full[k], lean[k])
+    again = B.nvfp4_46_quantize(xd, alpha, layout=B.BOTH, out=full)      # in place, same result
+    for k in ("codes_row", "scales_row", "codes_col", "scales_col"):
+        assert torch.equal(again[k], lean[k])
+
+
+def test_runs_on_a_side_stream_and_is_deterministic():
+    x = wl.make("c3", 512, 1024)
+    xd = x.cuda()
+    s = torch.cuda.Stream()
+    base = B.nvfp4_46_quantize(xd, B.nvfp4_46_tensor_scale(xd))
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        alpha = B.nvfp4_46_tensor_scale(xd, stream=s)
+        outs = [B.nvfp4_46_quantize(xd, alpha, stream=s) for _ in range(3)]
+    s.synchronize()
+    for o in outs:
+        for k in ("codes_row", "scales_row", "choice_row"):
+            assert torch.equal(o[k], base[k])
+
+
+def test_gpu_error_paths_enqueue_nothing():
+    x = wl.make("c1", 32, 64).cuda()
+    alpha = torch.ones(1, dtype=torch.float32, device="cuda")
+    out = B.alloc_outputs(32, 64, B.ROWWISE, x.device)
+    out["codes_row"].fill_(0xAB)
+    p = B.make_params(32, 64, select=7)
+    rc = B.quantize_raw(x, p, alpha, out["codes_row"], out["scales_row"], None, None, None, None)
+    torch.cuda.synchronize()
+    assert rc == 4 and bool((out["codes_row"] == 0xAB).all())
+    with pytest.raises(B.Nvfp4Error):
+        B.nvfp4_46_fake_quant(x, alpha, layout=B.BOTH)
+
+
+# ------------------------------------------------------------------ the five workloads, full size
+
+def test_workload_c1_full():
+    check_case(wl.make("c1"), tag="c1-full")
+
+
+def test_workload_c2_full_rowwise_rtn_and_mse():
+    x = wl.make("c2")
+    out = check_case(x, tag="c2-full")
+    frac4 = float(_np(out["choice_row"]).mean())
+    _log(f"c2: fraction of blocks scaled to 4 = {frac4:.4f}")
+    assert 0.05 < frac4 < 0.7
+    # 4/6 never has a larger tensor MSE than scale-to-6-only at the same alpha
+    xd = x.cuda()
+    alpha = B.nvfp4_46_tensor_scale(xd)
+    xf = xd.double()
+    mse46 = float(((B.nvfp4_46_fake_quant(xd, alpha).double() - xf) ** 2).mean())
+    mse6 = float(((B.nvfp4_46_fake_quant(xd, alpha, select=B.SEL_FORCE6).double() - xf) ** 2).mean())
+    _log(f"c2: MSE 4/6 = {mse46:.6e}, MSE scale-to-6 = {mse6:.6e}, ratio {mse46 / mse6:.4f}")
+    assert mse46 <= mse6
+
+
+def test_workload_c3_full_fake_quant():
+    check_case(wl.make("c3"), tag="c3-full")
+
+
+def test_workload_c4_full_both_layouts():
+    check_case(wl.make("c4"), layout=B.BOTH, tag="c4-full")
+
+
+def test_workload_c5_full_rht_sr():
+    check_case(wl.make("c5"), rounding=B.SR, rht=1, tag="c5-full")
