@@ -44,6 +44,10 @@ def parse():
     ap.add_argument("--cols", type=int, default=8192)
     ap.add_argument("--buffers", type=int, default=4, help="independent buffer sets rotated over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--counter-pass", action="store_true",
+                    help="launch a calibration copy and each kernel of the step a few times and "
+                         "exit (for `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE -- python3 bench.py "
+                         "--counter-pass`); prints no benchmark line")
     return ap.parse_args()
 
 
@@ -128,6 +132,17 @@ def main():
     x_host = wl.make("c2", rows, cols)
     sets = [BufferSet(x_host) for _ in range(max(1, args.buffers))]
     torch.cuda.synchronize()
+
+    if args.counter_pass:
+        # a plain copy of known size (rows*cols*2 bytes read, the same written) calibrates
+        # the byte counters; then every kernel of the step runs on rotating buffer sets
+        for i in range(3):
+            sets[i % len(sets)].deq.copy_(sets[(i + 1) % len(sets)].x)
+        for i in range(6):
+            step(sets[i % len(sets)])
+        torch.cuda.synchronize()
+        print("counter pass done: 3 copies of %d bytes, 6 steps" % (n * 2))
+        return
 
     for i in range(args.warmup):
         step(sets[i % len(sets)])

@@ -19,13 +19,32 @@ struct ScaleTable {
   float2 e[128];
 };
 
-NV_DEV void build_scale_table(ScaleTable &tab, float alpha) {
+// Per-tensor constants of Eq. (2): the denominators alpha*6 and alpha*4 and their
+// reciprocals (each one IEEE operation).
+struct ScaleConsts {
+  float c6, c4, rc6, rc4;
+};
+
+// Fills the table (entry 127, which is no scale byte, carries the two reciprocals
+// of ScaleConsts) and returns the constants.  Ends with a barrier.
+NV_DEV ScaleConsts build_scale_table(ScaleTable &tab, float alpha) {
+  ScaleConsts k;
+  k.c6 = alpha * 6.0f;
+  k.c4 = alpha * 4.0f;
   for (uint32_t s = threadIdx.x; s < 128u; s += blockDim.x) {
-    float dec = (s < 127u) ? e4m3_decode_sw(s) * alpha : 0.0f;
-    float enc = (dec == 0.0f) ? 0.0f : 1.0f / dec;
-    tab.e[s] = make_float2(dec, enc);
+    if (s < 127u) {
+      float dec = e4m3_decode_sw(s) * alpha;
+      float enc = (dec == 0.0f) ? 0.0f : 1.0f / dec;
+      tab.e[s] = make_float2(dec, enc);
+    } else {
+      tab.e[s] = make_float2(1.0f / k.c6, 1.0f / k.c4);
+    }
   }
   __syncthreads();
+  const float2 r = tab.e[127];
+  k.rc6 = r.x;
+  k.rc4 = r.y;
+  return k;
 }
 
 // The packed FP4 conversions take the destination / source byte as an immediate.
@@ -79,35 +98,48 @@ NV_DEV float candidate(const float (&v)[16], const float (&u)[16], float dec, fl
   float e[16];
   uint32_t c[2] = {0u, 0u};
 #pragma unroll
-  for (int i = 0; i < 16; i += 2) {
-    float y0 = v[i] * enc, y1 = v[i + 1] * enc;
-    float g0, g1;
-    if (ROUNDING == kSR) {
-      g0 = e2m1_sr_value(y0, u[i]);
-      g1 = e2m1_sr_value(y1, u[i + 1]);
-      c[i >> 3] |= (e2m1_code_of_grid_value(g0) | (e2m1_code_of_grid_value(g1) << 4))
-                   << (4 * (i & 7));
-    } else {
+  for (int h = 0; h < 2; ++h) {
+    float g[8];
 #if NVFP4_46_HW_FP4
-      // v_cvt_scalef32_pk_fp4_f32 writes byte (i&7)/2 of the word: first source in
-      // the low nibble; v_cvt_scalef32_pk_f32_fp4 reads the same byte back.
-      c[i >> 3] = hw_pk_fp4_sel(c[i >> 3], y0, y1, (i & 7) >> 1);
-      f32x2 g = hw_pk_f32_fp4_sel(c[i >> 3], (i & 7) >> 1);
-      g0 = g.x;
-      g1 = g.y;
-#else
-      float r0, r1;
-      uint32_t k0 = e2m1_rtn_mag_sw(fminf(fabsf(y0), 6.0f), r0) | ((f2u(y0) >> 28) & 8u);
-      uint32_t k1 = e2m1_rtn_mag_sw(fminf(fabsf(y1), 6.0f), r1) | ((f2u(y1) >> 28) & 8u);
-      g0 = u2f(f2u(r0) | (f2u(y0) & 0x80000000u));
-      g1 = u2f(f2u(r1) | (f2u(y1) & 0x80000000u));
-      c[i >> 3] |= (k0 | (k1 << 4)) << (4 * (i & 7));
+    if (ROUNDING == kRTN) {
+      // v_cvt_scalef32_pk_fp4_f32 fills byte j of the word (first source in the low
+      // nibble); the word is complete before v_cvt_scalef32_pk_f32_fp4 reads the bytes
+      // back, so no partial copies of it have to be kept.
+      uint32_t w = 0u;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        w = hw_pk_fp4_sel(w, v[8 * h + 2 * j] * enc, v[8 * h + 2 * j + 1] * enc, j);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        f32x2 p = hw_pk_f32_fp4_sel(w, j);
+        g[2 * j] = p.x;
+        g[2 * j + 1] = p.y;
+      }
+      c[h] = w;
+    } else
 #endif
+    {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float y = v[8 * h + j] * enc;
+        uint32_t k;
+        if (ROUNDING == kSR) {
+          g[j] = e2m1_sr_value(y, u[8 * h + j]);
+          k = e2m1_code_of_grid_value(g[j]);
+        } else {
+          float r;
+          k = e2m1_rtn_mag_sw(fminf(fabsf(y), 6.0f), r) | ((f2u(y) >> 28) & 8u);
+          g[j] = u2f(f2u(r) | (f2u(y) & 0x80000000u));
+        }
+        c[h] |= k << (4 * j);
+      }
     }
-    float D0 = g0 * dec, D1 = g1 * dec;
-    float d0 = D0 - v[i], d1 = D1 - v[i + 1];
-    e[i] = d0 * d0;
-    e[i + 1] = d1 * d1;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float D = g[j] * dec;
+      const float d = D - v[8 * h + j];
+      e[8 * h + j] = d * d;
+    }
   }
   lo = c[0];
   hi = c[1];
@@ -121,27 +153,61 @@ struct BlockResult {
   float dec;         // value(scale) * alpha, for dequantizing the chosen codes
 };
 
-// The whole per-block procedure.  c6 = alpha*6 and c4 = alpha*4 are the
-// denominators of Eq. (2).
+// True when the E4M3 byte of q = fl(b * fl(1/c)) might differ from the byte of the
+// correctly rounded quotient fl(b / c).  q is within 3.01 * 2^-24 (relative) of that
+// quotient, and the byte is a monotone step function of its argument, so the two can
+// differ only if a rounding boundary lies within about 3 ulp of q:
+//   - in the normal E4M3 range the boundaries are the fp32 values whose low 20
+//     mantissa bits are 0x80000; anything within 16 ulp of one is reported;
+//   - in the subnormal E4M3 range (below 2^-6) the boundaries have no fixed bit
+//     position, so every q in [2^-12, 2^-6) is reported; below 2^-11 both round to 0.
+// Values from 448 up all saturate to the same byte, so false alarms there are harmless.
+NV_DEV bool scale_byte_at_risk(float q) {
+  const uint32_t bits = f2u(q);
+  const bool near_midpoint = ((bits & 0xfffffu) - 0x7fff0u) <= 32u;
+  const bool subnormal_range = (bits - 0x39800000u) < (0x3c800000u - 0x39800000u);
+  return near_midpoint | subnormal_range;
+}
+
+// The whole per-block procedure (Table 3 lines 1-14).
 template <int ROUNDING, int SELECT>
-NV_DEV BlockResult quantize_block(const float (&v)[16], const float (&u)[16], float c6, float c4,
-                                  const ScaleTable &tab) {
+NV_DEV BlockResult quantize_block(const float (&v)[16], const float (&u)[16],
+                                  const ScaleConsts &k, const ScaleTable &tab) {
   float b = 0.0f;
 #pragma unroll
   for (int i = 0; i < 16; i += 2) b = fmaxf(fmaxf(b, fabsf(v[i])), fabsf(v[i + 1]));
 
+  // Eq. (2): S_M = e4m3(b / (alpha*M)).  The quotient is first approximated by one
+  // multiplication; the exact division runs only for the rare block whose byte could
+  // depend on the difference (so the result is always that of the division).
+  uint32_t S6 = 0u, S4 = 0u;
+  const float q6 = b * k.rc6, q4 = b * k.rc4;
+  bool risk = false;
+  if (SELECT != kSelForce4) {
+    S6 = e4m3_encode(q6);
+    risk |= scale_byte_at_risk(q6);
+  }
+  if (SELECT != kSelForce6) {
+    S4 = e4m3_encode(q4);
+    risk |= scale_byte_at_risk(q4);
+  }
+  if (risk) {
+    if (SELECT != kSelForce4) S6 = e4m3_encode(b / k.c6);
+    if (SELECT != kSelForce6) S4 = e4m3_encode(b / k.c4);
+  }
+
   BlockResult r6{}, r4{};
   float E6 = 0.0f, E4 = 0.0f;
   if (SELECT != kSelForce4) {
-    r6.scale = e4m3_encode(b / c6);
-    float2 t = tab.e[r6.scale];
+    float2 t = tab.e[S6];
+    r6.scale = S6;
     r6.dec = t.x;
     r6.four = 0u;
     E6 = candidate<ROUNDING>(v, u, t.x, t.y, r6.lo, r6.hi);
   }
   if (SELECT != kSelForce6) {
-    r4.scale = e4m3_encode(b / c4);
-    float2 t = tab.e[r4.scale];
+    float2 t = tab.e[S4];
+    r4.scale = S4;
     r4.dec = t.x;
     r4.four = 1u;
     E4 = candidate<ROUNDING>(v, u, t.x, t.y, r4.lo, r4.hi);

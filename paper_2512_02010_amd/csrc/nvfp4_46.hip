@@ -25,6 +25,11 @@ namespace nvfp4_46 {
 constexpr int kThreads = 256;
 enum : int { kOutCodes = 0, kOutFake = 1, kOutAmax = 2 };
 
+// workgroups per compute unit launched by the rowwise kernel (it strides over the tensor)
+#ifndef NVFP4_46_FLAT_WG_PER_CU
+#define NVFP4_46_FLAT_WG_PER_CU 8
+#endif
+
 NV_DEV void unpack16(const uint4 &w0, const uint4 &w1, float (&v)[16]) {
   const uint32_t w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
 #pragma unroll
@@ -40,11 +45,22 @@ NV_DEV float wave_max(float m) {
   return m;
 }
 
-// Largest magnitude of a non-negative-float bit pattern set: unsigned order
-// equals value order, so an integer atomic max is exact and order-free.
+// Fold a workgroup's maximum magnitude into the global one.  Bit patterns of
+// non-negative floats order like the values, so an integer atomic max is exact
+// and order-free.  All atomics hit one address and serialise in L2, hence one
+// per workgroup at most, and none when a plain read already shows a value that
+// is at least as large (the value only ever grows).
 NV_DEV void publish_amax(float m, uint32_t *amax_bits) {
+  __shared__ float wave_part[kThreads / 64];
   m = wave_max(m);
-  if ((threadIdx.x & 63) == 0) atomicMax(amax_bits, f2u(m));
+  if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 1; w < kThreads / 64; ++w) m = fmaxf(m, wave_part[w]);
+    const uint32_t bits = f2u(m);
+    if (bits > __atomic_load_n(amax_bits, __ATOMIC_RELAXED)) atomicMax(amax_bits, bits);
+  }
 }
 
 // ------------------------------------------------------------ tensor scale
@@ -86,28 +102,29 @@ __global__ __launch_bounds__(kThreads) void k_flat(
     uint32_t *amax_bits, int64_t nblocks, uint32_t nb_per_row, uint64_t sr_seed,
     uint64_t rht_seed) {
   __shared__ ScaleTable tab;
-  float c6 = 0.0f, c4 = 0.0f;
-  if (OUT != kOutAmax) {
-    const float alpha = *alpha_p;
-    build_scale_table(tab, alpha);
-    c6 = alpha * 6.0f;
-    c4 = alpha * 4.0f;
-  }
-  const int64_t stride = (int64_t)gridDim.x * kThreads;
-  int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  uint32_t B = 0, B_step = 0;
-  if (RHT) {
-    B = (uint32_t)(k % nb_per_row);
-    B_step = (uint32_t)(stride % nb_per_row);
-  }
+  ScaleConsts sc{};
+  if (OUT != kOutAmax) sc = build_scale_table(tab, *alpha_p);
+  // The tensor is cut into rounds of 256 consecutive blocks; workgroup w takes rounds
+  // w, w + gridDim, ...  Everything that depends on the round only (base pointers, the
+  // number of live lanes) is wave-uniform and stays on the scalar unit; a lane adds its
+  // own constant offset.
+  const uint32_t tid = threadIdx.x;
+  const uint32_t rounds = (uint32_t)((nblocks + kThreads - 1) / kThreads);
+  const uint32_t tail = (uint32_t)(nblocks - (int64_t)(rounds - 1) * kThreads);  // 1..256
+  uint32_t B_lane = 0;
+  if (RHT) B_lane = tid % nb_per_row;
   float amax = 0.0f;
-  for (; k < nblocks; k += stride) {
+  for (uint32_t r = blockIdx.x; r < rounds; r += gridDim.x) {
+    const uint32_t live = (r == rounds - 1) ? tail : (uint32_t)kThreads;
+    if (tid >= live) continue;   // only in the last round of a ragged tensor
+    const int64_t base = (int64_t)r * kThreads;
+    const uint4 *xb = x + 2 * base;
     float v[16], u[16];
-    unpack16(x[2 * k], x[2 * k + 1], v);
+    unpack16(xb[2 * tid], xb[2 * tid + 1], v);
     if (RHT) {
-      rht16(v, rht_sign_word(rht_seed, B));
-      B += B_step;
+      uint32_t B = (uint32_t)(base % nb_per_row) + B_lane;
       if (B >= nb_per_row) B -= nb_per_row;
+      rht16(v, rht_sign_word(rht_seed, B));
     }
     if (OUT == kOutAmax) {
 #pragma unroll
@@ -115,22 +132,24 @@ __global__ __launch_bounds__(kThreads) void k_flat(
       continue;
     }
     if (ROUNDING == kSR) {
+      const uint64_t q0 = ((uint64_t)base + tid) * 4u;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) sr_uniforms4(sr_seed, (uint64_t)k * 4u + j, &u[4 * j]);
+      for (int j = 0; j < 4; ++j) sr_uniforms4(sr_seed, q0 + j, &u[4 * j]);
     }
-    BlockResult r = quantize_block<ROUNDING, SELECT>(v, u, c6, c4, tab);
+    const BlockResult res = quantize_block<ROUNDING, SELECT>(v, u, sc, tab);
     if (OUT == kOutCodes) {
-      codes[k] = make_uint2(r.lo, r.hi);
-      scales[k] = (uint8_t)r.scale;
-      if (choice) choice[k] = (uint8_t)r.four;
+      (codes + base)[tid] = make_uint2(res.lo, res.hi);
+      (scales + base)[tid] = (uint8_t)res.scale;
+      if (choice) (choice + base)[tid] = (uint8_t)res.four;
     } else {
       float D0[8], D1[8];
-      dequant8(r.lo, r.dec, D0);
-      dequant8(r.hi, r.dec, D1);
-      out_bf16[2 * k] = make_uint4(pack_bf16x2(D0[0], D0[1]), pack_bf16x2(D0[2], D0[3]),
-                                   pack_bf16x2(D0[4], D0[5]), pack_bf16x2(D0[6], D0[7]));
-      out_bf16[2 * k + 1] = make_uint4(pack_bf16x2(D1[0], D1[1]), pack_bf16x2(D1[2], D1[3]),
-                                       pack_bf16x2(D1[4], D1[5]), pack_bf16x2(D1[6], D1[7]));
+      dequant8(res.lo, res.dec, D0);
+      dequant8(res.hi, res.dec, D1);
+      uint4 *ob = out_bf16 + 2 * base;
+      ob[2 * tid] = make_uint4(pack_bf16x2(D0[0], D0[1]), pack_bf16x2(D0[2], D0[3]),
+                               pack_bf16x2(D0[4], D0[5]), pack_bf16x2(D0[6], D0[7]));
+      ob[2 * tid + 1] = make_uint4(pack_bf16x2(D1[0], D1[1]), pack_bf16x2(D1[2], D1[3]),
+                                   pack_bf16x2(D1[4], D1[5]), pack_bf16x2(D1[6], D1[7]));
     }
   }
   if (OUT == kOutAmax) publish_amax(amax, amax_bits);
@@ -194,13 +213,8 @@ __global__ __launch_bounds__(kThreads) void k_tile(
   const int64_t r0 = tcd.r0, c0 = tcd.c0;
   const int t = threadIdx.x;
 
-  float c6 = 0.0f, c4 = 0.0f;
-  if (OUT != kOutAmax) {
-    const float alpha = *alpha_p;
-    build_scale_table(tab, alpha);
-    c6 = alpha * 6.0f;
-    c4 = alpha * 4.0f;
-  }
+  ScaleConsts sc{};
+  if (OUT != kOutAmax) sc = build_scale_table(tab, *alpha_p);
 
   // ---- phase 1: global -> LDS (and the rowwise outputs on the way)
   {
@@ -240,7 +254,7 @@ __global__ __launch_bounds__(kThreads) void k_tile(
 #pragma unroll
             for (int q = 0; q < 4; ++q) sr_uniforms4(sr_seed, (uint64_t)k * 4u + q, &u[4 * q]);
           }
-          BlockResult r = quantize_block<ROUNDING, SELECT>(v, u, c6, c4, tab);
+          BlockResult r = quantize_block<ROUNDING, SELECT>(v, u, sc, tab);
           reinterpret_cast<uint2 *>(codes_row)[k] = make_uint2(r.lo, r.hi);
           scales_row[k] = (uint8_t)r.scale;
           if (choice_row) choice_row[k] = (uint8_t)r.four;
@@ -290,8 +304,8 @@ __global__ __launch_bounds__(kThreads) void k_tile(
         ub[i] = (g & 2u) ? uu[3] : uu[1];
       }
     }
-    BlockResult ra = quantize_block<ROUNDING, SELECT>(va, ua, c6, c4, tab);
-    BlockResult rbk = quantize_block<ROUNDING, SELECT>(vb, ub, c6, c4, tab);
+    BlockResult ra = quantize_block<ROUNDING, SELECT>(va, ua, sc, tab);
+    BlockResult rbk = quantize_block<ROUNDING, SELECT>(vb, ub, sc, tab);
     if (OUT == kOutCodes) {
       const int ia = (2 * cp) * 8 + rb, ib = (2 * cp + 1) * 8 + rb;
       stage_codes[ia] = make_uint2(ra.lo, ra.hi);
@@ -485,7 +499,7 @@ struct FlatArgs {
 
 template <int ROUNDING, int SELECT, bool RHT, int OUT>
 static void launch_flat(const FlatArgs &a) {
-  const int grid = grid_for(a.nblocks, 8);
+  const int grid = grid_for(a.nblocks, NVFP4_46_FLAT_WG_PER_CU);
   hipLaunchKernelGGL((k_flat<ROUNDING, SELECT, RHT, OUT>), dim3(grid), dim3(kThreads), 0, a.stream,
                      a.x, a.alpha, a.codes, a.scales, a.choice, a.out, a.amax, a.nblocks,
                      a.nb_per_row, a.sr_seed, a.rht_seed);
