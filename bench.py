@@ -60,21 +60,23 @@ class BufferSet:
         self.out = B.alloc_outputs(rows, cols, B.ROWWISE, "cuda", want_choice=False)
         self.deq = torch.empty((rows, cols), dtype=torch.bfloat16, device="cuda")
         self.params = B.make_params(rows, cols)
+        self.stream = torch.cuda.current_stream()
 
 
 def step(bs: BufferSet, ev=None):
     """tensor_scale -> quantize -> dequantize, all on the current stream."""
+    st = bs.stream
     if ev:
         ev[0].record()
-    rc = B.tensor_scale_raw(bs.x, bs.params, bs.alpha)
+    rc = B.tensor_scale_raw(bs.x, bs.params, bs.alpha, st)
     if ev:
         ev[1].record()
     rc |= B.quantize_raw(bs.x, bs.params, bs.alpha, bs.out["codes_row"], bs.out["scales_row"], None,
-                         None, None, None)
+                         None, None, None, st)
     if ev:
         ev[2].record()
     rc |= B.dequantize_raw(bs.out["codes_row"], bs.out["scales_row"], bs.alpha, bs.rows, bs.cols,
-                           B.ROWWISE, bs.deq)
+                           B.ROWWISE, bs.deq, st)
     if ev:
         ev[3].record()
     if rc:

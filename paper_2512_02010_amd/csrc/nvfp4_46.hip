@@ -26,9 +26,61 @@ constexpr int kThreads = 256;
 enum : int { kOutCodes = 0, kOutFake = 1, kOutAmax = 2 };
 
 // workgroups per compute unit launched by the rowwise kernel (it strides over the tensor)
+// the plain absolute-maximum pass: few, long-lived workgroups (each ends with a
+// serialising access to the one result word) with many loads in flight per lane
+#ifndef NVFP4_46_AMAX_UNROLL
+#define NVFP4_46_AMAX_UNROLL 8
+#endif
+#ifndef NVFP4_46_AMAX_WG_PER_CU
+#define NVFP4_46_AMAX_WG_PER_CU 1
+#endif
 #ifndef NVFP4_46_FLAT_WG_PER_CU
 #define NVFP4_46_FLAT_WG_PER_CU 8
 #endif
+
+// Streaming accesses: every input word is read once and every output byte written once,
+// so neither should displace anything in the caches (the `nt` forms of the memory
+// instructions); the knobs exist to measure that choice.
+#ifndef NVFP4_46_NT_LOAD
+#define NVFP4_46_NT_LOAD 0
+#endif
+#ifndef NVFP4_46_NT_STORE
+#define NVFP4_46_NT_STORE 1
+#endif
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+NV_DEV uint4 load_stream(const uint4 *p) {
+#if NVFP4_46_NT_LOAD
+  u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+#else
+  return *p;
+#endif
+}
+NV_DEV void store_stream(uint4 *p, const uint4 &v) {
+#if NVFP4_46_NT_STORE
+  u32x4 t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, reinterpret_cast<u32x4 *>(p));
+#else
+  *p = v;
+#endif
+}
+NV_DEV void store_stream(uint2 *p, const uint2 &v) {
+#if NVFP4_46_NT_STORE
+  u32x2 t = {v.x, v.y};
+  __builtin_nontemporal_store(t, reinterpret_cast<u32x2 *>(p));
+#else
+  *p = v;
+#endif
+}
+NV_DEV void store_stream(uint8_t *p, uint8_t v) {
+#if NVFP4_46_NT_STORE
+  __builtin_nontemporal_store(v, p);
+#else
+  *p = v;
+#endif
+}
 
 NV_DEV void unpack16(const uint4 &w0, const uint4 &w1, float (&v)[16]) {
   const uint32_t w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
@@ -75,20 +127,30 @@ __global__ void k_finish_alpha(float *alpha, float fp8_max) {
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 
-// max|x| without the transform: compare BF16 magnitudes as 15-bit integers.
+// max|x| without the transform: compare BF16 magnitudes as 15-bit integers.  Four
+// independent 128-bit loads per lane are in flight at a time.
 __global__ __launch_bounds__(kThreads) void k_amax_plain(const uint4 *__restrict__ x, int64_t n16,
                                                          uint32_t *amax_bits) {
   u16x2 acc = {0, 0};
-  const int64_t stride = (int64_t)gridDim.x * kThreads;
-  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += stride) {
-    uint4 w = x[i];
+  auto fold = [&](const uint4 &w) {
     const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       uint32_t m = ww[j] & 0x7fff7fffu;
       acc = __builtin_elementwise_max(acc, *reinterpret_cast<u16x2 *>(&m));
     }
+  };
+  constexpr int U = NVFP4_46_AMAX_UNROLL;
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  for (; i + (U - 1) * stride < n16; i += U * stride) {
+    uint4 w[U];
+#pragma unroll
+    for (int j = 0; j < U; ++j) w[j] = load_stream(x + i + j * stride);
+#pragma unroll
+    for (int j = 0; j < U; ++j) fold(w[j]);
   }
+  for (; i < n16; i += stride) fold(load_stream(x + i));
   uint32_t top = acc.x > acc.y ? acc.x : acc.y;
   publish_amax(u2f(top << 16), amax_bits);
 }
@@ -102,8 +164,10 @@ __global__ __launch_bounds__(kThreads) void k_flat(
     uint32_t *amax_bits, int64_t nblocks, uint32_t nb_per_row, uint64_t sr_seed,
     uint64_t rht_seed) {
   __shared__ ScaleTable tab;
-  ScaleConsts sc{};
-  if (OUT != kOutAmax) sc = build_scale_table(tab, *alpha_p);
+  // fake-quant only: a wave's 2 KiB of output is turned round in LDS so that each of its
+  // two store instructions writes 1 KiB of whole cache lines (streaming stores of half
+  // lines are slow), instead of every lane writing its own 32 bytes
+  __shared__ uint4 xpose[OUT == kOutFake ? 2 * kThreads : 1];
   // The tensor is cut into rounds of 256 consecutive blocks; workgroup w takes rounds
   // w, w + gridDim, ...  Everything that depends on the round only (base pointers, the
   // number of live lanes) is wave-uniform and stays on the scalar unit; a lane adds its
@@ -114,13 +178,16 @@ __global__ __launch_bounds__(kThreads) void k_flat(
   uint32_t B_lane = 0;
   if (RHT) B_lane = tid % nb_per_row;
   float amax = 0.0f;
-  for (uint32_t r = blockIdx.x; r < rounds; r += gridDim.x) {
-    const uint32_t live = (r == rounds - 1) ? tail : (uint32_t)kThreads;
-    if (tid >= live) continue;   // only in the last round of a ragged tensor
+  ScaleConsts sc{};
+
+  auto lanes_in_round = [&](uint32_t r) { return (r == rounds - 1) ? tail : (uint32_t)kThreads; };
+
+  // one block, already loaded as two 128-bit words; `live` = lanes of this round that
+  // hold a block (fewer than 256 only in the last round of a ragged tensor)
+  auto work = [&](uint32_t r, uint32_t live, const uint4 &w0, const uint4 &w1) {
     const int64_t base = (int64_t)r * kThreads;
-    const uint4 *xb = x + 2 * base;
     float v[16], u[16];
-    unpack16(xb[2 * tid], xb[2 * tid + 1], v);
+    unpack16(w0, w1, v);
     if (RHT) {
       uint32_t B = (uint32_t)(base % nb_per_row) + B_lane;
       if (B >= nb_per_row) B -= nb_per_row;
@@ -129,7 +196,7 @@ __global__ __launch_bounds__(kThreads) void k_flat(
     if (OUT == kOutAmax) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(v[i]));
-      continue;
+      return;
     }
     if (ROUNDING == kSR) {
       const uint64_t q0 = ((uint64_t)base + tid) * 4u;
@@ -138,19 +205,56 @@ __global__ __launch_bounds__(kThreads) void k_flat(
     }
     const BlockResult res = quantize_block<ROUNDING, SELECT>(v, u, sc, tab);
     if (OUT == kOutCodes) {
-      (codes + base)[tid] = make_uint2(res.lo, res.hi);
-      (scales + base)[tid] = (uint8_t)res.scale;
-      if (choice) (choice + base)[tid] = (uint8_t)res.four;
+      store_stream(codes + base + tid, make_uint2(res.lo, res.hi));
+      store_stream(scales + base + tid, (uint8_t)res.scale);
+      if (choice) store_stream(choice + base + tid, (uint8_t)res.four);
     } else {
       float D0[8], D1[8];
       dequant8(res.lo, res.dec, D0);
       dequant8(res.hi, res.dec, D1);
-      uint4 *ob = out_bf16 + 2 * base;
-      ob[2 * tid] = make_uint4(pack_bf16x2(D0[0], D0[1]), pack_bf16x2(D0[2], D0[3]),
-                               pack_bf16x2(D0[4], D0[5]), pack_bf16x2(D0[6], D0[7]));
-      ob[2 * tid + 1] = make_uint4(pack_bf16x2(D1[0], D1[1]), pack_bf16x2(D1[2], D1[3]),
-                                   pack_bf16x2(D1[4], D1[5]), pack_bf16x2(D1[6], D1[7]));
+      // lane l of a wave holds 16-byte pieces 2l and 2l+1 of the wave's output and
+      // stores pieces l and 64+l; LDS operations of one wave execute in order, so the
+      // reads below see the writes above without a barrier
+      const uint32_t wave0 = tid & ~63u, lane = tid & 63u;
+      uint4 *slot = xpose + 2 * wave0;
+      slot[2 * lane] = make_uint4(pack_bf16x2(D0[0], D0[1]), pack_bf16x2(D0[2], D0[3]),
+                                  pack_bf16x2(D0[4], D0[5]), pack_bf16x2(D0[6], D0[7]));
+      slot[2 * lane + 1] = make_uint4(pack_bf16x2(D1[0], D1[1]), pack_bf16x2(D1[2], D1[3]),
+                                      pack_bf16x2(D1[4], D1[5]), pack_bf16x2(D1[6], D1[7]));
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      uint4 *ob = out_bf16 + 2 * (base + wave0);
+      if (wave0 + (lane >> 1) < live) store_stream(ob + lane, slot[lane]);
+      if (wave0 + 32 + (lane >> 1) < live) store_stream(ob + 64 + lane, slot[64 + lane]);
     }
+  };
+
+  // The first round's loads go out before the scale table is built, so the table's
+  // divisions and barrier hide under the first memory latency instead of adding to it.
+  // In the fake-quant kernel lanes without a block still run (on zeros), because they
+  // store pieces of their neighbours' blocks; elsewhere they skip the round.
+  const uint32_t r0 = blockIdx.x;
+  const uint32_t live0 = r0 < rounds ? lanes_in_round(r0) : 0u;
+  uint4 p0 = make_uint4(0, 0, 0, 0), p1 = p0;
+  if (tid < live0) {
+    const uint4 *xb = x + 2 * ((int64_t)r0 * kThreads);
+    p0 = load_stream(xb + 2 * tid);
+    p1 = load_stream(xb + 2 * tid + 1);
+  }
+  if (OUT != kOutAmax) sc = build_scale_table(tab, *alpha_p);
+  if (OUT == kOutFake ? live0 != 0u : tid < live0) work(r0, live0, p0, p1);
+  for (uint32_t r = r0 + gridDim.x; r < rounds; r += gridDim.x) {
+    const uint32_t live = lanes_in_round(r);
+    uint4 w0 = make_uint4(0, 0, 0, 0), w1 = w0;
+    if (tid < live) {
+      const uint4 *xb = x + 2 * ((int64_t)r * kThreads);
+      w0 = load_stream(xb + 2 * tid);
+      w1 = load_stream(xb + 2 * tid + 1);
+    } else if (OUT != kOutFake) {
+      continue;
+    }
+    work(r, live, w0, w1);
   }
   if (OUT == kOutAmax) publish_amax(amax, amax_bits);
 }
@@ -166,8 +270,8 @@ __global__ __launch_bounds__(kThreads) void k_dequant_flat(const uint32_t *__res
     float dec = e4m3_decode_sw(scales[t >> 1]) * alpha;
     float D[8];
     dequant8(codes[t], dec, D);
-    out[t] = make_uint4(pack_bf16x2(D[0], D[1]), pack_bf16x2(D[2], D[3]), pack_bf16x2(D[4], D[5]),
-                        pack_bf16x2(D[6], D[7]));
+    store_stream(out + t, make_uint4(pack_bf16x2(D[0], D[1]), pack_bf16x2(D[2], D[3]),
+                                     pack_bf16x2(D[4], D[5]), pack_bf16x2(D[6], D[7])));
   }
 }
 
@@ -624,7 +728,7 @@ int nvfp4_46_tensor_scale(const void *x_bf16, const nvfp4_46_params *p, float *a
   const int64_t n = p->rows * p->cols;
   if (!p->rht) {
     const int64_t n16 = n / 8;  // 128-bit pieces (n is a multiple of 8 by the shape checks)
-    hipLaunchKernelGGL(k_amax_plain, dim3(grid_for(n16, 8)), dim3(kThreads), 0, s,
+    hipLaunchKernelGGL(k_amax_plain, dim3(grid_for(n16, NVFP4_46_AMAX_WG_PER_CU)), dim3(kThreads), 0, s,
                        static_cast<const uint4 *>(x_bf16), n16, amax);
   } else if (p->layout == NVFP4_ROWWISE) {
     FlatArgs a{static_cast<const uint4 *>(x_bf16), nullptr, nullptr, nullptr, nullptr, nullptr, amax,
