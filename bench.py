@@ -30,6 +30,14 @@ from paper_2512_02010_amd import binding as B  # noqa: E402
 from paper_2512_02010_amd import workloads as wl  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
+# plain (unpacked) fp32 VALU issue rate: 256 CUs x 64 lanes x 2.4 GHz, in lane-operations/s
+VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
+# VALU wave-instructions per block of 16 elements in the rowwise 4/6 kernel, from
+# rocprofv3 --pmc SQ_INSTS_VALU (profiles/c2_step_counters.txt): 16,532,464 per 4,194,304/64 wave-blocks
+VALU_INSTS_PER_BLOCK_46 = 16532464.0 / (4194304.0 / 64.0)
+# HBM bytes per element of the same kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled
+# by a plain copy's readings (same file): (65578.7 * 2.000 + 36885.6 * 1.000) KiB per 67,108,864
+HBM_TRAFFIC_PER_ELEM_46 = (65578.7 * 2.0 + 36885.6) * 1024.0 / 67108864.0
 BYTES_PER_ELEM_QUANT = 2.0 + 0.5 + 1.0 / 16.0        # read x, write codes, write scales
 BYTES_PER_ELEM_AMAX = 2.0
 BYTES_PER_ELEM_DEQUANT = 0.5 + 1.0 / 16.0 + 2.0
@@ -204,7 +212,19 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": quant_gbs / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": n * HBM_TRAFFIC_PER_ELEM_46,
+            "traffic_note": "bytes per launch from rocprofv3 FETCH_SIZE/WRITE_SIZE at this "
+                            "shape (profiles/c2_step_counters.txt), not re-measured in this run",
+        },
+        "roofline_alu": {
+            "bound": "alu",
+            "note": "the same kernel against plain fp32 VALU issue (packed fp32 is not used): "
+                    "lane-operations = wave-instructions per block (rocprofv3 SQ_INSTS_VALU) "
+                    "x blocks",
+            "achieved": VALU_INSTS_PER_BLOCK_46 * (n / 16.0) / (t_quant * 1e-3) / 1e12,
+            "peak": VALU_PEAK_TOPS,
+            "unit": "T lane-op/s",
+            "frac": VALU_INSTS_PER_BLOCK_46 * (n / 16.0) / (t_quant * 1e-3) / 1e12 / VALU_PEAK_TOPS,
         },
         "kernels_us": {
             "tensor_scale": t_scale * 1e3,

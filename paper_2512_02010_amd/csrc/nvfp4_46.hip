@@ -44,9 +44,14 @@ enum : int { kOutCodes = 0, kOutFake = 1, kOutAmax = 2 };
 #ifndef NVFP4_46_NT_LOAD
 #define NVFP4_46_NT_LOAD 0
 #endif
-#ifndef NVFP4_46_NT_STORE
-#define NVFP4_46_NT_STORE 1
+#ifndef NVFP4_46_NT_STORE_CODES
+#define NVFP4_46_NT_STORE_CODES 0
 #endif
+#ifndef NVFP4_46_NT_STORE_BF16
+#define NVFP4_46_NT_STORE_BF16 1
+#endif
+constexpr bool kNtCodes = NVFP4_46_NT_STORE_CODES != 0;   // codes / scales / choice bytes
+constexpr bool kNtBf16 = NVFP4_46_NT_STORE_BF16 != 0;     // dequantized BF16 tensors
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
@@ -58,28 +63,30 @@ NV_DEV uint4 load_stream(const uint4 *p) {
   return *p;
 #endif
 }
-NV_DEV void store_stream(uint4 *p, const uint4 &v) {
-#if NVFP4_46_NT_STORE
-  u32x4 t = {v.x, v.y, v.z, v.w};
-  __builtin_nontemporal_store(t, reinterpret_cast<u32x4 *>(p));
-#else
-  *p = v;
-#endif
+template <bool NT>
+NV_DEV void store_as(uint4 *p, const uint4 &v) {
+  if (NT) {
+    u32x4 t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<u32x4 *>(p));
+  } else {
+    *p = v;
+  }
 }
-NV_DEV void store_stream(uint2 *p, const uint2 &v) {
-#if NVFP4_46_NT_STORE
-  u32x2 t = {v.x, v.y};
-  __builtin_nontemporal_store(t, reinterpret_cast<u32x2 *>(p));
-#else
-  *p = v;
-#endif
+template <bool NT>
+NV_DEV void store_as(uint2 *p, const uint2 &v) {
+  if (NT) {
+    u32x2 t = {v.x, v.y};
+    __builtin_nontemporal_store(t, reinterpret_cast<u32x2 *>(p));
+  } else {
+    *p = v;
+  }
 }
-NV_DEV void store_stream(uint8_t *p, uint8_t v) {
-#if NVFP4_46_NT_STORE
-  __builtin_nontemporal_store(v, p);
-#else
-  *p = v;
-#endif
+template <bool NT>
+NV_DEV void store_as(uint8_t *p, uint8_t v) {
+  if (NT)
+    __builtin_nontemporal_store(v, p);
+  else
+    *p = v;
 }
 
 NV_DEV void unpack16(const uint4 &w0, const uint4 &w1, float (&v)[16]) {
@@ -205,9 +212,9 @@ __global__ __launch_bounds__(kThreads) void k_flat(
     }
     const BlockResult res = quantize_block<ROUNDING, SELECT>(v, u, sc, tab);
     if (OUT == kOutCodes) {
-      store_stream(codes + base + tid, make_uint2(res.lo, res.hi));
-      store_stream(scales + base + tid, (uint8_t)res.scale);
-      if (choice) store_stream(choice + base + tid, (uint8_t)res.four);
+      store_as<kNtCodes>(codes + base + tid, make_uint2(res.lo, res.hi));
+      store_as<kNtCodes>(scales + base + tid, (uint8_t)res.scale);
+      if (choice) store_as<kNtCodes>(choice + base + tid, (uint8_t)res.four);
     } else {
       float D0[8], D1[8];
       dequant8(res.lo, res.dec, D0);
@@ -225,8 +232,8 @@ __global__ __launch_bounds__(kThreads) void k_flat(
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       uint4 *ob = out_bf16 + 2 * (base + wave0);
-      if (wave0 + (lane >> 1) < live) store_stream(ob + lane, slot[lane]);
-      if (wave0 + 32 + (lane >> 1) < live) store_stream(ob + 64 + lane, slot[64 + lane]);
+      if (wave0 + (lane >> 1) < live) store_as<kNtBf16>(ob + lane, slot[lane]);
+      if (wave0 + 32 + (lane >> 1) < live) store_as<kNtBf16>(ob + 64 + lane, slot[64 + lane]);
     }
   };
 
@@ -270,8 +277,8 @@ __global__ __launch_bounds__(kThreads) void k_dequant_flat(const uint32_t *__res
     float dec = e4m3_decode_sw(scales[t >> 1]) * alpha;
     float D[8];
     dequant8(codes[t], dec, D);
-    store_stream(out + t, make_uint4(pack_bf16x2(D[0], D[1]), pack_bf16x2(D[2], D[3]),
-                                     pack_bf16x2(D[4], D[5]), pack_bf16x2(D[6], D[7])));
+    store_as<kNtBf16>(out + t, make_uint4(pack_bf16x2(D[0], D[1]), pack_bf16x2(D[2], D[3]),
+                                          pack_bf16x2(D[4], D[5]), pack_bf16x2(D[6], D[7])));
   }
 }
 
