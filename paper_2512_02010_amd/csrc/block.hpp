@@ -90,13 +90,31 @@ NV_DEV float error_tree(const float (&e)[16]) {
   return c[0] + c[1];
 }
 
-// Quantize the block with scale (dec, enc): codes (element i in nibble i of
-// lo for i < 8, of hi for i >= 8) and the block's squared error.
-template <int ROUNDING>
+// Grid values (sign included) of 8 codes packed in one word.
+NV_DEV void grid8(uint32_t codes, float (&g)[8]) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+#if NVFP4_46_HW_FP4
+    f32x2 p = hw_pk_f32_fp4_sel(codes, j);
+    g[2 * j] = p.x;
+    g[2 * j + 1] = p.y;
+#else
+    g[2 * j] = e2m1_decode_sw((codes >> (8 * j)) & 15u);
+    g[2 * j + 1] = e2m1_decode_sw((codes >> (8 * j + 4)) & 15u);
+#endif
+  }
+}
+
+// Quantize the block with scale (dec, enc): codes (element i in nibble i of lo for
+// i < 8, of hi for i >= 8).  Also returns a cheap estimate E' of the block's squared
+// error: d' = fma(g, dec, -v) and a running fma(d', d', E'), i.e. two instructions per
+// element where the defining sequence (product, difference, square, tree sum, each
+// rounded) takes four.  E' is only ever used through decide_four() below.
+template <int ROUNDING, bool WANT_ERROR>
 NV_DEV float candidate(const float (&v)[16], const float (&u)[16], float dec, float enc,
                        uint32_t &lo, uint32_t &hi) {
-  float e[16];
   uint32_t c[2] = {0u, 0u};
+  float acc[2] = {0.0f, 0.0f};
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     float g[8];
@@ -109,12 +127,7 @@ NV_DEV float candidate(const float (&v)[16], const float (&u)[16], float dec, fl
 #pragma unroll
       for (int j = 0; j < 4; ++j)
         w = hw_pk_fp4_sel(w, v[8 * h + 2 * j] * enc, v[8 * h + 2 * j + 1] * enc, j);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        f32x2 p = hw_pk_f32_fp4_sel(w, j);
-        g[2 * j] = p.x;
-        g[2 * j + 1] = p.y;
-      }
+      if (WANT_ERROR) grid8(w, g);
       c[h] = w;
     } else
 #endif
@@ -134,6 +147,27 @@ NV_DEV float candidate(const float (&v)[16], const float (&u)[16], float dec, fl
         c[h] |= k << (4 * j);
       }
     }
+    if (WANT_ERROR) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float d = __builtin_fmaf(g[j], dec, -v[8 * h + j]);
+        acc[j & 1] = __builtin_fmaf(d, d, acc[j & 1]);
+      }
+    }
+  }
+  lo = c[0];
+  hi = c[1];
+  return acc[0] + acc[1];
+}
+
+// The block's squared error exactly as it is defined (Table 3 lines 5-6 / 11-12 in fp32):
+// D = fl(g*dec), d = fl(D - v), e = fl(d*d), fixed summation tree.
+NV_DEV float exact_error(const float (&v)[16], uint32_t lo, uint32_t hi, float dec) {
+  float e[16];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    float g[8];
+    grid8(h ? hi : lo, g);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const float D = g[j] * dec;
@@ -141,9 +175,57 @@ NV_DEV float candidate(const float (&v)[16], const float (&u)[16], float dec, fl
       e[8 * h + j] = d * d;
     }
   }
-  lo = c[0];
-  hi = c[1];
   return error_tree(e);
+}
+
+// Table 3 line 13: is the defined error of the M=4 candidate strictly smaller than that
+// of the M=6 candidate?  Decided from the estimates whenever they differ by more than
+// they can be off, otherwise from the defined errors themselves, so the answer is always
+// the defined one.
+//
+// Bound used (u = 2^-24, S = sum of the exact real squares t_i^2, t_i = g_i*dec - v_i,
+// |g_i| <= 6, m = max(dec^2, S)):
+//   defined value E:  D_i carries a relative error u, d_i another, so d_i = t_i + eps_i
+//     with |eps_i| <= u(6 dec + |t_i|)(1+u); squaring and summing 16 terms through a
+//     4-level tree (and sum|t_i| <= 4 sqrt(S), dec sqrt(S) <= m) gives
+//     |E - S| <= 48.1 u m + 7.1 u S;
+//   estimate E':  one rounding in d', at most 9 more per term in the accumulation:
+//     |E' - S| <= 18.1 u S.
+// Hence |E - E'| <= 48.1 u m + 25.2 u S < tol := 64 u (max(dec^2, E') + E').  If
+// |E4' - E6'| > tol4 + tol6 the order of E4 and E6 is the order of the estimates.
+// Overflowed (infinite / NaN) estimates fail the test and take the exact path.
+//
+// Exact ties are common and must not pay for the exact path: a block whose maximum is an
+// outlier quantizes every other element to zero under both scalings, and then the two
+// candidates dequantize to the very same values.  same_dequantized() recognises the two
+// ways this happens from the codes alone.
+NV_DEV bool same_dequantized(uint32_t lo6, uint32_t hi6, uint32_t lo4, uint32_t hi4, float dec6,
+                             float dec4) {
+  // (a) the same scale byte: identical candidates
+  const bool identical = (lo6 == lo4) & (hi6 == hi4) & (dec6 == dec4);
+  // (b) every M=6 code in {0, 1.5, 3, 6} and the M=4 code the matching one of {0, 1, 2, 4}
+  // (as 3-bit indices 0,3,5,7 -> 0,2,4,6: the M=4 nibble is the M=6 nibble with its low
+  // bit cleared, and a nibble's low bit is set exactly when one of its two upper magnitude
+  // bits is), and fl(1.5 * dec6) == dec4: then fl(1.5*2^k * dec6) = 2^k * fl(1.5 * dec6)
+  // = fl(2^k * dec4) for every element, i.e. the rounded dequantized values coincide.
+  const uint32_t ones = 0x11111111u;
+  const bool scaled = 1.5f * dec6 == dec4;
+  const bool lo_ok = (lo4 == (lo6 & ~ones)) & ((((lo6 >> 1) | (lo6 >> 2)) & ones) == (lo6 & ones));
+  const bool hi_ok = (hi4 == (hi6 & ~ones)) & ((((hi6 >> 1) | (hi6 >> 2)) & ones) == (hi6 & ones));
+  return identical | (scaled & lo_ok & hi_ok);
+}
+
+NV_DEV bool decide_four(const float (&v)[16], float E6p, float E4p, float dec6, float dec4,
+                        uint32_t lo6, uint32_t hi6, uint32_t lo4, uint32_t hi4) {
+  const float tol = 0x1p-18f * ((fmaxf(dec6 * dec6, E6p) + E6p) + (fmaxf(dec4 * dec4, E4p) + E4p));
+  const float diff = E4p - E6p;
+  bool four = diff < 0.0f;
+  if (!(fabsf(diff) > tol)) {
+    four = false;   // identical dequantized values: equal errors, and ties keep 6
+    if (!same_dequantized(lo6, hi6, lo4, hi4, dec6, dec4))
+      four = exact_error(v, lo4, hi4, dec4) < exact_error(v, lo6, hi6, dec6);
+  }
+  return four;
 }
 
 struct BlockResult {
@@ -196,40 +278,34 @@ NV_DEV BlockResult quantize_block(const float (&v)[16], const float (&u)[16],
     if (SELECT != kSelForce6) S4 = e4m3_encode(b / k.c4);
   }
 
+  constexpr bool kBoth = SELECT == kSel46;
   BlockResult r6{}, r4{};
-  float E6 = 0.0f, E4 = 0.0f;
+  float E6p = 0.0f, E4p = 0.0f;
   if (SELECT != kSelForce4) {
     float2 t = tab.e[S6];
     r6.scale = S6;
     r6.dec = t.x;
     r6.four = 0u;
-    E6 = candidate<ROUNDING>(v, u, t.x, t.y, r6.lo, r6.hi);
+    E6p = candidate<ROUNDING, kBoth>(v, u, t.x, t.y, r6.lo, r6.hi);
   }
   if (SELECT != kSelForce6) {
     float2 t = tab.e[S4];
     r4.scale = S4;
     r4.dec = t.x;
     r4.four = 1u;
-    E4 = candidate<ROUNDING>(v, u, t.x, t.y, r4.lo, r4.hi);
+    E4p = candidate<ROUNDING, kBoth>(v, u, t.x, t.y, r4.lo, r4.hi);
   }
   if (SELECT == kSelForce6) return r6;
   if (SELECT == kSelForce4) return r4;
-  return (E4 < E6) ? r4 : r6;   // strict: ties keep 6 (Table 3 line 13)
+  return decide_four(v, E6p, E4p, r6.dec, r4.dec, r6.lo, r6.hi, r4.lo, r4.hi) ? r4 : r6;
 }
 
 // Dequantized fp32 values of 8 codes packed in one word: value(code) * dec.
 NV_DEV void dequant8(uint32_t codes, float dec, float (&D)[8]) {
+  float g[8];
+  grid8(codes, g);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-#if NVFP4_46_HW_FP4
-    f32x2 g = hw_pk_f32_fp4_sel(codes, j);
-    D[2 * j] = g.x * dec;
-    D[2 * j + 1] = g.y * dec;
-#else
-    D[2 * j] = e2m1_decode_sw((codes >> (8 * j)) & 15u) * dec;
-    D[2 * j + 1] = e2m1_decode_sw((codes >> (8 * j + 4)) & 15u) * dec;
-#endif
-  }
+  for (int j = 0; j < 8; ++j) D[j] = g[j] * dec;
 }
 
 }  // namespace nvfp4_46

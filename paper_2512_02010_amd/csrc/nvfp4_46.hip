@@ -35,7 +35,7 @@ enum : int { kOutCodes = 0, kOutFake = 1, kOutAmax = 2 };
 #define NVFP4_46_AMAX_WG_PER_CU 1
 #endif
 #ifndef NVFP4_46_FLAT_WG_PER_CU
-#define NVFP4_46_FLAT_WG_PER_CU 8
+#define NVFP4_46_FLAT_WG_PER_CU 16
 #endif
 
 // Streaming accesses: every input word is read once and every output byte written once,
@@ -237,31 +237,42 @@ __global__ __launch_bounds__(kThreads) void k_flat(
     }
   };
 
-  // The first round's loads go out before the scale table is built, so the table's
-  // divisions and barrier hide under the first memory latency instead of adding to it.
-  // In the fake-quant kernel lanes without a block still run (on zeros), because they
-  // store pieces of their neighbours' blocks; elsewhere they skip the round.
-  const uint32_t r0 = blockIdx.x;
-  const uint32_t live0 = r0 < rounds ? lanes_in_round(r0) : 0u;
-  uint4 p0 = make_uint4(0, 0, 0, 0), p1 = p0;
-  if (tid < live0) {
-    const uint4 *xb = x + 2 * ((int64_t)r0 * kThreads);
-    p0 = load_stream(xb + 2 * tid);
-    p1 = load_stream(xb + 2 * tid + 1);
-  }
-  if (OUT != kOutAmax) sc = build_scale_table(tab, *alpha_p);
-  if (OUT == kOutFake ? live0 != 0u : tid < live0) work(r0, live0, p0, p1);
-  for (uint32_t r = r0 + gridDim.x; r < rounds; r += gridDim.x) {
+  // Loads run one round ahead of the arithmetic: while a wave works on one block the two
+  // 128-bit loads of its next block are already in flight (two register sets, used
+  // alternately), so a round costs max(memory latency, arithmetic) instead of their sum.
+  // The first round's loads also go out before the scale table is built.
+  // In the fake-quant kernel lanes without a block still run (their results are not
+  // stored), because they store pieces of their neighbours' blocks; elsewhere they skip
+  // the round.
+  // The loads are unconditional (a conditional load would have to be waited for right
+  // where the two control paths join): a round past the end re-reads the last round and
+  // a lane past the end of a ragged last round re-reads that round's last block; what
+  // they fetch is never used.
+  auto fetch = [&](uint32_t r, uint4 &w0, uint4 &w1) {
+    const uint32_t rr = r < rounds ? r : rounds - 1;
+    const uint32_t last = lanes_in_round(rr) - 1;
+    const uint32_t lane = tid < last ? tid : last;
+    const uint4 *xb = x + 2 * ((int64_t)rr * kThreads);
+    w0 = load_stream(xb + 2 * lane);
+    w1 = load_stream(xb + 2 * lane + 1);
+  };
+  auto run = [&](uint32_t r, const uint4 &w0, const uint4 &w1) {
     const uint32_t live = lanes_in_round(r);
-    uint4 w0 = make_uint4(0, 0, 0, 0), w1 = w0;
-    if (tid < live) {
-      const uint4 *xb = x + 2 * ((int64_t)r * kThreads);
-      w0 = load_stream(xb + 2 * tid);
-      w1 = load_stream(xb + 2 * tid + 1);
-    } else if (OUT != kOutFake) {
-      continue;
-    }
-    work(r, live, w0, w1);
+    if (OUT == kOutFake || tid < live) work(r, live, w0, w1);
+  };
+  const uint32_t step = gridDim.x;
+  uint32_t r = blockIdx.x;
+  uint4 a0, a1, b0, b1;
+  fetch(r, a0, a1);
+  if (OUT != kOutAmax) sc = build_scale_table(tab, *alpha_p);
+  while (r < rounds) {
+    fetch(r + step, b0, b1);
+    run(r, a0, a1);
+    r += step;
+    if (r >= rounds) break;
+    fetch(r + step, a0, a1);
+    run(r, b0, b1);
+    r += step;
   }
   if (OUT == kOutAmax) publish_amax(amax, amax_bits);
 }
@@ -284,8 +295,28 @@ __global__ __launch_bounds__(kThreads) void k_dequant_flat(const uint32_t *__res
 
 // ------------------------------------------------ columnwise / both (tiled)
 
-constexpr int TR = 128;  // tile rows
-constexpr int TC = 128;  // tile columns
+#ifndef NVFP4_46_TILE_ROWS
+#define NVFP4_46_TILE_ROWS 128
+#endif
+#ifndef NVFP4_46_TILE_COLS
+#define NVFP4_46_TILE_COLS 128
+#endif
+constexpr int TR = NVFP4_46_TILE_ROWS;   // tile rows    (multiple of 16)
+constexpr int TC = NVFP4_46_TILE_COLS;   // tile columns (multiple of 16)
+constexpr int kRowBlocksPerTileRow = TC / 16;          // 16-element row blocks across a tile row
+constexpr int kRowBlocksPerTile = TR * TC / 16;
+constexpr int kRowBlocksPerLane = kRowBlocksPerTile / kThreads;
+constexpr int kColPairs = TC / 2;                      // pairs of adjacent columns
+constexpr int kColBlockRows = TR / 16;                 // 16-row blocks down a tile column
+constexpr int kPairUnits = kColPairs * kColBlockRows;  // (column pair, row block) units
+constexpr int kPairUnitsPerLane = kPairUnits / kThreads;
+constexpr int kColItems = TC * kColBlockRows;          // (column, row block) results per tile
+constexpr int kColItemsPerLane = kColItems / kThreads;
+constexpr int kPieces = TR * TC / 8;                   // 128-bit pieces of a BF16 tile
+constexpr int kPiecesPerLane = kPieces / kThreads;
+static_assert(TR % 16 == 0 && TC % 16 == 0, "tiles are made of whole blocks both ways");
+static_assert(kRowBlocksPerTile % kThreads == 0 && kPairUnits % kThreads == 0 &&
+              kColItems % kThreads == 0, "tile work must divide evenly over the workgroup");
 
 struct TileCoord {
   int64_t r0, c0;
@@ -313,27 +344,25 @@ __global__ __launch_bounds__(kThreads) void k_tile(
     uint16_t *__restrict__ out_bf16, uint32_t *amax_bits, int64_t rows, int64_t cols,
     uint64_t sr_seed, uint64_t rht_seed) {
   __shared__ ScaleTable tab;
-  __shared__ __align__(16) uint32_t tile[TR * TC / 2];  // BF16 pairs, row-major, 32 KiB
+  __shared__ __align__(16) uint32_t tile[TR * TC / 2];  // BF16 pairs, row-major
   // columnwise results wait here until a whole column segment can leave at once
-  __shared__ uint2 stage_codes[OUT == kOutCodes ? TC * 8 : 1];     // [TC][8]  8 KiB
-  __shared__ uint8_t stage_scale[OUT == kOutCodes ? TC * 8 : 1];   // [TC][8]  1 KiB
-  __shared__ uint8_t stage_choice[OUT == kOutCodes ? TC * 8 : 1];  // [TC][8]  1 KiB
+  __shared__ uint2 stage_codes[OUT == kOutCodes ? kColItems : 1];     // [TC][TR/16]
+  __shared__ uint8_t stage_scale[OUT == kOutCodes ? kColItems : 1];   // [TC][TR/16]
+  __shared__ uint8_t stage_choice[OUT == kOutCodes ? kColItems : 1];  // [TC][TR/16]
 
   const TileCoord tcd = tile_of_workgroup(rows, cols);
   if (!tcd.valid) return;  // uniform over the workgroup
   const int64_t r0 = tcd.r0, c0 = tcd.c0;
   const int t = threadIdx.x;
 
-  ScaleConsts sc{};
-  if (OUT != kOutAmax) sc = build_scale_table(tab, *alpha_p);
-
-  // ---- phase 1: global -> LDS (and the rowwise outputs on the way)
+  // ---- phase 1: global -> LDS (and the rowwise outputs on the way); the loads go out
+  // before the scale table is built
   {
-    uint4 w[4][2];
+    uint4 w[kRowBlocksPerLane][2];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int unit = t + j * kThreads;          // 1024 row-blocks of the tile
-      const int row = unit >> 3, rbk = unit & 7;
+    for (int j = 0; j < kRowBlocksPerLane; ++j) {
+      const int unit = t + j * kThreads;
+      const int row = unit / kRowBlocksPerTileRow, rbk = unit % kRowBlocksPerTileRow;
       const int64_t gr = r0 + row, gc = c0 + rbk * 16;
       const uint4 *src = reinterpret_cast<const uint4 *>(x + gr * cols + gc);
       w[j][0] = w[j][1] = make_uint4(0, 0, 0, 0);   // outside the tensor: zeros
@@ -341,55 +370,58 @@ __global__ __launch_bounds__(kThreads) void k_tile(
       if (gr < rows && gc + 8 < cols) w[j][1] = src[1];
     }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < kRowBlocksPerLane; ++j) {
       const int unit = t + j * kThreads;
       uint4 *dst = reinterpret_cast<uint4 *>(tile) + unit * 2;
       dst[0] = w[j][0];
       dst[1] = w[j][1];
     }
-    if (WANT_ROW) {
-      // the lane's own four row-blocks, taken back from LDS one at a time (keeps the
-      // register footprint of the quantizer to a single block)
-      const int64_t nb_per_row = cols / 16;
+  }
+  ScaleConsts sc{};
+  if (OUT != kOutAmax) sc = build_scale_table(tab, *alpha_p);   // ends with a barrier
+  else __syncthreads();
+
+  if (WANT_ROW) {
+    // the lane's own row blocks, taken back from LDS one at a time (keeps the register
+    // footprint of the quantizer to a single block)
+    const int64_t nb_per_row = cols / 16;
 #pragma unroll 1
-      for (int j = 0; j < 4; ++j) {
-        const int unit = t + j * kThreads;
-        const int row = unit >> 3, rbk = unit & 7;
-        const int64_t gr = r0 + row, gc = c0 + rbk * 16;
-        if (gr < rows && gc < cols) {
-          float v[16], u[16];
-          const uint4 *own = reinterpret_cast<const uint4 *>(tile) + unit * 2;
-          unpack16(own[0], own[1], v);
-          const int64_t k = gr * nb_per_row + (gc >> 4);
-          if (ROUNDING == kSR) {
+    for (int j = 0; j < kRowBlocksPerLane; ++j) {
+      const int unit = t + j * kThreads;
+      const int row = unit / kRowBlocksPerTileRow, rbk = unit % kRowBlocksPerTileRow;
+      const int64_t gr = r0 + row, gc = c0 + rbk * 16;
+      if (gr < rows && gc < cols) {
+        float v[16], u[16];
+        const uint4 *own = reinterpret_cast<const uint4 *>(tile) + unit * 2;
+        unpack16(own[0], own[1], v);
+        const int64_t k = gr * nb_per_row + (gc >> 4);
+        if (ROUNDING == kSR) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) sr_uniforms4(sr_seed, (uint64_t)k * 4u + q, &u[4 * q]);
-          }
-          BlockResult r = quantize_block<ROUNDING, SELECT>(v, u, sc, tab);
-          reinterpret_cast<uint2 *>(codes_row)[k] = make_uint2(r.lo, r.hi);
-          scales_row[k] = (uint8_t)r.scale;
-          if (choice_row) choice_row[k] = (uint8_t)r.four;
+          for (int q = 0; q < 4; ++q) sr_uniforms4(sr_seed, (uint64_t)k * 4u + q, &u[4 * q]);
         }
+        BlockResult r = quantize_block<ROUNDING, SELECT>(v, u, sc, tab);
+        reinterpret_cast<uint2 *>(codes_row)[k] = make_uint2(r.lo, r.hi);
+        scales_row[k] = (uint8_t)r.scale;
+        if (choice_row) choice_row[k] = (uint8_t)r.four;
       }
     }
   }
-  __syncthreads();
 
-  // ---- phase 2: every lane takes two adjacent columns x 16 rows, twice.  A (column
-  // pair, row block) unit is read and, for the fake-quant output, rewritten in place by
-  // its owner lane only, so no barrier is needed inside this phase.
+  // ---- phase 2: every lane takes two adjacent columns x 16 rows.  A (column pair, row
+  // block) unit is read and, for the fake-quant output, rewritten in place by its owner
+  // lane only, so no barrier is needed inside this phase.
   float amax = 0.0f;
 #pragma unroll 1
-  for (int j = 0; j < 2; ++j) {
-    const int pu = t + j * kThreads;              // 512 (column pair, row block) units
-    const int cp = pu & 63, rb = pu >> 6;
+  for (int j = 0; j < kPairUnitsPerLane; ++j) {
+    const int pu = t + j * kThreads;
+    const int cp = pu % kColPairs, rb = pu / kColPairs;
     const int64_t gr = r0 + rb * 16;              // first row of the block
     const int64_t gc = c0 + 2 * cp;               // even column of the pair
     if (gr >= rows || gc >= cols) continue;       // (cols is even, so the pair is in or out together)
     float va[16], vb[16], ua[16], ub[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const uint32_t pair = tile[(rb * 16 + i) * (TC / 2) + cp];
+      const uint32_t pair = tile[(rb * 16 + i) * kColPairs + cp];
       va[i] = bf16_lo(pair);
       vb[i] = bf16_hi(pair);
     }
@@ -418,7 +450,7 @@ __global__ __launch_bounds__(kThreads) void k_tile(
     BlockResult ra = quantize_block<ROUNDING, SELECT>(va, ua, sc, tab);
     BlockResult rbk = quantize_block<ROUNDING, SELECT>(vb, ub, sc, tab);
     if (OUT == kOutCodes) {
-      const int ia = (2 * cp) * 8 + rb, ib = (2 * cp + 1) * 8 + rb;
+      const int ia = (2 * cp) * kColBlockRows + rb, ib = ia + kColBlockRows;
       stage_codes[ia] = make_uint2(ra.lo, ra.hi);
       stage_codes[ib] = make_uint2(rbk.lo, rbk.hi);
       stage_scale[ia] = (uint8_t)ra.scale;
@@ -443,7 +475,7 @@ __global__ __launch_bounds__(kThreads) void k_tile(
         for (int i = 0; i < 8; ++i) Db[8 + i] = h[i];
       }
 #pragma unroll
-      for (int i = 0; i < 16; ++i) tile[(rb * 16 + i) * (TC / 2) + cp] = pack_bf16x2(Da[i], Db[i]);
+      for (int i = 0; i < 16; ++i) tile[(rb * 16 + i) * kColPairs + cp] = pack_bf16x2(Da[i], Db[i]);
     }
   }
   if (OUT == kOutAmax) {
@@ -456,9 +488,9 @@ __global__ __launch_bounds__(kThreads) void k_tile(
   if (OUT == kOutCodes) {
     const int64_t col_codes = rows / 2, col_scales = rows / 16;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int it = t + j * kThreads;            // 1024 (column, row block) items
-      const int cl = it >> 3, rb = it & 7;
+    for (int j = 0; j < kColItemsPerLane; ++j) {
+      const int it = t + j * kThreads;
+      const int cl = it / kColBlockRows, rb = it % kColBlockRows;
       const int64_t gc = c0 + cl, gr = r0 + rb * 16;
       if (gc < cols && gr < rows) {
         *reinterpret_cast<uint2 *>(codes_col + gc * col_codes + (gr >> 1)) = stage_codes[it];
@@ -468,18 +500,18 @@ __global__ __launch_bounds__(kThreads) void k_tile(
     }
   } else {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int idx = t + j * kThreads;           // 2048 128-bit pieces of the tile
-      const int row = idx >> 4, seg = idx & 15;
+    for (int j = 0; j < kPiecesPerLane; ++j) {
+      const int idx = t + j * kThreads;
+      const int row = idx / (TC / 8), seg = idx % (TC / 8);
       const int64_t gr = r0 + row, gc = c0 + seg * 8;
       if (gr < rows && gc < cols)
-        *reinterpret_cast<uint4 *>(out_bf16 + gr * cols + gc) =
-            reinterpret_cast<const uint4 *>(tile)[idx];
+        store_as<kNtBf16>(reinterpret_cast<uint4 *>(out_bf16 + gr * cols + gc),
+                          reinterpret_cast<const uint4 *>(tile)[idx]);
     }
   }
 }
 
-// Columnwise codes/scales -> row-major BF16, through a 128x128 LDS tile.
+// Columnwise codes/scales -> row-major BF16, through an LDS tile.
 __global__ __launch_bounds__(kThreads) void k_dequant_col(const uint8_t *__restrict__ codes,
                                                           const uint8_t *__restrict__ scales,
                                                           const float *__restrict__ alpha_p,
@@ -493,9 +525,9 @@ __global__ __launch_bounds__(kThreads) void k_dequant_col(const uint8_t *__restr
   const float alpha = *alpha_p;
   const int64_t col_codes = rows / 2, col_scales = rows / 16;
 #pragma unroll 1
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < kColItemsPerLane; ++j) {
     const int it = t + j * kThreads;
-    const int cl = it >> 3, rb = it & 7;
+    const int cl = it / kColBlockRows, rb = it % kColBlockRows;
     const int64_t gc = c0 + cl, gr = r0 + rb * 16;
     if (gc < cols && gr < rows) {
       const uint2 c = *reinterpret_cast<const uint2 *>(codes + gc * col_codes + (gr >> 1));
@@ -512,13 +544,13 @@ __global__ __launch_bounds__(kThreads) void k_dequant_col(const uint8_t *__restr
   }
   __syncthreads();
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
+  for (int j = 0; j < kPiecesPerLane; ++j) {
     const int idx = t + j * kThreads;
-    const int row = idx >> 4, seg = idx & 15;
+    const int row = idx / (TC / 8), seg = idx % (TC / 8);
     const int64_t gr = r0 + row, gc = c0 + seg * 8;
     if (gr < rows && gc < cols)
-      *reinterpret_cast<uint4 *>(out + gr * cols + gc) =
-          reinterpret_cast<const uint4 *>(tile16)[idx];
+      store_as<kNtBf16>(reinterpret_cast<uint4 *>(out + gr * cols + gc),
+                        reinterpret_cast<const uint4 *>(tile16)[idx]);
   }
 }
 
