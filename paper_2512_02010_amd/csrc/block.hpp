@@ -129,6 +129,14 @@ NV_DEV float candidate(const float (&v)[16], const float (&u)[16], float dec, fl
         w = hw_pk_fp4_sel(w, v[8 * h + 2 * j] * enc, v[8 * h + 2 * j + 1] * enc, j);
       if (WANT_ERROR) grid8(w, g);
       c[h] = w;
+    } else if (ROUNDING == kSR) {
+      // the rounded values are on the grid, so the conversion that packs them is exact
+#pragma unroll
+      for (int j = 0; j < 8; ++j) g[j] = e2m1_sr_value(v[8 * h + j] * enc, u[8 * h + j]);
+      uint32_t w = 0u;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) w = hw_pk_fp4_sel(w, g[2 * j], g[2 * j + 1], j);
+      c[h] = w;
     } else
 #endif
     {

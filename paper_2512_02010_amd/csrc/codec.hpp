@@ -97,24 +97,21 @@ NV_DEV uint32_t e2m1_rtn_sw(float y) {
   return k | ((f2u(y) >> 28) & 8u);
 }
 
-// Stochastic rounding of y with uniform u in [0,1): lo <= |y| < hi neighbours
-// on the grid, up iff u < (|y|-lo)/(hi-lo).  hi-lo is a power of two, so the
-// test is done as u*(hi-lo) < |y|-lo, every term exact.  Returns the signed
-// rounded value (exactly representable), from which code and dequantized
-// value both follow.
+// Stochastic rounding of y with uniform u in [0,1): lo <= |y| < hi neighbours on the
+// grid, up iff u < (|y|-lo)/(hi-lo).  The grid step around a = min(|y|, 6) is a power of
+// two (0.5 below 2, then 1, then 2), so q = a/step is an exact scaling, lo/step = floor(q)
+// and the probability (|y|-lo)/(hi-lo) = q - floor(q), all without rounding.  Returns the
+// signed rounded value (exactly representable), from which code and dequantized value
+// both follow.
 NV_DEV float e2m1_sr_value(float y, float u) {
-  float a = fminf(fabsf(y), 6.0f);
-  uint32_t bits = f2u(a);
-  float lo, step;
-  if (a >= 1.0f) {
-    lo = u2f(bits & 0xffc00000u);                      // keep exponent + top mantissa bit
-    step = u2f((bits & 0x7f800000u) - 0x00800000u);    // half of 2^exponent
-  } else {
-    lo = (a >= 0.5f) ? 0.5f : 0.0f;
-    step = 0.5f;
-  }
-  float frac = a - lo;
-  float r = (u * step < frac) ? lo + step : lo;
+  const float a = fminf(fabsf(y), 6.0f);
+  uint32_t e = f2u(a) & 0x7f800000u;                    // 2^floor(log2 a)
+  e = e > 0x3f800000u ? e : 0x3f800000u;                // everything below 2 steps by 0.5
+  const uint32_t step_bits = e - 0x00800000u;           // step = 2^(exponent-1)
+  const float q = a * u2f(0x7f000000u - step_bits);     // a / step, in [0, 4)
+  const float fl = __builtin_floorf(q);
+  const float up = (u < q - fl) ? 1.0f : 0.0f;
+  const float r = (fl + up) * u2f(step_bits);
   return u2f(f2u(r) | (f2u(y) & 0x80000000u));
 }
 
@@ -158,6 +155,11 @@ NV_DEV uint32_t e4m3_encode(float x) {
 
 // --------------------------------------------------------------- Philox
 
+// a ^ b ^ c in one instruction (v_bitop3_b32 with the truth table of a 3-input XOR)
+NV_DEV uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+  return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
 // Philox4x32-10 (Salmon et al., SC'11).
 struct Philox4 {
   uint32_t w[4];
@@ -167,12 +169,12 @@ NV_DEV Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                              uint32_t k1) {
 #pragma unroll
   for (int r = 0; r < 10; ++r) {
-    uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
-    uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
-    c0 = h1 ^ c1 ^ k0;
-    c1 = l1;
-    c2 = h0 ^ c3 ^ k1;
-    c3 = l0;
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0;   // one 32x32->64 multiply each
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+    c0 = xor3((uint32_t)(p1 >> 32), c1, k0);
+    c1 = (uint32_t)p1;
+    c2 = xor3((uint32_t)(p0 >> 32), c3, k1);
+    c3 = (uint32_t)p0;
     k0 += 0x9E3779B9u;
     k1 += 0xBB67AE85u;
   }

@@ -182,7 +182,7 @@ __global__ __launch_bounds__(kThreads) void k_flat(
   const uint32_t tid = threadIdx.x;
   const uint32_t rounds = (uint32_t)((nblocks + kThreads - 1) / kThreads);
   const uint32_t tail = (uint32_t)(nblocks - (int64_t)(rounds - 1) * kThreads);  // 1..256
-  uint32_t B_lane = 0;
+  uint32_t B_lane = 0, sign_B = 0xffffffffu, sign_word = 0;
   if (RHT) B_lane = tid % nb_per_row;
   float amax = 0.0f;
   ScaleConsts sc{};
@@ -196,9 +196,15 @@ __global__ __launch_bounds__(kThreads) void k_flat(
     float v[16], u[16];
     unpack16(w0, w1, v);
     if (RHT) {
+      // the sign word depends on the block's position in its row only; with the usual
+      // shapes a lane meets the same position in every round and keeps the word
       uint32_t B = (uint32_t)(base % nb_per_row) + B_lane;
       if (B >= nb_per_row) B -= nb_per_row;
-      rht16(v, rht_sign_word(rht_seed, B));
+      if (B != sign_B) {
+        sign_B = B;
+        sign_word = rht_sign_word(rht_seed, B);
+      }
+      rht16(v, sign_word);
     }
     if (OUT == kOutAmax) {
 #pragma unroll
@@ -642,7 +648,15 @@ struct FlatArgs {
 
 template <int ROUNDING, int SELECT, bool RHT, int OUT>
 static void launch_flat(const FlatArgs &a) {
-  const int grid = grid_for(a.nblocks, NVFP4_46_FLAT_WG_PER_CU);
+  int grid = grid_for(a.nblocks, NVFP4_46_FLAT_WG_PER_CU);
+  if (RHT) {
+    // round r of a workgroup starts at block 256*r; if 256*grid is a multiple of the
+    // blocks per row, every lane sees one position along the row in all its rounds
+    uint32_t g = a.nb_per_row, t = kThreads;
+    while (t) { const uint32_t q = g % t; g = t; t = q; }      // gcd(nb_per_row, 256)
+    const int period = (int)(a.nb_per_row / g);
+    if (period <= grid / 2) grid -= grid % period;
+  }
   hipLaunchKernelGGL((k_flat<ROUNDING, SELECT, RHT, OUT>), dim3(grid), dim3(kThreads), 0, a.stream,
                      a.x, a.alpha, a.codes, a.scales, a.choice, a.out, a.amax, a.nblocks,
                      a.nb_per_row, a.sr_seed, a.rht_seed);
