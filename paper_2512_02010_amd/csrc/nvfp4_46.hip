@@ -9,9 +9,9 @@
 //             registers, no cross-lane traffic); a wave's 64 lanes cover 2 KiB of
 //             contiguous input, 512 B of codes and 64 B of scales.
 //   columnwise / both
-//             A workgroup stages a 128x128 tile of x in LDS (coalesced 128-bit
+//             A workgroup stages a 64x128 tile of x in LDS (coalesced 128-bit
 //             loads), every lane then reads two adjacent columns x 16 rows from
-//             LDS, and the results go back through LDS so that each column's 64
+//             LDS, and the results go back through LDS so that each column's 32
 //             code bytes leave as one contiguous run.  When both orientations
 //             are wanted the rowwise half is produced from the registers of the
 //             staging loads, so x is read from HBM once.
@@ -302,7 +302,7 @@ __global__ __launch_bounds__(kThreads) void k_dequant_flat(const uint32_t *__res
 // ------------------------------------------------ columnwise / both (tiled)
 
 #ifndef NVFP4_46_TILE_ROWS
-#define NVFP4_46_TILE_ROWS 128
+#define NVFP4_46_TILE_ROWS 64
 #endif
 #ifndef NVFP4_46_TILE_COLS
 #define NVFP4_46_TILE_COLS 128

@@ -193,6 +193,27 @@ def adversarial(kind: str, rows: int = 32, cols: int = 64) -> torch.Tensor:
         idx = torch.randint(0, len(mids), (rows, cols), generator=g)
         x = mids[idx]
         x[:, ::16] = 6.0
+    elif kind == "decision_stress":
+        # blocks on which the two scalings give equal or nearly equal errors: a lone
+        # outlier (everything else rounds to zero both ways), an outlier over faint noise,
+        # two equal peaks, constants, plain noise -- at many magnitudes
+        nb = cols // 16
+        x = torch.zeros((rows, nb, 16))
+        pat = torch.randint(0, 6, (rows, nb), generator=g)
+        mag = torch.exp2(torch.randint(-12, 6, (rows, nb), generator=g).float())
+        mag = mag * (1.0 + torch.rand((rows, nb), generator=g))
+        noise = _normal((rows, nb, 16), g)
+        pos = torch.randint(0, 16, (rows, nb), generator=g)
+        peak = torch.zeros((rows, nb, 16)).scatter_(2, pos.unsqueeze(-1), 1.0)
+        pos2 = (pos + 1 + torch.randint(0, 15, (rows, nb), generator=g)) % 16
+        peak2 = torch.zeros((rows, nb, 16)).scatter_(2, pos2.unsqueeze(-1), 1.0)
+        x = torch.where((pat == 0).unsqueeze(-1), peak, x)
+        x = torch.where((pat == 1).unsqueeze(-1), peak + 1e-3 * noise, x)
+        x = torch.where((pat == 2).unsqueeze(-1), peak + 0.03 * noise, x)
+        x = torch.where((pat == 3).unsqueeze(-1), peak - peak2, x)
+        x = torch.where((pat == 4).unsqueeze(-1), torch.ones(16) * 0.75, x)
+        x = torch.where((pat == 5).unsqueeze(-1), 0.3 * noise, x)
+        x = (x * mag.unsqueeze(-1)).reshape(rows, cols)
     elif kind == "bf16_small":
         x = _normal((rows, cols), g) * 1.0e-24
     elif kind == "bf16_large":

@@ -134,6 +134,18 @@ def test_adversarial_with_sr_and_rht():
         check_case(wl.adversarial(kind), rounding=B.SR, rht=1, tag=f"adv-{kind}-sr-rht")
 
 
+@pytest.mark.parametrize("layout", [B.ROWWISE, B.BOTH])
+@pytest.mark.parametrize("rounding", [B.RTN, B.SR])
+def test_decision_on_ties_and_near_ties(layout, rounding):
+    """Blocks whose two candidates have equal or almost equal errors: the kernel decides
+    most blocks from cheap error estimates and must fall back to the defined errors (or
+    recognise an exact tie) on exactly these."""
+    x = wl.adversarial("decision_stress", 1024, 2048)
+    out = check_case(x, layout=layout, rounding=rounding, tag="decision-stress")
+    frac4 = float(_np(out["choice_row"]).mean())
+    assert 0.02 < frac4 < 0.9
+
+
 def test_caller_supplied_alpha_replays_table3():
     # Table 3's blocks with the tensor scale written as 1: [10,20,30,40] -> 4, [15,30,120,180] -> 6
     x = torch.zeros((16, 32), dtype=torch.float32)
