@@ -194,6 +194,48 @@ def test_runs_on_a_side_stream_and_is_deterministic():
             assert torch.equal(o[k], base[k])
 
 
+def test_step_can_be_captured_in_a_graph_and_replayed():
+    """tensor_scale -> quantize -> dequantize recorded into a HIP graph (the library only
+    launches kernels on the stream it is given: no allocation, no memset, no sync) and
+    replayed with eager work in between; every replay must equal the eager result."""
+    x1 = wl.make("c2", 512, 1024)
+    x2 = wl.make("c3", 512, 1024)
+    xd = x1.cuda()
+    rows, cols = xd.shape
+    alpha = torch.empty(1, dtype=torch.float32, device="cuda")
+    out = B.alloc_outputs(rows, cols, B.BOTH, "cuda")
+    deq = torch.empty_like(xd)
+    p = B.make_params(rows, cols, layout=B.BOTH)
+
+    def step(stream):
+        assert B.tensor_scale_raw(xd, p, alpha, stream) == 0
+        assert B.quantize_raw(xd, p, alpha, out["codes_row"], out["scales_row"], out["codes_col"],
+                              out["scales_col"], out["choice_row"], out["choice_col"], stream) == 0
+        assert B.dequantize_raw(out["codes_row"], out["scales_row"], alpha, rows, cols, B.ROWWISE,
+                                deq, stream) == 0
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [alpha.clone(), deq.clone()] + [out[k].clone() for k in sorted(out)]
+
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        step(s)                       # warm-up outside the capture
+    s.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        step(torch.cuda.current_stream())
+    for src in (x1, x2, x1, x2):
+        xd.copy_(src.cuda())
+        step(torch.cuda.current_stream())
+        want = snapshot()
+        for t in [alpha, deq] + [out[k] for k in out]:
+            t.zero_()                 # eager work between the replays
+        g.replay()
+        got = snapshot()
+        assert all(torch.equal(a, b) for a, b in zip(got, want))
+
+
 def test_gpu_error_paths_enqueue_nothing():
     x = wl.make("c1", 32, 64).cuda()
     alpha = torch.ones(1, dtype=torch.float32, device="cuda")
