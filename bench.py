@@ -52,6 +52,10 @@ def parse():
     ap.add_argument("--cols", type=int, default=8192)
     ap.add_argument("--buffers", type=int, default=4, help="independent buffer sets rotated over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--other-workloads", action="store_true",
+                    help="also time the c3 (fake-quant), c4 (both orientations) and c5 "
+                         "(Hadamard + stochastic rounding) steps at their full sizes and add "
+                         "them to the JSON line as `other_workloads`")
     ap.add_argument("--counter-pass", action="store_true",
                     help="launch a calibration copy and each kernel of the step a few times and "
                          "exit (for `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE -- python3 bench.py "
@@ -127,6 +131,65 @@ def cpu_baseline(x_host):
             "kind": "oracle",
             "sample": f"{reps} full passes (tensor scale + quantize + dequantize) over the same "
                       f"{rows}x{cols} tensor, OpenMP over rows"}
+
+
+def time_other_workloads(iters=30):
+    """Median event-timed duration of the tensor-scale call and of the main call of
+    workloads c3, c4, c5 (full size, two rotating buffer sets each)."""
+    import statistics
+    res = {}
+    st = torch.cuda.current_stream()
+
+    def med(fn):
+        for i in range(4):
+            fn(i)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(iters)]
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(evs):
+            a.record()
+            fn(i)
+            b.record()
+        torch.cuda.synchronize()
+        return statistics.median(a.elapsed_time(b) for a, b in evs) * 1e3
+
+    def entry(n, bpe, t_scale, t_main, what):
+        return {"what": what, "elements": n, "tensor_scale_us": t_scale, "main_us": t_main,
+                "main_g_elem_s": n / t_main / 1e3, "main_algorithmic_gb_s": n * bpe / t_main / 1e3,
+                "main_frac_of_8tbs": n * bpe / t_main / 1e3 / HBM_PEAK_GBS}
+
+    # c3: activation batch, fake-quant round trip in one kernel (2 B read + 2 B written)
+    xs = [wl.make("c3").cuda() for _ in range(2)]
+    r, c = xs[0].shape
+    alpha = torch.empty(1, dtype=torch.float32, device="cuda")
+    outs = [torch.empty_like(xs[0]) for _ in range(2)]
+    p = B.make_params(r, c)
+    t_s = med(lambda i: B.tensor_scale_raw(xs[i % 2], p, alpha, st))
+    t_m = med(lambda i: B.fake_quant_raw(xs[i % 2], p, alpha, outs[i % 2], st))
+    res["c3"] = entry(r * c, 4.0, t_s, t_m, "16384x4096 fake-quant, rowwise RTN 4/6")
+    del xs, outs
+    # c4: rowwise + columnwise outputs from one read (2 B read + 1.125 B written)
+    xs = [wl.make("c4").cuda() for _ in range(2)]
+    r, c = xs[0].shape
+    os_ = [B.alloc_outputs(r, c, B.BOTH, "cuda", want_choice=False) for _ in range(2)]
+    p = B.make_params(r, c, layout=B.BOTH)
+    t_s = med(lambda i: B.tensor_scale_raw(xs[i % 2], p, alpha, st))
+    t_m = med(lambda i: B.quantize_raw(xs[i % 2], p, alpha, os_[i % 2]["codes_row"],
+                                       os_[i % 2]["scales_row"], os_[i % 2]["codes_col"],
+                                       os_[i % 2]["scales_col"], None, None, st))
+    res["c4"] = entry(r * c, 3.125, t_s, t_m, "8192x8192 quantize, both orientations, RTN 4/6")
+    del xs, os_
+    # c5: gradient tensor, Hadamard transform + stochastic rounding (arithmetic-bound)
+    xs = [wl.make("c5").cuda() for _ in range(2)]
+    r, c = xs[0].shape
+    os_ = [B.alloc_outputs(r, c, B.ROWWISE, "cuda", want_choice=False) for _ in range(2)]
+    p = B.make_params(r, c, rounding=B.SR, rht=1, sr_seed=wl.C5_SR_SEED, rht_seed=wl.C5_RHT_SEED)
+    t_s = med(lambda i: B.tensor_scale_raw(xs[i % 2], p, alpha, st))
+    t_m = med(lambda i: B.quantize_raw(xs[i % 2], p, alpha, os_[i % 2]["codes_row"],
+                                       os_[i % 2]["scales_row"], None, None, None, None, st))
+    res["c5"] = entry(r * c, BYTES_PER_ELEM_QUANT, t_s, t_m,
+                      "32768x8192 quantize, rowwise, Hadamard + stochastic rounding, 4/6")
+    return res
 
 
 def main():
@@ -274,6 +337,10 @@ def main():
                              "quantization on NVIDIA Blackwell (Sections 1, 3.2)",
         },
     }
+    if args.other_workloads:
+        del sets, graphs
+        torch.cuda.empty_cache()
+        result["other_workloads"] = time_other_workloads()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(x_host)
     print(json.dumps(result))
