@@ -17,6 +17,9 @@
  *   - the 4/6 procedure (quantize with M=6 and M=4, dequantize, squared error,
  *     keep M=4 only if its error is strictly smaller): Table 3 lines 1-14 and
  *     Section 3.1;
+ *   - the two alternative selection rules of Section 3.1 / Table 4 (mean absolute
+ *     error, the rule Section 4.1 and Appendix A.1 recommend for pre-training, and
+ *     largest absolute error);
  *   - stochastic rounding of gradients with selection on the rounded values
  *     ("biased selection"): Section 2.2, Section 4.1, Appendix A.3;
  *   - 16-point random Hadamard transform: named in Section 2.2 / 4.1 / Fig. 3.
@@ -45,7 +48,8 @@
 #define BLOCK 16
 
 enum { REF_RTN = 0, REF_SR = 1 };
-enum { REF_SEL_46_MSE = 0, REF_SEL_FORCE6 = 1, REF_SEL_FORCE4 = 2 };
+enum { REF_SEL_46_MSE = 0, REF_SEL_FORCE6 = 1, REF_SEL_FORCE4 = 2, REF_SEL_46_MAE = 3,
+       REF_SEL_46_ABSMAX = 4 };
 enum { REF_ROWWISE = 1, REF_COLWISE = 2 };
 
 /* ------------------------------------------------------------------ formats */
@@ -266,6 +270,21 @@ float ref_block_with_scale(const float v[BLOCK], float alpha, uint8_t S, int rou
   return error_sum(e);
 }
 
+/* The other two selection metrics of Section 3.1 (Table 4), from a candidate's
+ * dequantized values: the sum of |D_i - v_i| (the mean without its common 1/n,
+ * added in the same fixed order as the squared errors), or the largest
+ * |D_i - v_i|.  READING: the paper prints the latter as max_i(Xbar_i - X_i),
+ * without absolute value and on the codes; it is taken as max_i |D_i - X_i|. */
+float ref_block_abs_metric(const float v[BLOCK], const float D[BLOCK], int select) {
+  float e[BLOCK];
+  for (int i = 0; i < BLOCK; ++i) e[i] = fabsf(D[i] - v[i]);
+  if (select == REF_SEL_46_MAE) return error_sum(e);
+  float m = 0.0f;
+  for (int i = 0; i < BLOCK; ++i)
+    if (e[i] > m) m = e[i];
+  return m;
+}
+
 /* Eq. (2) for a block whose largest magnitude is b, mapped to M (6 or 4):
  * one fp32 product and one fp32 division, then the cast to E4M3. */
 uint8_t ref_block_scale(float b, float alpha, float M) {
@@ -276,8 +295,9 @@ uint8_t ref_block_scale(float b, float alpha, float M) {
 /* The 4/6 procedure on one block of 16 fp32 values (Table 3).  `select`
  * can force either candidate (standard NVFP4 is "always 6").  Outputs: the
  * chosen codes, scale byte and dequantized values, whether 4 was chosen, and
- * both candidates' errors (E[0] for M=6, E[1] for M=4; a forced mode fills
- * only its own). */
+ * both candidates' errors under the rule in force (E[0] for M=6, E[1] for M=4;
+ * squared error unless `select` names another metric; a forced mode fills only
+ * its own). */
 void ref_quantize_block(const float v[BLOCK], float alpha, int rounding, int select,
                         const float u[BLOCK], uint8_t q_out[BLOCK], float D_out[BLOCK],
                         uint8_t *S_out, uint8_t *four_out, float E[2]) {
@@ -297,6 +317,10 @@ void ref_quantize_block(const float v[BLOCK], float alpha, int rounding, int sel
   if (select != REF_SEL_FORCE6) {
     S4 = ref_block_scale(b, alpha, 4.0f);
     E[1] = ref_block_with_scale(v, alpha, S4, rounding, u, q4, D4);
+  }
+  if (select == REF_SEL_46_MAE || select == REF_SEL_46_ABSMAX) {
+    E[0] = ref_block_abs_metric(v, D6, select);
+    E[1] = ref_block_abs_metric(v, D4, select);
   }
   int four;
   if (select == REF_SEL_FORCE6)
@@ -428,11 +452,12 @@ int nvfp4_46_ref_fake_quant(const uint16_t *x, int64_t rows, int64_t cols, int l
                                alpha, NULL, NULL, NULL, out);
 }
 
-/* Per-block errors of both candidates for every block (test helper for the
- * invariant E_chosen <= E_6).  E6 / E4: [lines][len/16] fp32. */
-int nvfp4_46_ref_block_errors(const uint16_t *x, int64_t rows, int64_t cols, int layout,
-                              int rounding, int rht, uint64_t sr_seed, uint64_t rht_seed,
-                              float alpha, float *E6, float *E4) {
+/* Per-block errors of both candidates for every block under the metric that
+ * `select` names (test helper for the invariant E_chosen <= E_6).
+ * E6 / E4: [lines][len/16] fp32. */
+int nvfp4_46_ref_block_errors_sel(const uint16_t *x, int64_t rows, int64_t cols, int layout,
+                                  int rounding, int select, int rht, uint64_t sr_seed,
+                                  uint64_t rht_seed, float alpha, float *E6, float *E4) {
   int64_t L = n_lines(rows, cols, layout), NB = n_blocks(rows, cols, layout);
 #pragma omp parallel for schedule(static)
   for (int64_t line = 0; line < L; ++line)
@@ -443,11 +468,18 @@ int nvfp4_46_ref_block_errors(const uint16_t *x, int64_t rows, int64_t cols, int
       fetch_block(x, rows, cols, layout, line, blk, rht, rht_seed, v, g);
       for (int i = 0; i < BLOCK; ++i)
         u[i] = (rounding == REF_SR) ? ref_sr_uniform(sr_seed, g[i]) : 0.0f;
-      ref_quantize_block(v, alpha, rounding, REF_SEL_46_MSE, u, q, D, &S, &four, E);
+      ref_quantize_block(v, alpha, rounding, select, u, q, D, &S, &four, E);
       E6[line * NB + blk] = E[0];
       E4[line * NB + blk] = E[1];
     }
   return 0;
+}
+
+int nvfp4_46_ref_block_errors(const uint16_t *x, int64_t rows, int64_t cols, int layout,
+                              int rounding, int rht, uint64_t sr_seed, uint64_t rht_seed,
+                              float alpha, float *E6, float *E4) {
+  return nvfp4_46_ref_block_errors_sel(x, rows, cols, layout, rounding, REF_SEL_46_MSE, rht,
+                                       sr_seed, rht_seed, alpha, E6, E4);
 }
 
 /* Range helpers for exhaustive comparisons of the scalar codecs: evaluate a

@@ -21,7 +21,7 @@ _SRC = _HERE / "nvfp4_46_ref.c"
 _SO = _HERE / "libnvfp4_46_ref.so"
 
 RTN, SR = 0, 1
-SEL_46_MSE, SEL_FORCE6, SEL_FORCE4 = 0, 1, 2
+SEL_46_MSE, SEL_FORCE6, SEL_FORCE4, SEL_46_MAE, SEL_46_ABSMAX = 0, 1, 2, 3, 4
 ROWWISE, COLWISE = 1, 2
 
 # no FMA contraction, no fast-math, default (round-to-nearest) mode, SSE2 fp32
@@ -75,9 +75,11 @@ def lib() -> C.CDLL:
         L.nvfp4_46_ref_fake_quant.restype = i32
         L.nvfp4_46_ref_fake_quant.argtypes = [u16p, i64, i64, i32, i32, i32, i32, u64, u64, f32,
                                               u16p]
-        L.nvfp4_46_ref_block_errors.restype = i32
-        L.nvfp4_46_ref_block_errors.argtypes = [u16p, i64, i64, i32, i32, i32, u64, u64, f32,
-                                                f32p, f32p]
+        L.nvfp4_46_ref_block_errors_sel.restype = i32
+        L.nvfp4_46_ref_block_errors_sel.argtypes = [u16p, i64, i64, i32, i32, i32, i32, u64, u64,
+                                                    f32, f32p, f32p]
+        L.ref_block_abs_metric.restype = f32
+        L.ref_block_abs_metric.argtypes = [f32p, f32p, i32]
         L.ref_e2m1_rtn_bits_range.restype = None
         L.ref_e2m1_rtn_bits_range.argtypes = [C.c_uint32, i64, u8p]
         L.ref_e4m3_encode_bits_range.restype = None
@@ -246,15 +248,22 @@ def fake_quant(x_bits: np.ndarray, alpha: float, layout: int = ROWWISE, rounding
     return out
 
 
+def block_abs_metric(v, D, select: int) -> float:
+    a = np.array(v, dtype=np.float32).copy()
+    d = np.array(D, dtype=np.float32).copy()
+    assert a.shape == (16,) and d.shape == (16,)
+    return float(lib().ref_block_abs_metric(_p(a, C.c_float), _p(d, C.c_float), select))
+
+
 def block_errors(x_bits: np.ndarray, alpha: float, layout: int = ROWWISE, rounding: int = RTN,
-                 rht: int = 0, sr_seed: int = 0, rht_seed: int = 0):
+                 rht: int = 0, sr_seed: int = 0, rht_seed: int = 0, select: int = SEL_46_MSE):
     rows, cols = _check_x(x_bits)
     _, ss = _out_shapes(rows, cols, layout)
     E6 = np.zeros(ss, np.float32)
     E4 = np.zeros(ss, np.float32)
-    rc = lib().nvfp4_46_ref_block_errors(_p(x_bits, C.c_uint16), rows, cols, layout, rounding,
-                                         rht, sr_seed, rht_seed, alpha, _p(E6, C.c_float),
-                                         _p(E4, C.c_float))
+    rc = lib().nvfp4_46_ref_block_errors_sel(_p(x_bits, C.c_uint16), rows, cols, layout, rounding,
+                                             select, rht, sr_seed, rht_seed, alpha,
+                                             _p(E6, C.c_float), _p(E4, C.c_float))
     assert rc == 0
     return E6, E4
 
