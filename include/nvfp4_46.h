@@ -62,7 +62,8 @@ enum { NVFP4_ROWWISE = 1, NVFP4_COLWISE = 2 };
 /* rounding of scaled values onto the E2M1 grid */
 enum { NVFP4_RTN = 0, NVFP4_SR = 1 };
 /* how the block scale is chosen */
-enum { NVFP4_SEL_46_MSE = 0, NVFP4_SEL_FORCE6 = 1, NVFP4_SEL_FORCE4 = 2 };
+enum { NVFP4_SEL_46_MSE = 0, NVFP4_SEL_FORCE6 = 1, NVFP4_SEL_FORCE4 = 2, NVFP4_SEL_46_MAE = 3,
+       NVFP4_SEL_46_ABSMAX = 4 };
 
 typedef struct {
   int64_t rows, cols;  /* logical shape of x                                                  */
@@ -75,7 +76,9 @@ typedef struct {
                           element's flat index row*cols + col.  Both candidates use the same
                           u and the 4-vs-6 decision is taken on the rounded values.            */
   uint32_t select;     /* NVFP4_SEL_46_MSE: keep 4 iff its squared error is strictly
-                          smaller (Table 3 line 13).  FORCE6 = standard NVFP4.                 */
+                          smaller (Table 3 line 13).  FORCE6 = standard NVFP4.  _46_MAE /
+                          _46_ABSMAX: the same with the sum of |D_i - x_i| or the largest
+                          |D_i - x_i| as the error (the other rules of Section 3.1, Table 4). */
   uint32_t rht;        /* 1: apply the 16-point random Hadamard transform (Section 2.2) to
                           each block before anything else: y = (1/4) H16 (s .* x), Sylvester
                           ordering, s_j = -1 iff bit j of word 0 of Philox4x32-10(key =

@@ -17,7 +17,7 @@ _PKG = Path(__file__).resolve().parent
 
 ROWWISE, COLWISE, BOTH = 1, 2, 3
 RTN, SR = 0, 1
-SEL_46_MSE, SEL_FORCE6, SEL_FORCE4 = 0, 1, 2
+SEL_46_MSE, SEL_FORCE6, SEL_FORCE4, SEL_46_MAE, SEL_46_ABSMAX = 0, 1, 2, 3, 4
 
 STATUS_NAMES = {0: "NVFP4_OK", 1: "NVFP4_ERR_NULL", 2: "NVFP4_ERR_SHAPE", 3: "NVFP4_ERR_ALIGN",
                 4: "NVFP4_ERR_PARAM", 5: "NVFP4_ERR_UNSUPPORTED", 6: "NVFP4_ERR_HIP"}

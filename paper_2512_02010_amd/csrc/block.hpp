@@ -7,7 +7,9 @@
 namespace nvfp4_46 {
 
 enum : int { kRTN = 0, kSR = 1 };
-enum : int { kSel46 = 0, kSelForce6 = 1, kSelForce4 = 2 };
+enum : int { kSel46 = 0, kSelForce6 = 1, kSelForce4 = 2, kSel46Mae = 3, kSel46AbsMax = 4 };
+// what candidate() returns besides the codes
+enum : int { kErrNone = 0, kErrMseEstimate = 1, kErrMae = 2, kErrAbsMax = 3 };
 
 // (dec, enc) for every E4M3 scale byte under one tensor scale:
 //   dec = value(S) * alpha   -- what one unit of code is worth (Table 3 line 5)
@@ -110,7 +112,7 @@ NV_DEV void grid8(uint32_t codes, float (&g)[8]) {
 // error: d' = fma(g, dec, -v) and a running fma(d', d', E'), i.e. two instructions per
 // element where the defining sequence (product, difference, square, tree sum, each
 // rounded) takes four.  E' is only ever used through decide_four() below.
-template <int ROUNDING, bool WANT_ERROR>
+template <int ROUNDING, int ERR>
 NV_DEV float candidate(const float (&v)[16], const float (&u)[16], float dec, float enc,
                        uint32_t &lo, uint32_t &hi) {
   uint32_t c[2] = {0u, 0u};
@@ -127,7 +129,7 @@ NV_DEV float candidate(const float (&v)[16], const float (&u)[16], float dec, fl
 #pragma unroll
       for (int j = 0; j < 4; ++j)
         w = hw_pk_fp4_sel(w, v[8 * h + 2 * j] * enc, v[8 * h + 2 * j + 1] * enc, j);
-      if (WANT_ERROR) grid8(w, g);
+      if (ERR != kErrNone) grid8(w, g);
       c[h] = w;
     } else if (ROUNDING == kSR) {
       // the rounded values are on the grid, so the conversion that packs them is exact
@@ -155,17 +157,33 @@ NV_DEV float candidate(const float (&v)[16], const float (&u)[16], float dec, fl
         c[h] |= k << (4 * j);
       }
     }
-    if (WANT_ERROR) {
+    if (ERR == kErrMseEstimate) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const float d = __builtin_fmaf(g[j], dec, -v[8 * h + j]);
         acc[j & 1] = __builtin_fmaf(d, d, acc[j & 1]);
       }
     }
+    if (ERR == kErrMae || ERR == kErrAbsMax) {
+      // the other two rules of Section 3.1 are cheap enough to evaluate as defined:
+      // D = fl(g*dec), d = fl(D - v), then the fixed-order sum of |d| or the largest |d|
+      float e[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float D = g[j] * dec;
+        e[j] = fabsf(D - v[8 * h + j]);
+      }
+      if (ERR == kErrMae) {
+        acc[h] = ((e[0] + e[4]) + (e[2] + e[6])) + ((e[1] + e[5]) + (e[3] + e[7]));
+      } else {
+        acc[h] = fmaxf(fmaxf(fmaxf(e[0], e[1]), fmaxf(e[2], e[3])),
+                       fmaxf(fmaxf(e[4], e[5]), fmaxf(e[6], e[7])));
+      }
+    }
   }
   lo = c[0];
   hi = c[1];
-  return acc[0] + acc[1];
+  return ERR == kErrAbsMax ? fmaxf(acc[0], acc[1]) : acc[0] + acc[1];
 }
 
 // The block's squared error exactly as it is defined (Table 3 lines 5-6 / 11-12 in fp32):
@@ -286,7 +304,9 @@ NV_DEV BlockResult quantize_block(const float (&v)[16], const float (&u)[16],
     if (SELECT != kSelForce6) S4 = e4m3_encode(b / k.c4);
   }
 
-  constexpr bool kBoth = SELECT == kSel46;
+  constexpr int kErr = SELECT == kSel46 ? kErrMseEstimate
+                       : SELECT == kSel46Mae ? kErrMae
+                       : SELECT == kSel46AbsMax ? kErrAbsMax : kErrNone;
   BlockResult r6{}, r4{};
   float E6p = 0.0f, E4p = 0.0f;
   if (SELECT != kSelForce4) {
@@ -294,17 +314,18 @@ NV_DEV BlockResult quantize_block(const float (&v)[16], const float (&u)[16],
     r6.scale = S6;
     r6.dec = t.x;
     r6.four = 0u;
-    E6p = candidate<ROUNDING, kBoth>(v, u, t.x, t.y, r6.lo, r6.hi);
+    E6p = candidate<ROUNDING, kErr>(v, u, t.x, t.y, r6.lo, r6.hi);
   }
   if (SELECT != kSelForce6) {
     float2 t = tab.e[S4];
     r4.scale = S4;
     r4.dec = t.x;
     r4.four = 1u;
-    E4p = candidate<ROUNDING, kBoth>(v, u, t.x, t.y, r4.lo, r4.hi);
+    E4p = candidate<ROUNDING, kErr>(v, u, t.x, t.y, r4.lo, r4.hi);
   }
   if (SELECT == kSelForce6) return r6;
   if (SELECT == kSelForce4) return r4;
+  if (SELECT == kSel46Mae || SELECT == kSel46AbsMax) return (E4p < E6p) ? r4 : r6;   // as defined
   return decide_four(v, E6p, E4p, r6.dec, r4.dec, r6.lo, r6.hi, r4.lo, r4.hi) ? r4 : r6;
 }
 

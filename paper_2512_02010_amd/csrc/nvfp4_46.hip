@@ -684,8 +684,12 @@ static void launch_flat_sel(const FlatArgs &a, uint32_t select, bool rht, int ou
     launch_flat_rht<ROUNDING, kSel46>(a, rht, out);
   else if (select == NVFP4_SEL_FORCE6)
     launch_flat_rht<ROUNDING, kSelForce6>(a, rht, out);
-  else
+  else if (select == NVFP4_SEL_FORCE4)
     launch_flat_rht<ROUNDING, kSelForce4>(a, rht, out);
+  else if (select == NVFP4_SEL_46_MAE)
+    launch_flat_rht<ROUNDING, kSel46Mae>(a, rht, out);
+  else
+    launch_flat_rht<ROUNDING, kSel46AbsMax>(a, rht, out);
 }
 
 static void dispatch_flat(const FlatArgs &a, uint32_t rounding, uint32_t select, bool rht, int out) {
@@ -736,11 +740,15 @@ static void dispatch_tile(const TileArgs &a, uint32_t rounding, uint32_t select,
   if (rounding == NVFP4_SR) {
     if (select == NVFP4_SEL_46_MSE) launch_tile_variant<kSR, kSel46>(a, variant);
     else if (select == NVFP4_SEL_FORCE6) launch_tile_variant<kSR, kSelForce6>(a, variant);
-    else launch_tile_variant<kSR, kSelForce4>(a, variant);
+    else if (select == NVFP4_SEL_FORCE4) launch_tile_variant<kSR, kSelForce4>(a, variant);
+    else if (select == NVFP4_SEL_46_MAE) launch_tile_variant<kSR, kSel46Mae>(a, variant);
+    else launch_tile_variant<kSR, kSel46AbsMax>(a, variant);
   } else {
     if (select == NVFP4_SEL_46_MSE) launch_tile_variant<kRTN, kSel46>(a, variant);
     else if (select == NVFP4_SEL_FORCE6) launch_tile_variant<kRTN, kSelForce6>(a, variant);
-    else launch_tile_variant<kRTN, kSelForce4>(a, variant);
+    else if (select == NVFP4_SEL_FORCE4) launch_tile_variant<kRTN, kSelForce4>(a, variant);
+    else if (select == NVFP4_SEL_46_MAE) launch_tile_variant<kRTN, kSel46Mae>(a, variant);
+    else launch_tile_variant<kRTN, kSel46AbsMax>(a, variant);
   }
 }
 
@@ -750,7 +758,7 @@ static int check_params(const void *x, const nvfp4_46_params *p, bool one_layout
   if (p->rows <= 0 || p->cols <= 0) return NVFP4_ERR_SHAPE;
   if (p->layout < 1u || p->layout > 3u) return NVFP4_ERR_PARAM;
   if (one_layout_only && p->layout == 3u) return NVFP4_ERR_PARAM;
-  if (p->rounding > NVFP4_SR || p->select > NVFP4_SEL_FORCE4 || p->rht > 1u || p->reserved != 0u)
+  if (p->rounding > NVFP4_SR || p->select > NVFP4_SEL_46_ABSMAX || p->rht > 1u || p->reserved != 0u)
     return NVFP4_ERR_PARAM;
   if (!(p->fp8_max > 0.0f) || !(p->fp8_max <= 448.0f)) return NVFP4_ERR_PARAM;
   if ((p->layout & NVFP4_ROWWISE) && (p->cols % 16) != 0) return NVFP4_ERR_SHAPE;

@@ -103,7 +103,8 @@ def test_both_layouts_one_pass_small(shape):
 
 
 @pytest.mark.parametrize("layout", [B.ROWWISE, B.COLWISE])
-@pytest.mark.parametrize("select", [B.SEL_46_MSE, B.SEL_FORCE6, B.SEL_FORCE4])
+@pytest.mark.parametrize("select", [B.SEL_46_MSE, B.SEL_FORCE6, B.SEL_FORCE4, B.SEL_46_MAE,
+                                    B.SEL_46_ABSMAX])
 @pytest.mark.parametrize("rounding", [B.RTN, B.SR])
 @pytest.mark.parametrize("rht", [0, 1])
 def test_option_matrix(layout, select, rounding, rht):
@@ -144,6 +145,18 @@ def test_decision_on_ties_and_near_ties(layout, rounding):
     out = check_case(x, layout=layout, rounding=rounding, tag="decision-stress")
     frac4 = float(_np(out["choice_row"]).mean())
     assert 0.02 < frac4 < 0.9
+
+
+@pytest.mark.parametrize("select", [B.SEL_46_MAE, B.SEL_46_ABSMAX])
+@pytest.mark.parametrize("name,layout", [("c2", B.ROWWISE), ("c3", B.ROWWISE), ("c4", B.BOTH)])
+def test_other_selection_rules(name, layout, select):
+    # the mean-absolute-error and largest-absolute-error rules of Section 3.1 / Table 4
+    x = wl.make(name, 1024, 2048)
+    out = check_case(x, layout=layout, select=select, tag=f"{name}-sel{select}")
+    frac4 = float(_np(out["choice_row"]).mean())
+    assert 0.02 < frac4 < 0.9
+    check_case(wl.adversarial("decision_stress", 256, 512), layout=layout, select=select,
+               tag=f"stress-sel{select}")
 
 
 def test_caller_supplied_alpha_replays_table3():
