@@ -60,7 +60,7 @@ typedef enum {
 /* layout bits; NVFP4_ROWWISE | NVFP4_COLWISE = both outputs from one read of x */
 enum { NVFP4_ROWWISE = 1, NVFP4_COLWISE = 2 };
 /* rounding of scaled values onto the E2M1 grid */
-enum { NVFP4_RTN = 0, NVFP4_SR = 1 };
+enum { NVFP4_RTN = 0, NVFP4_SR = 1, NVFP4_SR_AFTER_RTN_SELECT = 2 };
 /* how the block scale is chosen */
 enum { NVFP4_SEL_46_MSE = 0, NVFP4_SEL_FORCE6 = 1, NVFP4_SEL_FORCE4 = 2, NVFP4_SEL_46_MAE = 3,
        NVFP4_SEL_46_ABSMAX = 4 };
@@ -74,7 +74,10 @@ typedef struct {
                           u < (a-lo)/(hi-lo), where u = (w >> 8) * 2^-24 and w is word (g&3)
                           of Philox4x32-10(key = sr_seed, counter = (g>>2, 0, 0)), g = the
                           element's flat index row*cols + col.  Both candidates use the same
-                          u and the 4-vs-6 decision is taken on the rounded values.            */
+                          u and the 4-vs-6 decision is taken on the rounded values.
+                          NVFP4_SR_AFTER_RTN_SELECT (Appendix A.3, second alternative): the
+                          4-vs-6 decision is taken on round-to-nearest candidates, then the
+                          block is rounded stochastically (same u) with the selected scale.    */
   uint32_t select;     /* NVFP4_SEL_46_MSE: keep 4 iff its squared error is strictly
                           smaller (Table 3 line 13).  FORCE6 = standard NVFP4.  _46_MAE /
                           _46_ABSMAX: the same with the sum of |D_i - x_i| or the largest

@@ -21,7 +21,9 @@
  *     error, the rule Section 4.1 and Appendix A.1 recommend for pre-training, and
  *     largest absolute error);
  *   - stochastic rounding of gradients with selection on the rounded values
- *     ("biased selection"): Section 2.2, Section 4.1, Appendix A.3;
+ *     ("biased selection"): Section 2.2, Section 4.1, Appendix A.3; and the
+ *     appendix's second alternative, selection on round-to-nearest candidates
+ *     followed by stochastic rounding with the selected scale;
  *   - 16-point random Hadamard transform: named in Section 2.2 / 4.1 / Fig. 3.
  *
  * Where the paper fixes no detail (tie rules, operation order, overflow,
@@ -47,7 +49,7 @@
 
 #define BLOCK 16
 
-enum { REF_RTN = 0, REF_SR = 1 };
+enum { REF_RTN = 0, REF_SR = 1, REF_SR_AFTER_RTN_SELECT = 2 };
 enum { REF_SEL_46_MSE = 0, REF_SEL_FORCE6 = 1, REF_SEL_FORCE4 = 2, REF_SEL_46_MAE = 3,
        REF_SEL_46_ABSMAX = 4 };
 enum { REF_ROWWISE = 1, REF_COLWISE = 2 };
@@ -310,13 +312,16 @@ void ref_quantize_block(const float v[BLOCK], float alpha, int rounding, int sel
   float D6[BLOCK], D4[BLOCK];
   uint8_t S6 = 0, S4 = 0;
   E[0] = E[1] = 0.0f;
+  /* Appendix A.3, second alternative: the candidates that are compared are rounded to
+   * nearest, and only the winner is then rounded stochastically (below). */
+  int cand_rounding = (rounding == REF_SR_AFTER_RTN_SELECT) ? REF_RTN : rounding;
   if (select != REF_SEL_FORCE4) {
     S6 = ref_block_scale(b, alpha, 6.0f);
-    E[0] = ref_block_with_scale(v, alpha, S6, rounding, u, q6, D6);
+    E[0] = ref_block_with_scale(v, alpha, S6, cand_rounding, u, q6, D6);
   }
   if (select != REF_SEL_FORCE6) {
     S4 = ref_block_scale(b, alpha, 4.0f);
-    E[1] = ref_block_with_scale(v, alpha, S4, rounding, u, q4, D4);
+    E[1] = ref_block_with_scale(v, alpha, S4, cand_rounding, u, q4, D4);
   }
   if (select == REF_SEL_46_MAE || select == REF_SEL_46_ABSMAX) {
     E[0] = ref_block_abs_metric(v, D6, select);
@@ -333,6 +338,8 @@ void ref_quantize_block(const float v[BLOCK], float alpha, int rounding, int sel
   memcpy(D_out, four ? D4 : D6, BLOCK * sizeof(float));
   *S_out = four ? S4 : S6;
   *four_out = (uint8_t)four;
+  if (rounding == REF_SR_AFTER_RTN_SELECT)
+    (void)ref_block_with_scale(v, alpha, *S_out, REF_SR, u, q_out, D_out);
 }
 
 /* ---------------------------------------------------------- whole tensors */
@@ -407,7 +414,7 @@ int nvfp4_46_ref_quantize(const uint16_t *x, int64_t rows, int64_t cols, int lay
       uint8_t q[BLOCK], S, four;
       fetch_block(x, rows, cols, layout, line, blk, rht, rht_seed, v, g);
       for (int i = 0; i < BLOCK; ++i)
-        u[i] = (rounding == REF_SR) ? ref_sr_uniform(sr_seed, g[i]) : 0.0f;
+        u[i] = (rounding != REF_RTN) ? ref_sr_uniform(sr_seed, g[i]) : 0.0f;
       ref_quantize_block(v, alpha, rounding, select, u, q, D, &S, &four, E);
       if (codes)
         for (int i = 0; i < BLOCK; i += 2)
@@ -467,7 +474,7 @@ int nvfp4_46_ref_block_errors_sel(const uint16_t *x, int64_t rows, int64_t cols,
       uint8_t q[BLOCK], S, four;
       fetch_block(x, rows, cols, layout, line, blk, rht, rht_seed, v, g);
       for (int i = 0; i < BLOCK; ++i)
-        u[i] = (rounding == REF_SR) ? ref_sr_uniform(sr_seed, g[i]) : 0.0f;
+        u[i] = (rounding != REF_RTN) ? ref_sr_uniform(sr_seed, g[i]) : 0.0f;
       ref_quantize_block(v, alpha, rounding, select, u, q, D, &S, &four, E);
       E6[line * NB + blk] = E[0];
       E4[line * NB + blk] = E[1];

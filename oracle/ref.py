@@ -20,7 +20,7 @@ _HERE = Path(__file__).resolve().parent
 _SRC = _HERE / "nvfp4_46_ref.c"
 _SO = _HERE / "libnvfp4_46_ref.so"
 
-RTN, SR = 0, 1
+RTN, SR, SR_AFTER_RTN_SELECT = 0, 1, 2
 SEL_46_MSE, SEL_FORCE6, SEL_FORCE4, SEL_46_MAE, SEL_46_ABSMAX = 0, 1, 2, 3, 4
 ROWWISE, COLWISE = 1, 2
 

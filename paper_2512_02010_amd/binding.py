@@ -16,7 +16,7 @@ import torch
 _PKG = Path(__file__).resolve().parent
 
 ROWWISE, COLWISE, BOTH = 1, 2, 3
-RTN, SR = 0, 1
+RTN, SR, SR_AFTER_RTN_SELECT = 0, 1, 2
 SEL_46_MSE, SEL_FORCE6, SEL_FORCE4, SEL_46_MAE, SEL_46_ABSMAX = 0, 1, 2, 3, 4
 
 STATUS_NAMES = {0: "NVFP4_OK", 1: "NVFP4_ERR_NULL", 2: "NVFP4_ERR_SHAPE", 3: "NVFP4_ERR_ALIGN",

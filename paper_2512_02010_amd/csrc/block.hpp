@@ -6,7 +6,7 @@
 
 namespace nvfp4_46 {
 
-enum : int { kRTN = 0, kSR = 1 };
+enum : int { kRTN = 0, kSR = 1, kSRAfterRtnSelect = 2 };
 enum : int { kSel46 = 0, kSelForce6 = 1, kSelForce4 = 2, kSel46Mae = 3, kSel46AbsMax = 4 };
 // what candidate() returns besides the codes
 enum : int { kErrNone = 0, kErrMseEstimate = 1, kErrMae = 2, kErrAbsMax = 3 };
@@ -307,26 +307,38 @@ NV_DEV BlockResult quantize_block(const float (&v)[16], const float (&u)[16],
   constexpr int kErr = SELECT == kSel46 ? kErrMseEstimate
                        : SELECT == kSel46Mae ? kErrMae
                        : SELECT == kSel46AbsMax ? kErrAbsMax : kErrNone;
+  // Appendix A.3's second alternative compares round-to-nearest candidates and rounds
+  // only the winner stochastically.
+  constexpr int kCandRounding = ROUNDING == kSRAfterRtnSelect ? kRTN : ROUNDING;
   BlockResult r6{}, r4{};
-  float E6p = 0.0f, E4p = 0.0f;
+  float E6p = 0.0f, E4p = 0.0f, enc6 = 0.0f, enc4 = 0.0f;
   if (SELECT != kSelForce4) {
     float2 t = tab.e[S6];
     r6.scale = S6;
     r6.dec = t.x;
     r6.four = 0u;
-    E6p = candidate<ROUNDING, kErr>(v, u, t.x, t.y, r6.lo, r6.hi);
+    enc6 = t.y;
+    if (!(ROUNDING == kSRAfterRtnSelect && SELECT == kSelForce6))
+      E6p = candidate<kCandRounding, kErr>(v, u, t.x, t.y, r6.lo, r6.hi);
   }
   if (SELECT != kSelForce6) {
     float2 t = tab.e[S4];
     r4.scale = S4;
     r4.dec = t.x;
     r4.four = 1u;
-    E4p = candidate<ROUNDING, kErr>(v, u, t.x, t.y, r4.lo, r4.hi);
+    enc4 = t.y;
+    if (!(ROUNDING == kSRAfterRtnSelect && SELECT == kSelForce4))
+      E4p = candidate<kCandRounding, kErr>(v, u, t.x, t.y, r4.lo, r4.hi);
   }
-  if (SELECT == kSelForce6) return r6;
-  if (SELECT == kSelForce4) return r4;
-  if (SELECT == kSel46Mae || SELECT == kSel46AbsMax) return (E4p < E6p) ? r4 : r6;   // as defined
-  return decide_four(v, E6p, E4p, r6.dec, r4.dec, r6.lo, r6.hi, r4.lo, r4.hi) ? r4 : r6;
+  bool four;
+  if (SELECT == kSelForce6) four = false;
+  else if (SELECT == kSelForce4) four = true;
+  else if (SELECT == kSel46Mae || SELECT == kSel46AbsMax) four = E4p < E6p;   // as defined
+  else four = decide_four(v, E6p, E4p, r6.dec, r4.dec, r6.lo, r6.hi, r4.lo, r4.hi);
+  BlockResult r = four ? r4 : r6;
+  if (ROUNDING == kSRAfterRtnSelect)
+    (void)candidate<kSR, kErrNone>(v, u, r.dec, four ? enc4 : enc6, r.lo, r.hi);
+  return r;
 }
 
 // Dequantized fp32 values of 8 codes packed in one word: value(code) * dec.

@@ -211,7 +211,7 @@ __global__ __launch_bounds__(kThreads) void k_flat(
       for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(v[i]));
       return;
     }
-    if (ROUNDING == kSR) {
+    if (ROUNDING != kRTN) {
       const uint64_t q0 = ((uint64_t)base + tid) * 4u;
 #pragma unroll
       for (int j = 0; j < 4; ++j) sr_uniforms4(sr_seed, q0 + j, &u[4 * j]);
@@ -401,7 +401,7 @@ __global__ __launch_bounds__(kThreads) void k_tile(
         const uint4 *own = reinterpret_cast<const uint4 *>(tile) + unit * 2;
         unpack16(own[0], own[1], v);
         const int64_t k = gr * nb_per_row + (gc >> 4);
-        if (ROUNDING == kSR) {
+        if (ROUNDING != kRTN) {
 #pragma unroll
           for (int q = 0; q < 4; ++q) sr_uniforms4(sr_seed, (uint64_t)k * 4u + q, &u[4 * q]);
         }
@@ -441,7 +441,7 @@ __global__ __launch_bounds__(kThreads) void k_tile(
       for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fmaxf(fabsf(va[i]), fabsf(vb[i])));
       continue;
     }
-    if (ROUNDING == kSR) {
+    if (ROUNDING != kRTN) {
       // element (row, col) has flat index g = row*cols + col; the pair (gc, gc+1) shares a
       // Philox call because gc is even and cols is a multiple of 4
 #pragma unroll
@@ -695,6 +695,8 @@ static void launch_flat_sel(const FlatArgs &a, uint32_t select, bool rht, int ou
 static void dispatch_flat(const FlatArgs &a, uint32_t rounding, uint32_t select, bool rht, int out) {
   if (rounding == NVFP4_SR)
     launch_flat_sel<kSR>(a, select, rht, out);
+  else if (rounding == NVFP4_SR_AFTER_RTN_SELECT)
+    launch_flat_sel<kSRAfterRtnSelect>(a, select, rht, out);
   else
     launch_flat_sel<kRTN>(a, select, rht, out);
 }
@@ -736,20 +738,19 @@ static void launch_tile_variant(const TileArgs &a, int variant) {
   }
 }
 
+template <int ROUNDING>
+static void launch_tile_sel(const TileArgs &a, uint32_t select, int variant) {
+  if (select == NVFP4_SEL_46_MSE) launch_tile_variant<ROUNDING, kSel46>(a, variant);
+  else if (select == NVFP4_SEL_FORCE6) launch_tile_variant<ROUNDING, kSelForce6>(a, variant);
+  else if (select == NVFP4_SEL_FORCE4) launch_tile_variant<ROUNDING, kSelForce4>(a, variant);
+  else if (select == NVFP4_SEL_46_MAE) launch_tile_variant<ROUNDING, kSel46Mae>(a, variant);
+  else launch_tile_variant<ROUNDING, kSel46AbsMax>(a, variant);
+}
+
 static void dispatch_tile(const TileArgs &a, uint32_t rounding, uint32_t select, int variant) {
-  if (rounding == NVFP4_SR) {
-    if (select == NVFP4_SEL_46_MSE) launch_tile_variant<kSR, kSel46>(a, variant);
-    else if (select == NVFP4_SEL_FORCE6) launch_tile_variant<kSR, kSelForce6>(a, variant);
-    else if (select == NVFP4_SEL_FORCE4) launch_tile_variant<kSR, kSelForce4>(a, variant);
-    else if (select == NVFP4_SEL_46_MAE) launch_tile_variant<kSR, kSel46Mae>(a, variant);
-    else launch_tile_variant<kSR, kSel46AbsMax>(a, variant);
-  } else {
-    if (select == NVFP4_SEL_46_MSE) launch_tile_variant<kRTN, kSel46>(a, variant);
-    else if (select == NVFP4_SEL_FORCE6) launch_tile_variant<kRTN, kSelForce6>(a, variant);
-    else if (select == NVFP4_SEL_FORCE4) launch_tile_variant<kRTN, kSelForce4>(a, variant);
-    else if (select == NVFP4_SEL_46_MAE) launch_tile_variant<kRTN, kSel46Mae>(a, variant);
-    else launch_tile_variant<kRTN, kSel46AbsMax>(a, variant);
-  }
+  if (rounding == NVFP4_SR) launch_tile_sel<kSR>(a, select, variant);
+  else if (rounding == NVFP4_SR_AFTER_RTN_SELECT) launch_tile_sel<kSRAfterRtnSelect>(a, select, variant);
+  else launch_tile_sel<kRTN>(a, select, variant);
 }
 
 // Checks shared by the entry points that take the parameter block.
@@ -758,7 +759,7 @@ static int check_params(const void *x, const nvfp4_46_params *p, bool one_layout
   if (p->rows <= 0 || p->cols <= 0) return NVFP4_ERR_SHAPE;
   if (p->layout < 1u || p->layout > 3u) return NVFP4_ERR_PARAM;
   if (one_layout_only && p->layout == 3u) return NVFP4_ERR_PARAM;
-  if (p->rounding > NVFP4_SR || p->select > NVFP4_SEL_46_ABSMAX || p->rht > 1u || p->reserved != 0u)
+  if (p->rounding > NVFP4_SR_AFTER_RTN_SELECT || p->select > NVFP4_SEL_46_ABSMAX || p->rht > 1u || p->reserved != 0u)
     return NVFP4_ERR_PARAM;
   if (!(p->fp8_max > 0.0f) || !(p->fp8_max <= 448.0f)) return NVFP4_ERR_PARAM;
   if ((p->layout & NVFP4_ROWWISE) && (p->cols % 16) != 0) return NVFP4_ERR_SHAPE;

@@ -105,7 +105,7 @@ def test_both_layouts_one_pass_small(shape):
 @pytest.mark.parametrize("layout", [B.ROWWISE, B.COLWISE])
 @pytest.mark.parametrize("select", [B.SEL_46_MSE, B.SEL_FORCE6, B.SEL_FORCE4, B.SEL_46_MAE,
                                     B.SEL_46_ABSMAX])
-@pytest.mark.parametrize("rounding", [B.RTN, B.SR])
+@pytest.mark.parametrize("rounding", [B.RTN, B.SR, B.SR_AFTER_RTN_SELECT])
 @pytest.mark.parametrize("rht", [0, 1])
 def test_option_matrix(layout, select, rounding, rht):
     check_case(wl.make("c5", 160, 304), layout=layout, rounding=rounding, select=select, rht=rht,
@@ -157,6 +157,15 @@ def test_other_selection_rules(name, layout, select):
     assert 0.02 < frac4 < 0.9
     check_case(wl.adversarial("decision_stress", 256, 512), layout=layout, select=select,
                tag=f"stress-sel{select}")
+
+
+@pytest.mark.parametrize("name,layout", [("c5", B.ROWWISE), ("c3", B.COLWISE), ("c4", B.BOTH)])
+def test_sr_after_rtn_selection(name, layout):
+    # Appendix A.3, second alternative: choose from round-to-nearest candidates, then SR
+    x = wl.make(name, 512, 1024)
+    check_case(x, layout=layout, rounding=B.SR_AFTER_RTN_SELECT, tag=f"{name}-sr-after-rtn")
+    check_case(wl.adversarial("decision_stress", 256, 512), layout=layout,
+               rounding=B.SR_AFTER_RTN_SELECT, tag="stress-sr-after-rtn")
 
 
 def test_caller_supplied_alpha_replays_table3():
