@@ -24,7 +24,8 @@
  *     ("biased selection"): Section 2.2, Section 4.1, Appendix A.3; and the
  *     appendix's second alternative, selection on round-to-nearest candidates
  *     followed by stochastic rounding with the selected scale;
- *   - 16-point random Hadamard transform: named in Section 2.2 / 4.1 / Fig. 3.
+ *   - 16-point random Hadamard transform: named in Section 2.2 / 4.1 / Fig. 3;
+ *   - 2D (16x16) block quantization of weight matrices: named in Section 4.1.
  *
  * Where the paper fixes no detail (tie rules, operation order, overflow,
  * nibble order, the random-number construction, the Hadamard ordering) the
@@ -423,6 +424,92 @@ int nvfp4_46_ref_quantize(const uint16_t *x, int64_t rows, int64_t cols, int lay
       if (choice) choice[line * NB + blk] = four;
       if (deq)
         for (int i = 0; i < BLOCK; ++i) deq[g[i]] = ref_f32_to_bf16(D[i]);
+    }
+  return 0;
+}
+
+/* 2D block quantization of weight matrices (named in Section 4.1 as part of the
+ * training recipe; READING throughout): one E4M3 scale per 16x16 tile instead of one per
+ * 16 values of a row, so that a matrix and its transpose are quantized consistently.  The
+ * tile is treated as sixteen row blocks that share their scale:
+ *   b      = largest magnitude of the 256 values;  S_M = e4m3(b / (alpha*M))   (Eq. 2)
+ *   each row of the tile is quantized with S_M exactly as a 1x16 block is (Eq. 3)
+ *   E_M    = the sixteen row errors added in the same fixed order in which a row adds
+ *            its sixteen element errors (for the largest-absolute-error rule: their
+ *            maximum)
+ *   keep M = 4 iff E_4 < E_6.
+ * Outputs: codes [rows][cols/2] packed along rows as in the rowwise layout, scales and
+ * choice [rows/16][cols/16], deq [rows][cols] (each optional).  With
+ * REF_SR_AFTER_RTN_SELECT the tile is chosen from round-to-nearest candidates and then
+ * rounded stochastically; uniforms are those of the elements' flat indices. */
+int nvfp4_46_ref_quantize_2d(const uint16_t *x, int64_t rows, int64_t cols, int rounding,
+                             int select, uint64_t sr_seed, float alpha, uint8_t *codes,
+                             uint8_t *scales, uint8_t *choice, uint16_t *deq) {
+  int64_t TR = rows / BLOCK, TCB = cols / BLOCK;
+#pragma omp parallel for schedule(static)
+  for (int64_t tr = 0; tr < TR; ++tr)
+    for (int64_t tc = 0; tc < TCB; ++tc) {
+      float v[BLOCK][BLOCK], u[BLOCK][BLOCK];
+      float b = 0.0f;
+      for (int r = 0; r < BLOCK; ++r)
+        for (int c = 0; c < BLOCK; ++c) {
+          uint64_t g = (uint64_t)(tr * BLOCK + r) * (uint64_t)cols + (uint64_t)(tc * BLOCK + c);
+          v[r][c] = ref_bf16_to_f32(x[g]);
+          u[r][c] = (rounding != REF_RTN) ? ref_sr_uniform(sr_seed, g) : 0.0f;
+          float a = fabsf(v[r][c]);
+          if (a > b) b = a;
+        }
+      int cand_rounding = (rounding == REF_SR_AFTER_RTN_SELECT) ? REF_RTN : rounding;
+      uint8_t S[2] = {0, 0}, q[2][BLOCK][BLOCK];
+      float D[2][BLOCK][BLOCK], E[2] = {0.0f, 0.0f};
+      for (int m = 0; m < 2; ++m) {
+        if ((m == 0 && select == REF_SEL_FORCE4) || (m == 1 && select == REF_SEL_FORCE6)) continue;
+        S[m] = ref_block_scale(b, alpha, m == 0 ? 6.0f : 4.0f);
+        float rowerr[BLOCK];
+        for (int r = 0; r < BLOCK; ++r) {
+          rowerr[r] = ref_block_with_scale(v[r], alpha, S[m], cand_rounding, u[r], q[m][r], D[m][r]);
+          if (select == REF_SEL_46_MAE || select == REF_SEL_46_ABSMAX)
+            rowerr[r] = ref_block_abs_metric(v[r], D[m][r], select);
+        }
+        if (select == REF_SEL_46_ABSMAX) {
+          E[m] = 0.0f;
+          for (int r = 0; r < BLOCK; ++r)
+            if (rowerr[r] > E[m]) E[m] = rowerr[r];
+        } else {
+          E[m] = error_sum(rowerr);
+        }
+      }
+      int four = (select == REF_SEL_FORCE6) ? 0 : (select == REF_SEL_FORCE4) ? 1 : (E[1] < E[0]);
+      if (rounding == REF_SR_AFTER_RTN_SELECT)
+        for (int r = 0; r < BLOCK; ++r)
+          (void)ref_block_with_scale(v[r], alpha, S[four], REF_SR, u[r], q[four][r], D[four][r]);
+      if (scales) scales[tr * TCB + tc] = S[four];
+      if (choice) choice[tr * TCB + tc] = (uint8_t)four;
+      for (int r = 0; r < BLOCK; ++r) {
+        int64_t row = tr * BLOCK + r;
+        if (codes)
+          for (int c = 0; c < BLOCK; c += 2)
+            codes[row * (cols / 2) + tc * (BLOCK / 2) + c / 2] =
+                (uint8_t)(q[four][r][c] | (q[four][r][c + 1] << 4));
+        if (deq)
+          for (int c = 0; c < BLOCK; ++c)
+            deq[row * cols + tc * BLOCK + c] = ref_f32_to_bf16(D[four][r][c]);
+      }
+    }
+  return 0;
+}
+
+/* Dequantize 2D-block data: scales [rows/16][cols/16], codes as above. */
+int nvfp4_46_ref_dequantize_2d(const uint8_t *codes, const uint8_t *scales, float alpha,
+                               int64_t rows, int64_t cols, uint16_t *out) {
+  int64_t TCB = cols / BLOCK;
+#pragma omp parallel for schedule(static)
+  for (int64_t r = 0; r < rows; ++r)
+    for (int64_t c = 0; c < cols; ++c) {
+      float dec = ref_e4m3_decode(scales[(r / BLOCK) * TCB + c / BLOCK]) * alpha;
+      uint8_t byte = codes[r * (cols / 2) + c / 2];
+      uint8_t code = (c & 1) ? (byte >> 4) : (byte & 15);
+      out[r * cols + c] = ref_f32_to_bf16(ref_e2m1_decode(code) * dec);
     }
   return 0;
 }

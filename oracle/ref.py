@@ -80,6 +80,11 @@ def lib() -> C.CDLL:
                                                     f32, f32p, f32p]
         L.ref_block_abs_metric.restype = f32
         L.ref_block_abs_metric.argtypes = [f32p, f32p, i32]
+        L.nvfp4_46_ref_quantize_2d.restype = i32
+        L.nvfp4_46_ref_quantize_2d.argtypes = [u16p, i64, i64, i32, i32, u64, f32, u8p, u8p, u8p,
+                                               u16p]
+        L.nvfp4_46_ref_dequantize_2d.restype = i32
+        L.nvfp4_46_ref_dequantize_2d.argtypes = [u8p, u8p, f32, i64, i64, u16p]
         L.ref_e2m1_rtn_bits_range.restype = None
         L.ref_e2m1_rtn_bits_range.argtypes = [C.c_uint32, i64, u8p]
         L.ref_e4m3_encode_bits_range.restype = None
@@ -266,6 +271,32 @@ def block_errors(x_bits: np.ndarray, alpha: float, layout: int = ROWWISE, roundi
                                              _p(E6, C.c_float), _p(E4, C.c_float))
     assert rc == 0
     return E6, E4
+
+
+def quantize_2d(x_bits: np.ndarray, alpha: float, rounding: int = RTN, select: int = SEL_46_MSE,
+                sr_seed: int = 0):
+    """16x16-tile quantization: (codes [rows][cols/2], scales, choice [rows/16][cols/16], deq)."""
+    rows, cols = _check_x(x_bits)
+    assert rows % 16 == 0 and cols % 16 == 0
+    codes = np.zeros((rows, cols // 2), np.uint8)
+    scales = np.zeros((rows // 16, cols // 16), np.uint8)
+    choice = np.zeros((rows // 16, cols // 16), np.uint8)
+    deq = np.zeros((rows, cols), np.uint16)
+    rc = lib().nvfp4_46_ref_quantize_2d(_p(x_bits, C.c_uint16), rows, cols, rounding, select,
+                                        sr_seed, alpha, _p(codes, C.c_uint8), _p(scales, C.c_uint8),
+                                        _p(choice, C.c_uint8), _p(deq, C.c_uint16))
+    assert rc == 0
+    return codes, scales, choice, deq
+
+
+def dequantize_2d(codes: np.ndarray, scales: np.ndarray, alpha: float, rows: int,
+                  cols: int) -> np.ndarray:
+    assert codes.shape == (rows, cols // 2) and scales.shape == (rows // 16, cols // 16)
+    out = np.zeros((rows, cols), np.uint16)
+    rc = lib().nvfp4_46_ref_dequantize_2d(_p(codes, C.c_uint8), _p(scales, C.c_uint8), alpha, rows,
+                                          cols, _p(out, C.c_uint16))
+    assert rc == 0
+    return out
 
 
 def e2m1_rtn_bits_range(first_bits: int, n: int) -> np.ndarray:
