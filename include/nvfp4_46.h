@@ -57,8 +57,10 @@ typedef enum {
   NVFP4_ERR_HIP = 6          /* the HIP runtime reported a launch error                      */
 } nvfp4_status;
 
-/* layout bits; NVFP4_ROWWISE | NVFP4_COLWISE = both outputs from one read of x */
-enum { NVFP4_ROWWISE = 1, NVFP4_COLWISE = 2 };
+/* layout bits; NVFP4_ROWWISE | NVFP4_COLWISE = both outputs from one read of x.
+ * NVFP4_BLOCK2D is only a value of nvfp4_46_dequantize's `layout` argument: data written
+ * with nvfp4_46_params.block2d = 1 (codes [rows][cols/2], scales [rows/16][cols/16]). */
+enum { NVFP4_ROWWISE = 1, NVFP4_COLWISE = 2, NVFP4_BLOCK2D = 4 };
 /* rounding of scaled values onto the E2M1 grid */
 enum { NVFP4_RTN = 0, NVFP4_SR = 1, NVFP4_SR_AFTER_RTN_SELECT = 2 };
 /* how the block scale is chosen */
@@ -90,7 +92,15 @@ typedef struct {
   uint64_t sr_seed, rht_seed;
   float fp8_max;       /* the FP8 constant of Eq. (1): 256 for 4/6 (Section 3.1), 448 for
                           standard NVFP4                                                       */
-  uint32_t reserved;   /* must be 0                                                            */
+  uint32_t block2d;    /* 1: one scale (and one 4-vs-6 choice) per 16x16 tile instead of per 16
+                          values of a row -- the 2D block quantization of weight matrices that
+                          Section 4.1 names, under which a matrix and its transpose get the
+                          same scales.  The tile's maximum sets the two candidate scales, each
+                          row of the tile is quantized with them, and the tile's error is the
+                          sum (largest, for _ABSMAX) of its sixteen row errors in the same
+                          fixed order as within a row.  Needs layout = NVFP4_ROWWISE, rht = 0,
+                          rows % 16 == cols % 16 == 0; codes_row is [rows][cols/2] as usual,
+                          scales_row and choice_row are [rows/16][cols/16].                   */
 } nvfp4_46_params;
 
 /* Eq. (1) with Section 3.1's constant: alpha = max|v| / (6 * fp8_max) over the values
@@ -120,10 +130,11 @@ int nvfp4_46_quantize(const void *x_bf16, const nvfp4_46_params *p, const float 
                       void *choice_row, void *choice_col, void *stream);
 
 /* Table 3 lines 5 / 11 on stored data: out = bf16_rne(value(code) * (value(scale) * alpha)).
- *   codes, scales  in   in the layout named by `layout` (NVFP4_ROWWISE or NVFP4_COLWISE)
+ *   codes, scales  in   in the layout named by `layout` (NVFP4_ROWWISE, NVFP4_COLWISE or
+ *                       NVFP4_BLOCK2D)
  *   out            out  [rows][cols] BF16, always row-major in the tensor's own orientation
  * Errors: NULL pointer -> ERR_NULL; bad dims -> ERR_SHAPE; misaligned -> ERR_ALIGN;
- * layout not exactly one orientation -> ERR_PARAM.                                    */
+ * layout not one of the three values -> ERR_PARAM.                                    */
 int nvfp4_46_dequantize(const void *codes, const void *scales, const float *alpha, int64_t rows,
                         int64_t cols, uint32_t layout, void *out_bf16, void *stream);
 

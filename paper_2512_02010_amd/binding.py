@@ -16,6 +16,7 @@ import torch
 _PKG = Path(__file__).resolve().parent
 
 ROWWISE, COLWISE, BOTH = 1, 2, 3
+BLOCK2D = 4          # nvfp4_46_dequantize's layout value for 16x16-tile data
 RTN, SR, SR_AFTER_RTN_SELECT = 0, 1, 2
 SEL_46_MSE, SEL_FORCE6, SEL_FORCE4, SEL_46_MAE, SEL_46_ABSMAX = 0, 1, 2, 3, 4
 
@@ -35,7 +36,7 @@ class Params(C.Structure):
     _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("layout", C.c_uint32),
                 ("rounding", C.c_uint32), ("select", C.c_uint32), ("rht", C.c_uint32),
                 ("sr_seed", C.c_uint64), ("rht_seed", C.c_uint64), ("fp8_max", C.c_float),
-                ("reserved", C.c_uint32)]
+                ("block2d", C.c_uint32)]
 
 
 class Nvfp4Error(RuntimeError):
@@ -95,8 +96,8 @@ def status_string(status: int) -> str:
 
 def make_params(rows: int, cols: int, layout: int = ROWWISE, rounding: int = RTN,
                 select: int = SEL_46_MSE, rht: int = 0, sr_seed: int = 0, rht_seed: int = 0,
-                fp8_max: float = 256.0) -> Params:
-    return Params(rows, cols, layout, rounding, select, rht, sr_seed, rht_seed, fp8_max, 0)
+                fp8_max: float = 256.0, block2d: int = 0) -> Params:
+    return Params(rows, cols, layout, rounding, select, rht, sr_seed, rht_seed, fp8_max, block2d)
 
 
 def _ptr(t):
@@ -162,16 +163,18 @@ def nvfp4_46_tensor_scale(x: torch.Tensor, layout: int = ROWWISE, rht: int = 0, 
     return alpha
 
 
-def alloc_outputs(rows: int, cols: int, layout: int, device, want_choice: bool = True) -> dict:
+def alloc_outputs(rows: int, cols: int, layout: int, device, want_choice: bool = True,
+                  block2d: int = 0) -> dict:
     """uint8 device tensors for nvfp4_46_quantize's outputs in the requested layout(s)."""
     o = dict.fromkeys(("codes_row", "scales_row", "choice_row", "codes_col", "scales_col",
                        "choice_col"))
     u8 = dict(dtype=torch.uint8, device=device)
     if layout & ROWWISE:
+        srows = rows // 16 if block2d else rows
         o["codes_row"] = torch.empty((rows, cols // 2), **u8)
-        o["scales_row"] = torch.empty((rows, cols // 16), **u8)
+        o["scales_row"] = torch.empty((srows, cols // 16), **u8)
         if want_choice:
-            o["choice_row"] = torch.empty((rows, cols // 16), **u8)
+            o["choice_row"] = torch.empty((srows, cols // 16), **u8)
     if layout & COLWISE:
         o["codes_col"] = torch.empty((cols, rows // 2), **u8)
         o["scales_col"] = torch.empty((cols, rows // 16), **u8)
@@ -183,10 +186,13 @@ def alloc_outputs(rows: int, cols: int, layout: int, device, want_choice: bool =
 def nvfp4_46_quantize(x: torch.Tensor, alpha: torch.Tensor, layout: int = ROWWISE,
                       rounding: int = RTN, select: int = SEL_46_MSE, rht: int = 0,
                       sr_seed: int = 0, rht_seed: int = 0, fp8_max: float = 256.0,
-                      want_choice: bool = True, out: dict | None = None, stream=None) -> dict:
+                      want_choice: bool = True, out: dict | None = None, stream=None,
+                      block2d: int = 0) -> dict:
     rows, cols = _shape_of(x)
-    o = out if out is not None else alloc_outputs(rows, cols, layout, x.device, want_choice)
-    p = make_params(rows, cols, layout, rounding, select, rht, sr_seed, rht_seed, fp8_max)
+    o = out if out is not None else alloc_outputs(rows, cols, layout, x.device, want_choice,
+                                                  block2d)
+    p = make_params(rows, cols, layout, rounding, select, rht, sr_seed, rht_seed, fp8_max,
+                    block2d)
     _check(quantize_raw(x, p, alpha, o["codes_row"], o["scales_row"], o["codes_col"],
                         o["scales_col"], o["choice_row"], o["choice_col"], stream),
            "nvfp4_46_quantize")
@@ -206,11 +212,13 @@ def nvfp4_46_dequantize(codes: torch.Tensor, scales: torch.Tensor, alpha: torch.
 def nvfp4_46_fake_quant(x: torch.Tensor, alpha: torch.Tensor, layout: int = ROWWISE,
                         rounding: int = RTN, select: int = SEL_46_MSE, rht: int = 0,
                         sr_seed: int = 0, rht_seed: int = 0, fp8_max: float = 256.0,
-                        out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+                        out: torch.Tensor | None = None, stream=None,
+                        block2d: int = 0) -> torch.Tensor:
     rows, cols = _shape_of(x)
     if out is None:
         out = torch.empty_like(x)
-    p = make_params(rows, cols, layout, rounding, select, rht, sr_seed, rht_seed, fp8_max)
+    p = make_params(rows, cols, layout, rounding, select, rht, sr_seed, rht_seed, fp8_max,
+                    block2d)
     _check(fake_quant_raw(x, p, alpha, out, stream), "nvfp4_46_fake_quant")
     return out
 

@@ -560,6 +560,121 @@ __global__ __launch_bounds__(kThreads) void k_dequant_col(const uint8_t *__restr
   }
 }
 
+// ------------------------------------------------------- 2D (16x16) blocks
+
+// One scale per 16x16 tile (the weight-matrix variant named in Section 4.1).  Sixteen
+// adjacent lanes own the sixteen rows of a tile (one row block each); the tile's
+// maximum, and the two candidates' errors, are combined across those lanes with XOR
+// shuffles.  Errors are evaluated as defined (no estimate): a row's sixteen terms in the
+// usual fixed order, then the sixteen row sums in the same order (strides 4, 2, 1 within
+// each half, then the two halves), which is the order of the shuffles 4, 2, 1, 8.
+// Lane -> (tile, row): lanes 0-15 are the rows of one tile, the next sixteen lanes the
+// tile to its right, so four lanes 16 apart read 128 contiguous bytes of one row.
+template <int ROUNDING, int SELECT, int OUT>
+__global__ __launch_bounds__(kThreads) void k_block2d(
+    const uint16_t *__restrict__ x, const float *__restrict__ alpha_p, uint8_t *__restrict__ codes,
+    uint8_t *__restrict__ scales, uint8_t *__restrict__ choice, uint16_t *__restrict__ out_bf16,
+    int64_t rows, int64_t cols, uint64_t sr_seed) {
+  __shared__ ScaleTable tab;
+  const ScaleConsts sc = build_scale_table(tab, *alpha_p);
+  const uint32_t tid = threadIdx.x, r_in_tile = tid & 15u, grp = tid >> 4;
+  const int64_t ncb = cols / 16, n_tiles = (rows / 16) * ncb;
+  constexpr int kGroups = kThreads / 16;
+  constexpr int kCandRounding = ROUNDING == kSRAfterRtnSelect ? kRTN : ROUNDING;
+  constexpr int kErr = SELECT == kSel46Mae ? kErrMae : SELECT == kSel46AbsMax ? kErrAbsMax : kErrNone;
+  for (int64_t T = (int64_t)blockIdx.x * kGroups + grp; T < n_tiles;
+       T += (int64_t)gridDim.x * kGroups) {
+    const int64_t tr = T / ncb, tc = T - tr * ncb;
+    const int64_t row = tr * 16 + r_in_tile;
+    const int64_t first = row * cols + tc * 16;           // flat index of the lane's first element
+    const uint4 *src = reinterpret_cast<const uint4 *>(x + first);
+    float v[16], u[16];
+    unpack16(src[0], src[1], v);
+    if (ROUNDING != kRTN) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) sr_uniforms4(sr_seed, (uint64_t)(first >> 2) + j, &u[4 * j]);
+    }
+    float b = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) b = fmaxf(fmaxf(b, fabsf(v[i])), fabsf(v[i + 1]));
+#pragma unroll
+    for (int m = 1; m < 16; m <<= 1) b = fmaxf(b, __shfl_xor(b, m, 64));
+
+    BlockResult r6{}, r4{};
+    float E6 = 0.0f, E4 = 0.0f, enc6 = 0.0f, enc4 = 0.0f;
+    if (SELECT != kSelForce4) {
+      r6.scale = e4m3_encode(b / sc.c6);
+      const float2 t = tab.e[r6.scale];
+      r6.dec = t.x;
+      enc6 = t.y;
+      if (!(ROUNDING == kSRAfterRtnSelect && SELECT == kSelForce6)) {
+        E6 = candidate<kCandRounding, kErr>(v, u, t.x, t.y, r6.lo, r6.hi);
+        if (SELECT == kSel46) E6 = exact_error(v, r6.lo, r6.hi, t.x);
+      }
+    }
+    if (SELECT != kSelForce6) {
+      r4.scale = e4m3_encode(b / sc.c4);
+      r4.four = 1u;
+      const float2 t = tab.e[r4.scale];
+      r4.dec = t.x;
+      enc4 = t.y;
+      if (!(ROUNDING == kSRAfterRtnSelect && SELECT == kSelForce4)) {
+        E4 = candidate<kCandRounding, kErr>(v, u, t.x, t.y, r4.lo, r4.hi);
+        if (SELECT == kSel46) E4 = exact_error(v, r4.lo, r4.hi, t.x);
+      }
+    }
+    bool four = SELECT == kSelForce4;
+    if (SELECT == kSel46 || SELECT == kSel46Mae || SELECT == kSel46AbsMax) {
+      constexpr int order[4] = {4, 2, 1, 8};
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const float o6 = __shfl_xor(E6, order[s], 64), o4 = __shfl_xor(E4, order[s], 64);
+        E6 = SELECT == kSel46AbsMax ? fmaxf(E6, o6) : E6 + o6;
+        E4 = SELECT == kSel46AbsMax ? fmaxf(E4, o4) : E4 + o4;
+      }
+      four = E4 < E6;
+    }
+    BlockResult res = four ? r4 : r6;
+    if (ROUNDING == kSRAfterRtnSelect)
+      (void)candidate<kSR, kErrNone>(v, u, res.dec, four ? enc4 : enc6, res.lo, res.hi);
+    if (OUT == kOutCodes) {
+      *reinterpret_cast<uint2 *>(codes + row * (cols / 2) + tc * 8) = make_uint2(res.lo, res.hi);
+      if (r_in_tile == 0) {
+        scales[T] = (uint8_t)res.scale;
+        if (choice) choice[T] = (uint8_t)res.four;
+      }
+    } else {
+      float D0[8], D1[8];
+      dequant8(res.lo, res.dec, D0);
+      dequant8(res.hi, res.dec, D1);
+      uint4 *dst = reinterpret_cast<uint4 *>(out_bf16 + first);
+      dst[0] = make_uint4(pack_bf16x2(D0[0], D0[1]), pack_bf16x2(D0[2], D0[3]),
+                          pack_bf16x2(D0[4], D0[5]), pack_bf16x2(D0[6], D0[7]));
+      dst[1] = make_uint4(pack_bf16x2(D1[0], D1[1]), pack_bf16x2(D1[2], D1[3]),
+                          pack_bf16x2(D1[4], D1[5]), pack_bf16x2(D1[6], D1[7]));
+    }
+  }
+}
+
+// 2D-block data -> BF16: one lane per 8 codes; the scale is the tile's.
+__global__ __launch_bounds__(kThreads) void k_dequant_2d(const uint32_t *__restrict__ codes,
+                                                         const uint8_t *__restrict__ scales,
+                                                         const float *__restrict__ alpha_p,
+                                                         uint4 *__restrict__ out, int64_t n8,
+                                                         int64_t cols) {
+  const float alpha = *alpha_p;
+  const int64_t per_row = cols / 8, ncb = cols / 16;
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x; t < n8; t += stride) {
+    const int64_t row = t / per_row, c8 = t - row * per_row;
+    const float dec = e4m3_decode_sw(scales[(row >> 4) * ncb + (c8 >> 1)]) * alpha;
+    float D[8];
+    dequant8(codes[t], dec, D);
+    store_as<kNtBf16>(out + t, make_uint4(pack_bf16x2(D[0], D[1]), pack_bf16x2(D[2], D[3]),
+                                          pack_bf16x2(D[4], D[5]), pack_bf16x2(D[6], D[7])));
+  }
+}
+
 // ------------------------------------------------------------ debug kernels
 
 __global__ void k_dbg_e2m1_rtn(uint32_t first, int64_t n, uint8_t *out) {
@@ -753,13 +868,52 @@ static void dispatch_tile(const TileArgs &a, uint32_t rounding, uint32_t select,
   else launch_tile_sel<kRTN>(a, select, variant);
 }
 
+struct Block2dArgs {
+  const uint16_t *x;
+  const float *alpha;
+  uint8_t *codes, *scales, *choice;
+  uint16_t *out;
+  int64_t rows, cols;
+  uint64_t sr_seed;
+  hipStream_t stream;
+};
+
+template <int ROUNDING, int SELECT>
+static void launch_block2d(const Block2dArgs &a, int out) {
+  const int64_t tiles = (a.rows / 16) * (a.cols / 16);
+  const int grid = grid_for(tiles * 16, 16);
+  if (out == kOutCodes)
+    hipLaunchKernelGGL((k_block2d<ROUNDING, SELECT, kOutCodes>), dim3(grid), dim3(kThreads), 0,
+                       a.stream, a.x, a.alpha, a.codes, a.scales, a.choice, a.out, a.rows, a.cols,
+                       a.sr_seed);
+  else
+    hipLaunchKernelGGL((k_block2d<ROUNDING, SELECT, kOutFake>), dim3(grid), dim3(kThreads), 0,
+                       a.stream, a.x, a.alpha, a.codes, a.scales, a.choice, a.out, a.rows, a.cols,
+                       a.sr_seed);
+}
+
+template <int ROUNDING>
+static void launch_block2d_sel(const Block2dArgs &a, uint32_t select, int out) {
+  if (select == NVFP4_SEL_46_MSE) launch_block2d<ROUNDING, kSel46>(a, out);
+  else if (select == NVFP4_SEL_FORCE6) launch_block2d<ROUNDING, kSelForce6>(a, out);
+  else if (select == NVFP4_SEL_FORCE4) launch_block2d<ROUNDING, kSelForce4>(a, out);
+  else if (select == NVFP4_SEL_46_MAE) launch_block2d<ROUNDING, kSel46Mae>(a, out);
+  else launch_block2d<ROUNDING, kSel46AbsMax>(a, out);
+}
+
+static void dispatch_block2d(const Block2dArgs &a, uint32_t rounding, uint32_t select, int out) {
+  if (rounding == NVFP4_SR) launch_block2d_sel<kSR>(a, select, out);
+  else if (rounding == NVFP4_SR_AFTER_RTN_SELECT) launch_block2d_sel<kSRAfterRtnSelect>(a, select, out);
+  else launch_block2d_sel<kRTN>(a, select, out);
+}
+
 // Checks shared by the entry points that take the parameter block.
 static int check_params(const void *x, const nvfp4_46_params *p, bool one_layout_only) {
   if (!x || !p) return NVFP4_ERR_NULL;
   if (p->rows <= 0 || p->cols <= 0) return NVFP4_ERR_SHAPE;
   if (p->layout < 1u || p->layout > 3u) return NVFP4_ERR_PARAM;
   if (one_layout_only && p->layout == 3u) return NVFP4_ERR_PARAM;
-  if (p->rounding > NVFP4_SR_AFTER_RTN_SELECT || p->select > NVFP4_SEL_46_ABSMAX || p->rht > 1u || p->reserved != 0u)
+  if (p->rounding > NVFP4_SR_AFTER_RTN_SELECT || p->select > NVFP4_SEL_46_ABSMAX || p->rht > 1u || p->block2d > 1u)
     return NVFP4_ERR_PARAM;
   if (!(p->fp8_max > 0.0f) || !(p->fp8_max <= 448.0f)) return NVFP4_ERR_PARAM;
   if ((p->layout & NVFP4_ROWWISE) && (p->cols % 16) != 0) return NVFP4_ERR_SHAPE;
@@ -770,6 +924,10 @@ static int check_params(const void *x, const nvfp4_46_params *p, bool one_layout
     return NVFP4_ERR_SHAPE;
   if (!aligned16(x)) return NVFP4_ERR_ALIGN;
   if (p->rht && p->layout == 3u) return NVFP4_ERR_UNSUPPORTED;
+  if (p->block2d) {
+    if ((p->rows % 16) != 0 || (p->cols % 16) != 0) return NVFP4_ERR_SHAPE;
+    if (p->layout != NVFP4_ROWWISE || p->rht) return NVFP4_ERR_UNSUPPORTED;
+  }
   return NVFP4_OK;
 }
 
@@ -820,6 +978,13 @@ int nvfp4_46_quantize(const void *x_bf16, const nvfp4_46_params *p, const float 
       !aligned16(scales_col) || !aligned16(choice_row) || !aligned16(choice_col))
     return NVFP4_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (p->block2d) {
+    Block2dArgs a{static_cast<const uint16_t *>(x_bf16), alpha, static_cast<uint8_t *>(codes_row),
+                  static_cast<uint8_t *>(scales_row), static_cast<uint8_t *>(choice_row), nullptr,
+                  p->rows, p->cols, p->sr_seed, s};
+    dispatch_block2d(a, p->rounding, p->select, kOutCodes);
+    return launch_status();
+  }
   if (!want_col) {
     FlatArgs a{static_cast<const uint4 *>(x_bf16), alpha, static_cast<uint2 *>(codes_row),
                static_cast<uint8_t *>(scales_row), static_cast<uint8_t *>(choice_row), nullptr,
@@ -840,14 +1005,21 @@ int nvfp4_46_dequantize(const void *codes, const void *scales, const float *alph
                         int64_t cols, uint32_t layout, void *out_bf16, void *stream) {
   if (!codes || !scales || !alpha || !out_bf16) return NVFP4_ERR_NULL;
   if (rows <= 0 || cols <= 0) return NVFP4_ERR_SHAPE;
-  if (layout != NVFP4_ROWWISE && layout != NVFP4_COLWISE) return NVFP4_ERR_PARAM;
+  if (layout != NVFP4_ROWWISE && layout != NVFP4_COLWISE && layout != NVFP4_BLOCK2D)
+    return NVFP4_ERR_PARAM;
+  if (layout == NVFP4_BLOCK2D && ((rows % 16) != 0 || (cols % 16) != 0)) return NVFP4_ERR_SHAPE;
   if (layout == NVFP4_ROWWISE && (cols % 16) != 0) return NVFP4_ERR_SHAPE;
   if (layout == NVFP4_COLWISE && ((rows % 16) != 0 || (cols % 8) != 0)) return NVFP4_ERR_SHAPE;
   if (rows > (int64_t)1 << 31 || cols > (int64_t)1 << 31 || rows * cols > (int64_t)1 << 40)
     return NVFP4_ERR_SHAPE;
   if (!aligned16(codes) || !aligned16(scales) || !aligned16(out_bf16)) return NVFP4_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (layout == NVFP4_ROWWISE) {
+  if (layout == NVFP4_BLOCK2D) {
+    const int64_t n8 = rows * cols / 8;
+    hipLaunchKernelGGL(k_dequant_2d, dim3(grid_for(n8, 16)), dim3(kThreads), 0, s,
+                       static_cast<const uint32_t *>(codes), static_cast<const uint8_t *>(scales),
+                       alpha, static_cast<uint4 *>(out_bf16), n8, cols);
+  } else if (layout == NVFP4_ROWWISE) {
     const int64_t n8 = rows * cols / 8;
     hipLaunchKernelGGL(k_dequant_flat, dim3(grid_for(n8, 16)), dim3(kThreads), 0, s,
                        static_cast<const uint32_t *>(codes), static_cast<const uint8_t *>(scales),
@@ -867,6 +1039,12 @@ int nvfp4_46_fake_quant(const void *x_bf16, const nvfp4_46_params *p, const floa
   if (rc != NVFP4_OK) return rc;
   if (!aligned16(out_bf16)) return NVFP4_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (p->block2d) {
+    Block2dArgs a{static_cast<const uint16_t *>(x_bf16), alpha, nullptr, nullptr, nullptr,
+                  static_cast<uint16_t *>(out_bf16), p->rows, p->cols, p->sr_seed, s};
+    dispatch_block2d(a, p->rounding, p->select, kOutFake);
+    return launch_status();
+  }
   if (p->layout == NVFP4_ROWWISE) {
     FlatArgs a{static_cast<const uint4 *>(x_bf16), alpha, nullptr, nullptr, nullptr,
                static_cast<uint4 *>(out_bf16), nullptr, p->rows * p->cols / 16,

@@ -31,7 +31,7 @@ def test_params_struct_layout_matches_header():
     assert C.sizeof(B.Params) == 56
     offs = {f[0]: getattr(B.Params, f[0]).offset for f in B.Params._fields_}
     assert offs == {"rows": 0, "cols": 8, "layout": 16, "rounding": 20, "select": 24, "rht": 28,
-                    "sr_seed": 32, "rht_seed": 40, "fp8_max": 48, "reserved": 52}
+                    "sr_seed": 32, "rht_seed": 40, "fp8_max": 48, "block2d": 52}
     # enum values quoted in the header
     for name, val in (("NVFP4_ROWWISE", 1), ("NVFP4_COLWISE", 2), ("NVFP4_RTN", 0), ("NVFP4_SR", 1), ("NVFP4_SR_AFTER_RTN_SELECT", 2),
                       ("NVFP4_SEL_46_MSE", 0), ("NVFP4_SEL_FORCE6", 1), ("NVFP4_SEL_FORCE4", 2),
@@ -69,8 +69,12 @@ def test_quantize_validation_codes():
     assert _q(B.make_params(32, 64, fp8_max=449.0)) == 4
     assert _q(B.make_params(32, 64, fp8_max=float("nan"))) == 4
     bad = B.make_params(32, 64)
-    bad.reserved = 1
+    bad.block2d = 2
     assert _q(bad) == 4
+    # 16x16 tiles: both dims multiples of 16, rowwise only, no transform
+    assert _q(B.make_params(40, 64, block2d=1)) == 2
+    assert _q(B.make_params(32, 64, block2d=1, rht=1)) == 5
+    assert _q(B.make_params(32, 64, layout=B.COLWISE, block2d=1), cr=None, sr=None, cc=P, sc=P) == 5
     # outputs for a layout that was not asked for
     assert _q(ok, cc=P, sc=P) == 4 and _q(ok, hc=P) == 4
     # columnwise requested but its outputs are missing
@@ -93,6 +97,7 @@ def test_other_entry_points_validation_codes():
     assert B.fake_quant_raw(P, ok, P, P + 6, stream=0) == 3
     assert B.dequantize_raw(None, P, P, 32, 64, B.ROWWISE, P, stream=0) == 1
     assert B.dequantize_raw(P, P, P, 32, 64, B.BOTH, P, stream=0) == 4
+    assert B.dequantize_raw(P, P, P, 40, 64, B.BLOCK2D, P, stream=0) == 2
     assert B.dequantize_raw(P, P, P, 32, 40, B.ROWWISE, P, stream=0) == 2
     assert B.dequantize_raw(P, P, P, 24, 64, B.COLWISE, P, stream=0) == 2
     assert B.dequantize_raw(P, P + 3, P, 32, 64, B.ROWWISE, P, stream=0) == 3

@@ -168,6 +168,41 @@ def test_sr_after_rtn_selection(name, layout):
                rounding=B.SR_AFTER_RTN_SELECT, tag="stress-sr-after-rtn")
 
 
+@pytest.mark.parametrize("select", [B.SEL_46_MSE, B.SEL_FORCE6, B.SEL_FORCE4, B.SEL_46_MAE,
+                                    B.SEL_46_ABSMAX])
+@pytest.mark.parametrize("rounding", [B.RTN, B.SR, B.SR_AFTER_RTN_SELECT])
+def test_block2d_matches_oracle(select, rounding):
+    """One scale per 16x16 tile (the weight quantization named in Section 4.1)."""
+    for name, shape in (("c2", (272, 400)), ("c4", (1024, 1024))):
+        x = wl.make(name, *shape)
+        rows, cols = shape
+        xb, xd = wl.bf16_bits(x), x.cuda()
+        alpha = B.nvfp4_46_tensor_scale(xd)
+        a = float(alpha.item())
+        kw = dict(rounding=rounding, select=select, sr_seed=SR_SEED)
+        c_ref, s_ref, f_ref, d_ref = ref.quantize_2d(xb, a, **kw)
+        out = B.nvfp4_46_quantize(xd, alpha, block2d=1, **kw)
+        assert out["scales_row"].shape == (rows // 16, cols // 16)
+        assert np.array_equal(_np(out["scales_row"]), s_ref)
+        assert np.array_equal(_np(out["choice_row"]), f_ref)
+        assert np.array_equal(_np(out["codes_row"]), c_ref)
+        deq = B.nvfp4_46_dequantize(out["codes_row"], out["scales_row"], alpha, rows, cols,
+                                    layout=B.BLOCK2D)
+        assert np.array_equal(_bits(deq), d_ref)
+        fq = B.nvfp4_46_fake_quant(xd, alpha, block2d=1, **kw)
+        assert np.array_equal(_bits(fq), d_ref)
+
+
+def test_block2d_transpose_consistency_on_gpu():
+    # under a fixed scale rule, quantizing W^T with 16x16 tiles is the transpose of quantizing W
+    x = wl.make("c2", 512, 768)
+    xd, xtd = x.cuda(), x.t().contiguous().cuda()
+    alpha = B.nvfp4_46_tensor_scale(xd)
+    d = B.nvfp4_46_fake_quant(xd, alpha, select=B.SEL_FORCE6, block2d=1)
+    dt = B.nvfp4_46_fake_quant(xtd, alpha, select=B.SEL_FORCE6, block2d=1)
+    assert torch.equal(dt, d.t().contiguous())
+
+
 def test_caller_supplied_alpha_replays_table3():
     # Table 3's blocks with the tensor scale written as 1: [10,20,30,40] -> 4, [15,30,120,180] -> 6
     x = torch.zeros((16, 32), dtype=torch.float32)
