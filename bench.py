@@ -158,6 +158,30 @@ def time_other_workloads(iters=30):
                 "main_g_elem_s": n / t_main / 1e3, "main_algorithmic_gb_s": n * bpe / t_main / 1e3,
                 "main_frac_of_8tbs": n * bpe / t_main / 1e3 / HBM_PEAK_GBS}
 
+    # variants of the rowwise quantizer on the c2 tensor: the other selection rules, the
+    # stochastic-rounding modes, 16x16 tiles
+    xs = [wl.make("c2").cuda() for _ in range(2)]
+    r, c = xs[0].shape
+    alpha = B.nvfp4_46_tensor_scale(xs[0])
+    os_ = [B.alloc_outputs(r, c, B.ROWWISE, "cuda", want_choice=False) for _ in range(2)]
+    variants = {
+        "mse (default)": dict(),
+        "always 6 (standard NVFP4)": dict(select=B.SEL_FORCE6),
+        "mean absolute error rule": dict(select=B.SEL_46_MAE),
+        "largest absolute error rule": dict(select=B.SEL_46_ABSMAX),
+        "stochastic rounding": dict(rounding=B.SR, sr_seed=wl.C5_SR_SEED),
+        "SR after RTN selection": dict(rounding=B.SR_AFTER_RTN_SELECT, sr_seed=wl.C5_SR_SEED),
+        "always 6 + SR": dict(rounding=B.SR, select=B.SEL_FORCE6, sr_seed=wl.C5_SR_SEED),
+        "16x16 tiles": dict(block2d=1),
+        "16x16 tiles, MAE rule": dict(block2d=1, select=B.SEL_46_MAE),
+    }
+    res["c2_variants_main_us"] = {}
+    for name, kw in variants.items():
+        p = B.make_params(r, c, **kw)
+        res["c2_variants_main_us"][name] = med(
+            lambda i: B.quantize_raw(xs[i % 2], p, alpha, os_[i % 2]["codes_row"],
+                                     os_[i % 2]["scales_row"], None, None, None, None, st))
+    del xs, os_
     # c3: activation batch, fake-quant round trip in one kernel (2 B read + 2 B written)
     xs = [wl.make("c3").cuda() for _ in range(2)]
     r, c = xs[0].shape
