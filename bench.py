@@ -237,6 +237,17 @@ def main():
             sets[i % len(sets)].deq.copy_(sets[(i + 1) % len(sets)].x)
         for i in range(6):
             step(sets[i % len(sets)])
+        if args.other_workloads:
+            # the kernels that stage data in LDS: both orientations in one pass (c4 recipe)
+            # and the fake-quant round trip, on tensors of the same shape
+            x4 = wl.make("c4", rows, cols).cuda()
+            o4 = B.alloc_outputs(rows, cols, B.BOTH, "cuda", want_choice=False)
+            p4 = B.make_params(rows, cols, layout=B.BOTH)
+            st = torch.cuda.current_stream()
+            for i in range(4):
+                B.quantize_raw(x4, p4, sets[0].alpha, o4["codes_row"], o4["scales_row"],
+                               o4["codes_col"], o4["scales_col"], None, None, st)
+                B.fake_quant_raw(x4, sets[0].params, sets[0].alpha, sets[0].deq, st)
         torch.cuda.synchronize()
         print("counter pass done: 3 copies of %d bytes, 6 steps" % (n * 2))
         return

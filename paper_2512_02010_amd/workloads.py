@@ -30,8 +30,6 @@ recipes at sizes the CPU oracle finishes quickly.
 """
 from __future__ import annotations
 
-from dataclasses import dataclass
-
 import numpy as np
 import torch
 
@@ -49,15 +47,6 @@ FULL_SHAPES = {
 # (stochastic rounding uniforms and Hadamard sign vectors).
 C5_SR_SEED = 0x46F5EED00000C5
 C5_RHT_SEED = 0x4AD0000000C5
-
-
-@dataclass(frozen=True)
-class Workload:
-    name: str
-    rows: int
-    cols: int
-    seed: int
-    description: str
 
 
 def _gen(seed: int) -> torch.Generator:
