@@ -33,11 +33,11 @@ HBM_PEAK_GBS = 8000.0
 # plain (unpacked) fp32 VALU issue rate: 256 CUs x 64 lanes x 2.4 GHz, in lane-operations/s
 VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
 # VALU wave-instructions per block of 16 elements in the rowwise 4/6 kernel, from
-# rocprofv3 --pmc SQ_INSTS_VALU (profiles/c2_step_counters.txt): 14,281,048 per 4,194,304/64 wave-blocks
-VALU_INSTS_PER_BLOCK_46 = 14281048.0 / (4194304.0 / 64.0)
+# rocprofv3 --pmc SQ_INSTS_VALU (profiles/c2_step_counters.txt): 14,920,024 per 4,194,304/64 wave-blocks
+VALU_INSTS_PER_BLOCK_46 = 14920024.0 / (4194304.0 / 64.0)
 # HBM bytes per element of the same kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled
-# by a plain copy's readings (same file): (65617.7 * 2.000 + 36873.5 * 1.000) KiB per 67,108,864
-HBM_TRAFFIC_PER_ELEM_46 = (65617.7 * 2.0 + 36873.5) * 1024.0 / 67108864.0
+# by a plain copy's readings (same file): (65612.8 * 2.000 + 36864.3 * 1.000) KiB per 67,108,864
+HBM_TRAFFIC_PER_ELEM_46 = (65612.8 * 2.0 + 36864.3) * 1024.0 / 67108864.0
 BYTES_PER_ELEM_QUANT = 2.0 + 0.5 + 1.0 / 16.0        # read x, write codes, write scales
 BYTES_PER_ELEM_AMAX = 2.0
 BYTES_PER_ELEM_DEQUANT = 0.5 + 1.0 / 16.0 + 2.0

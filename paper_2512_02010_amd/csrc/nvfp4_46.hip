@@ -35,7 +35,7 @@ enum : int { kOutCodes = 0, kOutFake = 1, kOutAmax = 2 };
 #define NVFP4_46_AMAX_WG_PER_CU 1
 #endif
 #ifndef NVFP4_46_FLAT_WG_PER_CU
-#define NVFP4_46_FLAT_WG_PER_CU 16
+#define NVFP4_46_FLAT_WG_PER_CU 32
 #endif
 
 // Streaming accesses: every input word is read once and every output byte written once,
