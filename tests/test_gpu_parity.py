@@ -81,8 +81,8 @@ def check_case(x: torch.Tensor, layout=B.ROWWISE, rounding=B.RTN, select=B.SEL_4
 
 # ------------------------------------------------------------------ small, many options
 
-SHAPES_ROW = [(16, 16), (48, 176), (144, 272), (1, 4096), (257, 48)]
-SHAPES_COL = [(16, 8), (48, 176), (144, 264), (272, 136), (4096, 8), (128, 128)]
+SHAPES_ROW = [(16, 16), (48, 176), (144, 272), (1, 4096), (257, 48), (1000, 4112)]
+SHAPES_COL = [(16, 8), (48, 176), (144, 264), (272, 136), (4096, 8), (128, 128), (1008, 4104)]
 
 
 @pytest.mark.parametrize("shape", SHAPES_ROW)
