@@ -345,12 +345,32 @@ void ref_quantize_block(const float v[BLOCK], float alpha, int rounding, int sel
 
 /* ---------------------------------------------------------- whole tensors */
 
+/* The input tensor: BF16 bit patterns (activations, gradients, and weights held in
+ * BF16) or fp32 values (the master weights of Fig. 3, which enter the quantizer without a
+ * BF16 rounding in between).  Either way the method's arithmetic starts from the fp32
+ * value of each element. */
+typedef struct {
+  const void *p;
+  int f32;
+} xin;
+static float x_at(xin x, uint64_t g) {
+  return x.f32 ? ((const float *)x.p)[g] : ref_bf16_to_f32(((const uint16_t *)x.p)[g]);
+}
+static xin x_bf16(const uint16_t *p) {
+  xin x = {p, 0};
+  return x;
+}
+static xin x_f32(const float *p) {
+  xin x = {p, 1};
+  return x;
+}
+
 /* Fetch the block with index (line, blk) along the blocked axis as fp32:
  * rowwise -> row `line`, columns 16*blk..; columnwise -> column `line`,
  * rows 16*blk.. (i.e. the rowwise block of the transposed tensor, which is
  * how Fig. 3 feeds the DGRAD/WGRAD operands).  Applies the Hadamard
  * transform when asked.  Also returns each element's flat index. */
-static void fetch_block(const uint16_t *x, int64_t rows, int64_t cols, int layout, int64_t line,
+static void fetch_block(xin x, int64_t rows, int64_t cols, int layout, int64_t line,
                         int64_t blk, int rht, uint64_t rht_seed, float v[BLOCK],
                         uint64_t g[BLOCK]) {
   (void)rows;
@@ -358,7 +378,7 @@ static void fetch_block(const uint16_t *x, int64_t rows, int64_t cols, int layou
     int64_t r = (layout == REF_ROWWISE) ? line : blk * BLOCK + i;
     int64_t c = (layout == REF_ROWWISE) ? blk * BLOCK + i : line;
     g[i] = (uint64_t)r * (uint64_t)cols + (uint64_t)c;
-    v[i] = ref_bf16_to_f32(x[g[i]]);
+    v[i] = x_at(x, g[i]);
   }
   if (rht) ref_rht16(v, ref_rht_sign_word(rht_seed, (uint64_t)blk));
 }
@@ -375,8 +395,8 @@ static int64_t n_blocks(int64_t rows, int64_t cols, int layout) {
  * quantized, i.e. after the Hadamard transform when it is on (READING).  One
  * fp32 division by the exactly representable constant.  An all-zero tensor
  * gets alpha = 1 (READING; Eq. (2) would divide by zero). */
-int nvfp4_46_ref_tensor_scale(const uint16_t *x, int64_t rows, int64_t cols, int layout, int rht,
-                              uint64_t rht_seed, float fp8_max, float *alpha) {
+static int tensor_scale_impl(xin x, int64_t rows, int64_t cols, int layout, int rht,
+                             uint64_t rht_seed, float fp8_max, float *alpha) {
   int64_t L = n_lines(rows, cols, layout), NB = n_blocks(rows, cols, layout);
   float amax = 0.0f;
 #pragma omp parallel for reduction(max : amax) schedule(static)
@@ -393,6 +413,14 @@ int nvfp4_46_ref_tensor_scale(const uint16_t *x, int64_t rows, int64_t cols, int
   *alpha = (amax == 0.0f) ? 1.0f : amax / (6.0f * fp8_max);
   return 0;
 }
+int nvfp4_46_ref_tensor_scale(const uint16_t *x, int64_t rows, int64_t cols, int layout, int rht,
+                              uint64_t rht_seed, float fp8_max, float *alpha) {
+  return tensor_scale_impl(x_bf16(x), rows, cols, layout, rht, rht_seed, fp8_max, alpha);
+}
+int nvfp4_46_ref_tensor_scale_f32(const float *x, int64_t rows, int64_t cols, int layout, int rht,
+                                  uint64_t rht_seed, float fp8_max, float *alpha) {
+  return tensor_scale_impl(x_f32(x), rows, cols, layout, rht, rht_seed, fp8_max, alpha);
+}
 
 /* Quantize a [rows][cols] BF16 tensor in one orientation.
  * Outputs, indexed by (line, position along the blocked axis):
@@ -403,9 +431,9 @@ int nvfp4_46_ref_tensor_scale(const uint16_t *x, int64_t rows, int64_t cols, int
  *   deq    [rows][cols]    BF16 of the chosen candidate's dequantized values,
  *                          always in the input's own row-major order (optional)
  * Only rows are distributed over threads; each block is independent. */
-int nvfp4_46_ref_quantize(const uint16_t *x, int64_t rows, int64_t cols, int layout, int rounding,
-                          int select, int rht, uint64_t sr_seed, uint64_t rht_seed, float alpha,
-                          uint8_t *codes, uint8_t *scales, uint8_t *choice, uint16_t *deq) {
+static int quantize_impl(xin x, int64_t rows, int64_t cols, int layout, int rounding,
+                         int select, int rht, uint64_t sr_seed, uint64_t rht_seed, float alpha,
+                         uint8_t *codes, uint8_t *scales, uint8_t *choice, uint16_t *deq) {
   int64_t L = n_lines(rows, cols, layout), NB = n_blocks(rows, cols, layout);
 #pragma omp parallel for schedule(static)
   for (int64_t line = 0; line < L; ++line)
@@ -427,6 +455,20 @@ int nvfp4_46_ref_quantize(const uint16_t *x, int64_t rows, int64_t cols, int lay
     }
   return 0;
 }
+int nvfp4_46_ref_quantize(const uint16_t *x, int64_t rows, int64_t cols, int layout, int rounding,
+                          int select, int rht, uint64_t sr_seed, uint64_t rht_seed, float alpha,
+                          uint8_t *codes, uint8_t *scales, uint8_t *choice, uint16_t *deq) {
+  return quantize_impl(x_bf16(x), rows, cols, layout, rounding, select, rht, sr_seed, rht_seed,
+                       alpha, codes, scales, choice, deq);
+}
+/* The same for an fp32 tensor (FP32 master weights, Fig. 3). */
+int nvfp4_46_ref_quantize_f32(const float *x, int64_t rows, int64_t cols, int layout,
+                              int rounding, int select, int rht, uint64_t sr_seed,
+                              uint64_t rht_seed, float alpha, uint8_t *codes, uint8_t *scales,
+                              uint8_t *choice, uint16_t *deq) {
+  return quantize_impl(x_f32(x), rows, cols, layout, rounding, select, rht, sr_seed, rht_seed,
+                       alpha, codes, scales, choice, deq);
+}
 
 /* 2D block quantization of weight matrices (named in Section 4.1 as part of the
  * training recipe; READING throughout): one E4M3 scale per 16x16 tile instead of one per
@@ -442,9 +484,9 @@ int nvfp4_46_ref_quantize(const uint16_t *x, int64_t rows, int64_t cols, int lay
  * choice [rows/16][cols/16], deq [rows][cols] (each optional).  With
  * REF_SR_AFTER_RTN_SELECT the tile is chosen from round-to-nearest candidates and then
  * rounded stochastically; uniforms are those of the elements' flat indices. */
-int nvfp4_46_ref_quantize_2d(const uint16_t *x, int64_t rows, int64_t cols, int rounding,
-                             int select, uint64_t sr_seed, float alpha, uint8_t *codes,
-                             uint8_t *scales, uint8_t *choice, uint16_t *deq) {
+static int quantize_2d_impl(xin x, int64_t rows, int64_t cols, int rounding,
+                            int select, uint64_t sr_seed, float alpha, uint8_t *codes,
+                            uint8_t *scales, uint8_t *choice, uint16_t *deq) {
   int64_t TR = rows / BLOCK, TCB = cols / BLOCK;
 #pragma omp parallel for schedule(static)
   for (int64_t tr = 0; tr < TR; ++tr)
@@ -454,7 +496,7 @@ int nvfp4_46_ref_quantize_2d(const uint16_t *x, int64_t rows, int64_t cols, int 
       for (int r = 0; r < BLOCK; ++r)
         for (int c = 0; c < BLOCK; ++c) {
           uint64_t g = (uint64_t)(tr * BLOCK + r) * (uint64_t)cols + (uint64_t)(tc * BLOCK + c);
-          v[r][c] = ref_bf16_to_f32(x[g]);
+          v[r][c] = x_at(x, g);
           u[r][c] = (rounding != REF_RTN) ? ref_sr_uniform(sr_seed, g) : 0.0f;
           float a = fabsf(v[r][c]);
           if (a > b) b = a;
@@ -497,6 +539,19 @@ int nvfp4_46_ref_quantize_2d(const uint16_t *x, int64_t rows, int64_t cols, int 
       }
     }
   return 0;
+}
+
+int nvfp4_46_ref_quantize_2d(const uint16_t *x, int64_t rows, int64_t cols, int rounding,
+                             int select, uint64_t sr_seed, float alpha, uint8_t *codes,
+                             uint8_t *scales, uint8_t *choice, uint16_t *deq) {
+  return quantize_2d_impl(x_bf16(x), rows, cols, rounding, select, sr_seed, alpha, codes, scales,
+                          choice, deq);
+}
+int nvfp4_46_ref_quantize_2d_f32(const float *x, int64_t rows, int64_t cols, int rounding,
+                                 int select, uint64_t sr_seed, float alpha, uint8_t *codes,
+                                 uint8_t *scales, uint8_t *choice, uint16_t *deq) {
+  return quantize_2d_impl(x_f32(x), rows, cols, rounding, select, sr_seed, alpha, codes, scales,
+                          choice, deq);
 }
 
 /* Dequantize 2D-block data: scales [rows/16][cols/16], codes as above. */
@@ -559,7 +614,7 @@ int nvfp4_46_ref_block_errors_sel(const uint16_t *x, int64_t rows, int64_t cols,
       float v[BLOCK], u[BLOCK], D[BLOCK], E[2];
       uint64_t g[BLOCK];
       uint8_t q[BLOCK], S, four;
-      fetch_block(x, rows, cols, layout, line, blk, rht, rht_seed, v, g);
+      fetch_block(x_bf16(x), rows, cols, layout, line, blk, rht, rht_seed, v, g);
       for (int i = 0; i < BLOCK; ++i)
         u[i] = (rounding != REF_RTN) ? ref_sr_uniform(sr_seed, g[i]) : 0.0f;
       ref_quantize_block(v, alpha, rounding, select, u, q, D, &S, &four, E);

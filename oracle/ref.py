@@ -70,6 +70,14 @@ def lib() -> C.CDLL:
         L.nvfp4_46_ref_quantize.restype = i32
         L.nvfp4_46_ref_quantize.argtypes = [u16p, i64, i64, i32, i32, i32, i32, u64, u64, f32,
                                             u8p, u8p, u8p, u16p]
+        L.nvfp4_46_ref_tensor_scale_f32.restype = i32
+        L.nvfp4_46_ref_tensor_scale_f32.argtypes = [f32p, i64, i64, i32, i32, u64, f32, f32p]
+        L.nvfp4_46_ref_quantize_f32.restype = i32
+        L.nvfp4_46_ref_quantize_f32.argtypes = [f32p, i64, i64, i32, i32, i32, i32, u64, u64, f32,
+                                                u8p, u8p, u8p, u16p]
+        L.nvfp4_46_ref_quantize_2d_f32.restype = i32
+        L.nvfp4_46_ref_quantize_2d_f32.argtypes = [f32p, i64, i64, i32, i32, u64, f32, u8p, u8p,
+                                                   u8p, u16p]
         L.nvfp4_46_ref_dequantize.restype = i32
         L.nvfp4_46_ref_dequantize.argtypes = [u8p, u8p, f32, i64, i64, i32, u16p]
         L.nvfp4_46_ref_fake_quant.restype = i32
@@ -101,8 +109,17 @@ def _p(a: np.ndarray | None, ctype):
 
 
 def _check_x(x_bits: np.ndarray):
-    assert x_bits.dtype == np.uint16 and x_bits.ndim == 2 and x_bits.flags["C_CONTIGUOUS"]
+    """The input tensor: uint16 = BF16 bit patterns, float32 = fp32 values."""
+    assert x_bits.dtype in (np.uint16, np.float32) and x_bits.ndim == 2
+    assert x_bits.flags["C_CONTIGUOUS"]
     return x_bits.shape
+
+
+def _x(x: np.ndarray, name: str):
+    """(C function, pointer) for the input's element type."""
+    if x.dtype == np.float32:
+        return getattr(lib(), name + "_f32"), _p(x, C.c_float)
+    return getattr(lib(), name), _p(x, C.c_uint16)
 
 
 def _out_shapes(rows, cols, layout):
@@ -204,8 +221,8 @@ def tensor_scale(x_bits: np.ndarray, layout: int = ROWWISE, rht: int = 0, rht_se
     rows, cols = _check_x(x_bits)
     _out_shapes(rows, cols, layout)
     a = C.c_float()
-    rc = lib().nvfp4_46_ref_tensor_scale(_p(x_bits, C.c_uint16), rows, cols, layout, rht,
-                                         rht_seed, fp8_max, C.byref(a))
+    fn, xp = _x(x_bits, "nvfp4_46_ref_tensor_scale")
+    rc = fn(xp, rows, cols, layout, rht, rht_seed, fp8_max, C.byref(a))
     assert rc == 0
     return float(a.value)
 
@@ -220,10 +237,10 @@ def quantize(x_bits: np.ndarray, alpha: float, layout: int = ROWWISE, rounding: 
     scales = np.zeros(ss, np.uint8)
     choice = np.zeros(ss, np.uint8)
     deq = np.zeros((rows, cols), np.uint16) if want_deq else None
-    rc = lib().nvfp4_46_ref_quantize(_p(x_bits, C.c_uint16), rows, cols, layout, rounding, select,
-                                     rht, sr_seed, rht_seed, alpha, _p(codes, C.c_uint8),
-                                     _p(scales, C.c_uint8), _p(choice, C.c_uint8),
-                                     _p(deq, C.c_uint16))
+    fn, xp = _x(x_bits, "nvfp4_46_ref_quantize")
+    rc = fn(xp, rows, cols, layout, rounding, select, rht, sr_seed, rht_seed, alpha,
+            _p(codes, C.c_uint8), _p(scales, C.c_uint8), _p(choice, C.c_uint8),
+            _p(deq, C.c_uint16))
     assert rc == 0
     return (codes, scales, choice, deq) if want_deq else (codes, scales, choice)
 
@@ -246,9 +263,14 @@ def fake_quant(x_bits: np.ndarray, alpha: float, layout: int = ROWWISE, rounding
     rows, cols = _check_x(x_bits)
     _out_shapes(rows, cols, layout)
     out = np.zeros((rows, cols), np.uint16)
-    rc = lib().nvfp4_46_ref_fake_quant(_p(x_bits, C.c_uint16), rows, cols, layout, rounding,
-                                       select, rht, sr_seed, rht_seed, alpha,
-                                       _p(out, C.c_uint16))
+    if x_bits.dtype == np.float32:
+        rc = lib().nvfp4_46_ref_quantize_f32(_p(x_bits, C.c_float), rows, cols, layout, rounding,
+                                             select, rht, sr_seed, rht_seed, alpha, None, None,
+                                             None, _p(out, C.c_uint16))
+    else:
+        rc = lib().nvfp4_46_ref_fake_quant(_p(x_bits, C.c_uint16), rows, cols, layout, rounding,
+                                           select, rht, sr_seed, rht_seed, alpha,
+                                           _p(out, C.c_uint16))
     assert rc == 0
     return out
 
@@ -262,6 +284,7 @@ def block_abs_metric(v, D, select: int) -> float:
 
 def block_errors(x_bits: np.ndarray, alpha: float, layout: int = ROWWISE, rounding: int = RTN,
                  rht: int = 0, sr_seed: int = 0, rht_seed: int = 0, select: int = SEL_46_MSE):
+    assert x_bits.dtype == np.uint16
     rows, cols = _check_x(x_bits)
     _, ss = _out_shapes(rows, cols, layout)
     E6 = np.zeros(ss, np.float32)
@@ -282,9 +305,9 @@ def quantize_2d(x_bits: np.ndarray, alpha: float, rounding: int = RTN, select: i
     scales = np.zeros((rows // 16, cols // 16), np.uint8)
     choice = np.zeros((rows // 16, cols // 16), np.uint8)
     deq = np.zeros((rows, cols), np.uint16)
-    rc = lib().nvfp4_46_ref_quantize_2d(_p(x_bits, C.c_uint16), rows, cols, rounding, select,
-                                        sr_seed, alpha, _p(codes, C.c_uint8), _p(scales, C.c_uint8),
-                                        _p(choice, C.c_uint8), _p(deq, C.c_uint16))
+    fn, xp = _x(x_bits, "nvfp4_46_ref_quantize_2d")
+    rc = fn(xp, rows, cols, rounding, select, sr_seed, alpha, _p(codes, C.c_uint8),
+            _p(scales, C.c_uint8), _p(choice, C.c_uint8), _p(deq, C.c_uint16))
     assert rc == 0
     return codes, scales, choice, deq
 

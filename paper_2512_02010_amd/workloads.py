@@ -68,57 +68,57 @@ def _normal(shape, g):
     return torch.randn(shape, generator=g, dtype=torch.float32)
 
 
-def make_c1(rows=256, cols=1024, seed=SEEDS["c1"]) -> torch.Tensor:
+def make_c1(rows=256, cols=1024, seed=SEEDS["c1"], dtype=torch.bfloat16) -> torch.Tensor:
     g = _gen(seed)
-    return _normal((rows, cols), g).to(torch.bfloat16)
+    return _normal((rows, cols), g).to(dtype)
 
 
-def make_c2(rows=8192, cols=8192, seed=SEEDS["c2"]) -> torch.Tensor:
+def make_c2(rows=8192, cols=8192, seed=SEEDS["c2"], dtype=torch.bfloat16) -> torch.Tensor:
     g = _gen(seed)
     n_out = max(1, round(0.01 * cols))
     perm = torch.randperm(cols, generator=g)
     col_gain = torch.ones(cols, dtype=torch.float32)
     col_gain[perm[:n_out]] = 50.0
-    out = torch.empty((rows, cols), dtype=torch.bfloat16)
+    out = torch.empty((rows, cols), dtype=dtype)
     for r0, n in _chunked_rows(rows, cols, 1 << 22):
         z = _normal((n, cols), g)
         chi = _normal((n, cols), g).square_()
         chi += _normal((n, cols), g).square_()
         chi += _normal((n, cols), g).square_()
         t = z / torch.sqrt(chi / 3.0)
-        out[r0:r0 + n] = (0.02 * t * col_gain).to(torch.bfloat16)
+        out[r0:r0 + n] = (0.02 * t * col_gain).to(dtype)
     return out
 
 
-def make_c3(rows=16384, cols=4096, seed=SEEDS["c3"]) -> torch.Tensor:
+def make_c3(rows=16384, cols=4096, seed=SEEDS["c3"], dtype=torch.bfloat16) -> torch.Tensor:
     g = _gen(seed)
     row_mag = torch.exp(_normal((rows, 1), g))
-    out = torch.empty((rows, cols), dtype=torch.bfloat16)
+    out = torch.empty((rows, cols), dtype=dtype)
     for r0, n in _chunked_rows(rows, cols):
         x = _normal((n, cols), g) * row_mag[r0:r0 + n]
         hit = torch.rand((n, cols), generator=g) < 1.0e-3
         mag = 100.0 + 900.0 * torch.rand((n, cols), generator=g)
         sgn = torch.where(torch.rand((n, cols), generator=g) < 0.5, -1.0, 1.0)
         x = torch.where(hit, mag * sgn, x)
-        out[r0:r0 + n] = x.to(torch.bfloat16)
+        out[r0:r0 + n] = x.to(dtype)
     return out
 
 
-def make_c4(rows=8192, cols=8192, seed=SEEDS["c4"]) -> torch.Tensor:
+def make_c4(rows=8192, cols=8192, seed=SEEDS["c4"], dtype=torch.bfloat16) -> torch.Tensor:
     g = _gen(seed)
-    out = torch.empty((rows, cols), dtype=torch.bfloat16)
+    out = torch.empty((rows, cols), dtype=dtype)
     for r0, n in _chunked_rows(rows, cols):
-        out[r0:r0 + n] = _normal((n, cols), g).to(torch.bfloat16)
+        out[r0:r0 + n] = _normal((n, cols), g).to(dtype)
     return out
 
 
-def make_c5(rows=32768, cols=8192, seed=SEEDS["c5"]) -> torch.Tensor:
+def make_c5(rows=32768, cols=8192, seed=SEEDS["c5"], dtype=torch.bfloat16) -> torch.Tensor:
     g = _gen(seed)
     row_mag = torch.exp(2.0 * _normal((rows, 1), g))
-    out = torch.empty((rows, cols), dtype=torch.bfloat16)
+    out = torch.empty((rows, cols), dtype=dtype)
     for r0, n in _chunked_rows(rows, cols):
         x = 1.0e-3 * _normal((n, cols), g) * row_mag[r0:r0 + n]
-        out[r0:r0 + n] = x.to(torch.bfloat16)
+        out[r0:r0 + n] = x.to(dtype)
     return out
 
 
@@ -126,10 +126,11 @@ _MAKERS = {"c1": make_c1, "c2": make_c2, "c3": make_c3, "c4": make_c4, "c5": mak
 
 
 def make(name: str, rows: int | None = None, cols: int | None = None,
-         seed: int | None = None) -> torch.Tensor:
-    """BF16 CPU tensor for workload `name`, at its full shape unless overridden."""
+         seed: int | None = None, dtype: torch.dtype = torch.bfloat16) -> torch.Tensor:
+    """CPU tensor for workload `name`, at its full shape unless overridden.  BF16 by default;
+    ``dtype=torch.float32`` keeps the fp32 draws unrounded (FP32 master weights, Fig. 3)."""
     fr, fc = FULL_SHAPES[name]
-    return _MAKERS[name](rows or fr, cols or fc, SEEDS[name] if seed is None else seed)
+    return _MAKERS[name](rows or fr, cols or fc, SEEDS[name] if seed is None else seed, dtype)
 
 
 def bf16_bits(x: torch.Tensor) -> np.ndarray:
@@ -138,13 +139,23 @@ def bf16_bits(x: torch.Tensor) -> np.ndarray:
     return x.view(torch.int16).numpy().view(np.uint16)
 
 
+def host_array(x: torch.Tensor) -> np.ndarray:
+    """What the CPU side consumes: BF16 tensors as uint16 bit patterns, fp32 tensors as
+    float32 arrays (no copy)."""
+    if x.dtype == torch.float32:
+        assert x.is_contiguous() and x.device.type == "cpu"
+        return x.numpy()
+    return bf16_bits(x)
+
+
 def bits_to_bf16(bits: np.ndarray) -> torch.Tensor:
     """Inverse of :func:`bf16_bits`."""
     b = np.ascontiguousarray(bits, dtype=np.uint16)
     return torch.from_numpy(b.view(np.int16)).view(torch.bfloat16)
 
 
-def adversarial(kind: str, rows: int = 32, cols: int = 64) -> torch.Tensor:
+def adversarial(kind: str, rows: int = 32, cols: int = 64,
+                dtype: torch.dtype = torch.bfloat16) -> torch.Tensor:
     """Small edge-case tensors (shapes are multiples of 16 both ways)."""
     g = _gen(977)
     if kind == "zeros":
@@ -209,7 +220,7 @@ def adversarial(kind: str, rows: int = 32, cols: int = 64) -> torch.Tensor:
         x = _normal((rows, cols), g) * 1.0e30
     else:
         raise ValueError(kind)
-    return x.to(torch.bfloat16).contiguous()
+    return x.to(dtype).contiguous()
 
 
 ADVERSARIAL_KINDS = ("zeros", "neg_zeros", "constant", "neg_constant", "one_hot",
