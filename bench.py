@@ -238,6 +238,23 @@ def time_other_workloads(iters=30):
             lambda i: B.quantize_raw(xs[i % 2], p, alpha, os_[i % 2]["codes_row"],
                                      os_[i % 2]["scales_row"], None, None, None, None, st))
     del xs, os_
+    # c2 held as FP32 master weights (Fig. 3): 4 B read per element
+    xh = wl.make("c2", dtype=torch.float32)
+    xs = [xh.cuda() for _ in range(2)]
+    os_ = [B.alloc_outputs(r, c, B.BOTH, "cuda", want_choice=False) for _ in range(2)]
+    p_row = B.make_params(r, c, x_dtype=B.X_F32)
+    p_both = B.make_params(r, c, layout=B.BOTH, x_dtype=B.X_F32)
+    t_s = med(lambda i: B.tensor_scale_raw(xs[i % 2], p_row, alpha, st))
+    t_m = med(lambda i: B.quantize_raw(xs[i % 2], p_row, alpha, os_[i % 2]["codes_row"],
+                                       os_[i % 2]["scales_row"], None, None, None, None, st))
+    res["c2_fp32_rowwise"] = entry(r * c, 4.0 + 0.5625, t_s, t_m,
+                                   "8192x8192 FP32 weights, rowwise RTN 4/6")
+    t_m = med(lambda i: B.quantize_raw(xs[i % 2], p_both, alpha, os_[i % 2]["codes_row"],
+                                       os_[i % 2]["scales_row"], os_[i % 2]["codes_col"],
+                                       os_[i % 2]["scales_col"], None, None, st))
+    res["c2_fp32_both"] = entry(r * c, 4.0 + 1.125, t_s, t_m,
+                                "8192x8192 FP32 weights, both orientations, RTN 4/6")
+    del xs, os_, xh
     # c3: activation batch, fake-quant round trip in one kernel (2 B read + 2 B written)
     xs = [wl.make("c3").cuda() for _ in range(2)]
     r, c = xs[0].shape

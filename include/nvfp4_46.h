@@ -14,7 +14,8 @@
  *     Work is enqueued on it and the call returns without synchronising; a call
  *     that fails validation enqueues nothing.
  *   - The return value is an nvfp4_status; nothing is printed, thrown or aborted.
- *   - Tensors are dense row-major: x is [rows][cols] BF16 (2 bytes per element).
+ *   - Tensors are dense row-major: x is [rows][cols], BF16 (2 bytes per element) or, with
+ *     nvfp4_46_params.x_dtype = NVFP4_X_F32, fp32 (4 bytes per element).
  *   - Inputs must be finite.  The tensor scale must lie in [2^-100, 2^118]
  *     (nvfp4_46_tensor_scale guarantees this whenever max|x| >= 2^-89).
  *   - x and every output buffer must be 16-byte aligned.
@@ -63,6 +64,8 @@ typedef enum {
 enum { NVFP4_ROWWISE = 1, NVFP4_COLWISE = 2, NVFP4_BLOCK2D = 4 };
 /* rounding of scaled values onto the E2M1 grid */
 enum { NVFP4_RTN = 0, NVFP4_SR = 1, NVFP4_SR_AFTER_RTN_SELECT = 2 };
+/* element type of the input tensor x */
+enum { NVFP4_X_BF16 = 0, NVFP4_X_F32 = 1 };
 /* how the block scale is chosen */
 enum { NVFP4_SEL_46_MSE = 0, NVFP4_SEL_FORCE6 = 1, NVFP4_SEL_FORCE4 = 2, NVFP4_SEL_46_MAE = 3,
        NVFP4_SEL_46_ABSMAX = 4 };
@@ -101,22 +104,27 @@ typedef struct {
                           fixed order as within a row.  Needs layout = NVFP4_ROWWISE, rht = 0,
                           rows % 16 == cols % 16 == 0; codes_row is [rows][cols/2] as usual,
                           scales_row and choice_row are [rows/16][cols/16].                   */
+  uint32_t x_dtype;    /* NVFP4_X_BF16, or NVFP4_X_F32: x holds fp32 values, which enter the
+                          quantizer as they are -- the weights of Fig. 3, which are stored in
+                          FP32 and quantized on every use.  Everything after the load is the
+                          same arithmetic (it is fp32 throughout either way); outputs of
+                          nvfp4_46_fake_quant stay BF16.                                       */
 } nvfp4_46_params;
 
 /* Eq. (1) with Section 3.1's constant: alpha = max|v| / (6 * fp8_max) over the values
  * that get quantized (after the Hadamard transform when rht = 1); alpha = 1 for an
  * all-zero tensor.  Uses rows, cols, layout (one orientation, matters only with rht),
  * rht, rht_seed and fp8_max of `p`.
- *   x      in   [rows][cols] BF16
+ *   x      in   [rows][cols] BF16 (fp32 with x_dtype = NVFP4_X_F32)
  *   alpha  out  1 float (device); also used as scratch while the kernels run
  * Errors: NULL x/p/alpha -> ERR_NULL; bad dims -> ERR_SHAPE; x misaligned -> ERR_ALIGN;
- * bad fp8_max / layout -> ERR_PARAM; rht with both layouts -> ERR_UNSUPPORTED.        */
-int nvfp4_46_tensor_scale(const void *x_bf16, const nvfp4_46_params *p, float *alpha,
+ * bad fp8_max / layout / x_dtype -> ERR_PARAM; rht with both layouts -> ERR_UNSUPPORTED.        */
+int nvfp4_46_tensor_scale(const void *x, const nvfp4_46_params *p, float *alpha,
                           void *stream);
 
 /* The 4/6 quantizer (Eq. (2), Eq. (3), Table 3 lines 1-14) in the requested
  * orientation(s).
- *   x           in   [rows][cols] BF16
+ *   x           in   [rows][cols] BF16 (fp32 with x_dtype = NVFP4_X_F32)
  *   alpha       in   1 float (device): the tensor scale, from nvfp4_46_tensor_scale or
  *                    written by the caller
  *   codes_row, scales_row   out  required iff layout has NVFP4_ROWWISE, else must be NULL
@@ -125,7 +133,7 @@ int nvfp4_46_tensor_scale(const void *x_bf16, const nvfp4_46_params *p, float *a
  * Errors: as above, plus a required output NULL -> ERR_NULL; an output given for a
  * layout that was not requested -> ERR_PARAM; rht = 1 with both layouts ->
  * ERR_UNSUPPORTED (the two orientations would be two different transformed tensors). */
-int nvfp4_46_quantize(const void *x_bf16, const nvfp4_46_params *p, const float *alpha,
+int nvfp4_46_quantize(const void *x, const nvfp4_46_params *p, const float *alpha,
                       void *codes_row, void *scales_row, void *codes_col, void *scales_col,
                       void *choice_row, void *choice_col, void *stream);
 
@@ -142,7 +150,7 @@ int nvfp4_46_dequantize(const void *codes, const void *scales, const float *alph
  * for nvfp4_46_quantize's outputs, bit for bit, without writing codes or scales.
  * `layout` must name exactly one orientation.  With rht = 1 the result stays in the
  * transformed domain.  out_bf16 may not alias x.                                       */
-int nvfp4_46_fake_quant(const void *x_bf16, const nvfp4_46_params *p, const float *alpha,
+int nvfp4_46_fake_quant(const void *x, const nvfp4_46_params *p, const float *alpha,
                         void *out_bf16, void *stream);
 
 /* Human-readable name of a status code (static storage, never NULL). */

@@ -19,6 +19,7 @@ ROWWISE, COLWISE, BOTH = 1, 2, 3
 BLOCK2D = 4          # nvfp4_46_dequantize's layout value for 16x16-tile data
 RTN, SR, SR_AFTER_RTN_SELECT = 0, 1, 2
 SEL_46_MSE, SEL_FORCE6, SEL_FORCE4, SEL_46_MAE, SEL_46_ABSMAX = 0, 1, 2, 3, 4
+X_BF16, X_F32 = 0, 1
 
 STATUS_NAMES = {0: "NVFP4_OK", 1: "NVFP4_ERR_NULL", 2: "NVFP4_ERR_SHAPE", 3: "NVFP4_ERR_ALIGN",
                 4: "NVFP4_ERR_PARAM", 5: "NVFP4_ERR_UNSUPPORTED", 6: "NVFP4_ERR_HIP"}
@@ -36,7 +37,7 @@ class Params(C.Structure):
     _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("layout", C.c_uint32),
                 ("rounding", C.c_uint32), ("select", C.c_uint32), ("rht", C.c_uint32),
                 ("sr_seed", C.c_uint64), ("rht_seed", C.c_uint64), ("fp8_max", C.c_float),
-                ("block2d", C.c_uint32)]
+                ("block2d", C.c_uint32), ("x_dtype", C.c_uint32)]
 
 
 class Nvfp4Error(RuntimeError):
@@ -96,8 +97,9 @@ def status_string(status: int) -> str:
 
 def make_params(rows: int, cols: int, layout: int = ROWWISE, rounding: int = RTN,
                 select: int = SEL_46_MSE, rht: int = 0, sr_seed: int = 0, rht_seed: int = 0,
-                fp8_max: float = 256.0, block2d: int = 0) -> Params:
-    return Params(rows, cols, layout, rounding, select, rht, sr_seed, rht_seed, fp8_max, block2d)
+                fp8_max: float = 256.0, block2d: int = 0, x_dtype: int = X_BF16) -> Params:
+    return Params(rows, cols, layout, rounding, select, rht, sr_seed, rht_seed, fp8_max, block2d,
+                  x_dtype)
 
 
 def _ptr(t):
@@ -148,17 +150,22 @@ def fake_quant_raw(x, params, alpha, out, stream=None) -> int:
 # ---- the same calls with output allocation and error checking ---------------------------
 
 def _shape_of(x):
-    assert x.dim() == 2 and x.dtype == torch.bfloat16
+    assert x.dim() == 2 and x.dtype in (torch.bfloat16, torch.float32)
     return int(x.shape[0]), int(x.shape[1])
+
+
+def x_dtype_of(x: torch.Tensor) -> int:
+    return X_F32 if x.dtype == torch.float32 else X_BF16
 
 
 def nvfp4_46_tensor_scale(x: torch.Tensor, layout: int = ROWWISE, rht: int = 0, rht_seed: int = 0,
                           fp8_max: float = 256.0, out: torch.Tensor | None = None,
                           stream=None) -> torch.Tensor:
-    """alpha (1-element fp32 device tensor) of a BF16 device tensor."""
+    """alpha (1-element fp32 device tensor) of a BF16 or fp32 device tensor."""
     rows, cols = _shape_of(x)
     alpha = out if out is not None else torch.empty(1, dtype=torch.float32, device=x.device)
-    p = make_params(rows, cols, layout=layout, rht=rht, rht_seed=rht_seed, fp8_max=fp8_max)
+    p = make_params(rows, cols, layout=layout, rht=rht, rht_seed=rht_seed, fp8_max=fp8_max,
+                    x_dtype=x_dtype_of(x))
     _check(tensor_scale_raw(x, p, alpha, stream), "nvfp4_46_tensor_scale")
     return alpha
 
@@ -192,7 +199,7 @@ def nvfp4_46_quantize(x: torch.Tensor, alpha: torch.Tensor, layout: int = ROWWIS
     o = out if out is not None else alloc_outputs(rows, cols, layout, x.device, want_choice,
                                                   block2d)
     p = make_params(rows, cols, layout, rounding, select, rht, sr_seed, rht_seed, fp8_max,
-                    block2d)
+                    block2d, x_dtype_of(x))
     _check(quantize_raw(x, p, alpha, o["codes_row"], o["scales_row"], o["codes_col"],
                         o["scales_col"], o["choice_row"], o["choice_col"], stream),
            "nvfp4_46_quantize")
@@ -216,9 +223,9 @@ def nvfp4_46_fake_quant(x: torch.Tensor, alpha: torch.Tensor, layout: int = ROWW
                         block2d: int = 0) -> torch.Tensor:
     rows, cols = _shape_of(x)
     if out is None:
-        out = torch.empty_like(x)
+        out = torch.empty(x.shape, dtype=torch.bfloat16, device=x.device)
     p = make_params(rows, cols, layout, rounding, select, rht, sr_seed, rht_seed, fp8_max,
-                    block2d)
+                    block2d, x_dtype_of(x))
     _check(fake_quant_raw(x, p, alpha, out, stream), "nvfp4_46_fake_quant")
     return out
 

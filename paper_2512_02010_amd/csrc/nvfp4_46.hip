@@ -98,6 +98,32 @@ NV_DEV void unpack16(const uint4 &w0, const uint4 &w1, float (&v)[16]) {
   }
 }
 
+// A block as it arrives from memory: two 128-bit pieces of BF16 or four of fp32.
+template <bool XF32>
+struct RawBlock {
+  static constexpr int kPieces = XF32 ? 4 : 2;
+  uint4 w[kPieces];
+};
+template <bool XF32>
+NV_DEV void load_block(const uint4 *p, RawBlock<XF32> &r) {
+#pragma unroll
+  for (int j = 0; j < RawBlock<XF32>::kPieces; ++j) r.w[j] = load_stream(p + j);
+}
+template <bool XF32>
+NV_DEV void unpack16(const RawBlock<XF32> &r, float (&v)[16]) {
+  if constexpr (XF32) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      v[4 * j] = u2f(r.w[j].x);
+      v[4 * j + 1] = u2f(r.w[j].y);
+      v[4 * j + 2] = u2f(r.w[j].z);
+      v[4 * j + 3] = u2f(r.w[j].w);
+    }
+  } else {
+    unpack16(r.w[0], r.w[1], v);
+  }
+}
+
 NV_DEV float wave_max(float m) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
@@ -134,17 +160,24 @@ __global__ void k_finish_alpha(float *alpha, float fp8_max) {
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 
-// max|x| without the transform: compare BF16 magnitudes as 15-bit integers.  Four
-// independent 128-bit loads per lane are in flight at a time.
+// max|x| without the transform: compare magnitudes as integers (15 bits of a BF16 value, 31
+// of an fp32 value).  Several independent 128-bit loads per lane are in flight at a time.
+template <bool XF32>
 __global__ __launch_bounds__(kThreads) void k_amax_plain(const uint4 *__restrict__ x, int64_t n16,
                                                          uint32_t *amax_bits) {
   u16x2 acc = {0, 0};
+  uint32_t acc32 = 0;
   auto fold = [&](const uint4 &w) {
     const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      uint32_t m = ww[j] & 0x7fff7fffu;
-      acc = __builtin_elementwise_max(acc, *reinterpret_cast<u16x2 *>(&m));
+      if constexpr (XF32) {
+        const uint32_t m = ww[j] & 0x7fffffffu;
+        acc32 = m > acc32 ? m : acc32;
+      } else {
+        uint32_t m = ww[j] & 0x7fff7fffu;
+        acc = __builtin_elementwise_max(acc, *reinterpret_cast<u16x2 *>(&m));
+      }
     }
   };
   constexpr int U = NVFP4_46_AMAX_UNROLL;
@@ -158,13 +191,13 @@ __global__ __launch_bounds__(kThreads) void k_amax_plain(const uint4 *__restrict
     for (int j = 0; j < U; ++j) fold(w[j]);
   }
   for (; i < n16; i += stride) fold(load_stream(x + i));
-  uint32_t top = acc.x > acc.y ? acc.x : acc.y;
-  publish_amax(u2f(top << 16), amax_bits);
+  const uint32_t top = XF32 ? acc32 : (uint32_t)(acc.x > acc.y ? acc.x : acc.y) << 16;
+  publish_amax(u2f(top), amax_bits);
 }
 
 // -------------------------------------------------------- rowwise (flat)
 
-template <int ROUNDING, int SELECT, bool RHT, int OUT>
+template <bool XF32, int ROUNDING, int SELECT, bool RHT, int OUT>
 __global__ __launch_bounds__(kThreads) void k_flat(
     const uint4 *__restrict__ x, const float *__restrict__ alpha_p, uint2 *__restrict__ codes,
     uint8_t *__restrict__ scales, uint8_t *__restrict__ choice, uint4 *__restrict__ out_bf16,
@@ -189,12 +222,13 @@ __global__ __launch_bounds__(kThreads) void k_flat(
 
   auto lanes_in_round = [&](uint32_t r) { return (r == rounds - 1) ? tail : (uint32_t)kThreads; };
 
-  // one block, already loaded as two 128-bit words; `live` = lanes of this round that
-  // hold a block (fewer than 256 only in the last round of a ragged tensor)
-  auto work = [&](uint32_t r, uint32_t live, const uint4 &w0, const uint4 &w1) {
+  // one block, already loaded; `live` = lanes of this round that hold a block (fewer than
+  // 256 only in the last round of a ragged tensor)
+  using Raw = RawBlock<XF32>;
+  auto work = [&](uint32_t r, uint32_t live, const Raw &raw) {
     const int64_t base = (int64_t)r * kThreads;
     float v[16], u[16];
-    unpack16(w0, w1, v);
+    unpack16(raw, v);
     if (RHT) {
       // the sign word depends on the block's position in its row only; with the usual
       // shapes a lane meets the same position in every round and keeps the word
@@ -243,7 +277,7 @@ __global__ __launch_bounds__(kThreads) void k_flat(
     }
   };
 
-  // Loads run one round ahead of the arithmetic: while a wave works on one block the two
+  // Loads run one round ahead of the arithmetic: while a wave works on one block the
   // 128-bit loads of its next block are already in flight (two register sets, used
   // alternately), so a round costs max(memory latency, arithmetic) instead of their sum.
   // The first round's loads also go out before the scale table is built.
@@ -254,30 +288,29 @@ __global__ __launch_bounds__(kThreads) void k_flat(
   // where the two control paths join): a round past the end re-reads the last round and
   // a lane past the end of a ragged last round re-reads that round's last block; what
   // they fetch is never used.
-  auto fetch = [&](uint32_t r, uint4 &w0, uint4 &w1) {
+  auto fetch = [&](uint32_t r, Raw &raw) {
     const uint32_t rr = r < rounds ? r : rounds - 1;
     const uint32_t last = lanes_in_round(rr) - 1;
     const uint32_t lane = tid < last ? tid : last;
-    const uint4 *xb = x + 2 * ((int64_t)rr * kThreads);
-    w0 = load_stream(xb + 2 * lane);
-    w1 = load_stream(xb + 2 * lane + 1);
+    const uint4 *xb = x + Raw::kPieces * ((int64_t)rr * kThreads);
+    load_block<XF32>(xb + Raw::kPieces * lane, raw);
   };
-  auto run = [&](uint32_t r, const uint4 &w0, const uint4 &w1) {
+  auto run = [&](uint32_t r, const Raw &raw) {
     const uint32_t live = lanes_in_round(r);
-    if (OUT == kOutFake || tid < live) work(r, live, w0, w1);
+    if (OUT == kOutFake || tid < live) work(r, live, raw);
   };
   const uint32_t step = gridDim.x;
   uint32_t r = blockIdx.x;
-  uint4 a0, a1, b0, b1;
-  fetch(r, a0, a1);
+  Raw a, b;
+  fetch(r, a);
   if (OUT != kOutAmax) sc = build_scale_table(tab, *alpha_p);
   while (r < rounds) {
-    fetch(r + step, b0, b1);
-    run(r, a0, a1);
+    fetch(r + step, b);
+    run(r, a);
     r += step;
     if (r >= rounds) break;
-    fetch(r + step, a0, a1);
-    run(r, b0, b1);
+    fetch(r + step, a);
+    run(r, b);
     r += step;
   }
   if (OUT == kOutAmax) publish_amax(amax, amax_bits);
@@ -341,16 +374,19 @@ NV_DEV TileCoord tile_of_workgroup(int64_t rows, int64_t cols) {
   return TileCoord{(int64_t)tr * TR, (int64_t)tc * TC, tc < nt_c};
 }
 
-template <int ROUNDING, int SELECT, bool RHT, bool WANT_ROW, int OUT>
+template <bool XF32, int ROUNDING, int SELECT, bool RHT, bool WANT_ROW, int OUT>
 __global__ __launch_bounds__(kThreads) void k_tile(
-    const uint16_t *__restrict__ x, const float *__restrict__ alpha_p,
+    const void *__restrict__ x_any, const float *__restrict__ alpha_p,
     uint8_t *__restrict__ codes_row, uint8_t *__restrict__ scales_row,
     uint8_t *__restrict__ choice_row, uint8_t *__restrict__ codes_col,
     uint8_t *__restrict__ scales_col, uint8_t *__restrict__ choice_col,
     uint16_t *__restrict__ out_bf16, uint32_t *amax_bits, int64_t rows, int64_t cols,
     uint64_t sr_seed, uint64_t rht_seed) {
   __shared__ ScaleTable tab;
-  __shared__ __align__(16) uint32_t tile[TR * TC / 2];  // BF16 pairs, row-major
+  // the tile, row-major: one 32-bit word (two BF16) or two (two fp32) per pair of columns
+  constexpr int kXW = XF32 ? 2 : 1;
+  using Raw = RawBlock<XF32>;
+  __shared__ __align__(16) uint32_t tile[TR * TC / 2 * kXW];
   // columnwise results wait here until a whole column segment can leave at once
   __shared__ uint2 stage_codes[OUT == kOutCodes ? kColItems : 1];     // [TC][TR/16]
   __shared__ uint8_t stage_scale[OUT == kOutCodes ? kColItems : 1];   // [TC][TR/16]
@@ -364,23 +400,27 @@ __global__ __launch_bounds__(kThreads) void k_tile(
   // ---- phase 1: global -> LDS (and the rowwise outputs on the way); the loads go out
   // before the scale table is built
   {
-    uint4 w[kRowBlocksPerLane][2];
+    constexpr int kElemsPerPiece = XF32 ? 4 : 8;
+    Raw w[kRowBlocksPerLane];
 #pragma unroll
     for (int j = 0; j < kRowBlocksPerLane; ++j) {
       const int unit = t + j * kThreads;
       const int row = unit / kRowBlocksPerTileRow, rbk = unit % kRowBlocksPerTileRow;
       const int64_t gr = r0 + row, gc = c0 + rbk * 16;
-      const uint4 *src = reinterpret_cast<const uint4 *>(x + gr * cols + gc);
-      w[j][0] = w[j][1] = make_uint4(0, 0, 0, 0);   // outside the tensor: zeros
-      if (gr < rows && gc < cols) w[j][0] = src[0];
-      if (gr < rows && gc + 8 < cols) w[j][1] = src[1];
+      // (gr * cols + gc) elements into x, counted in 128-bit pieces
+      const uint4 *src = static_cast<const uint4 *>(x_any) + (gr * cols + gc) / kElemsPerPiece;
+#pragma unroll
+      for (int q = 0; q < Raw::kPieces; ++q) {
+        w[j].w[q] = make_uint4(0, 0, 0, 0);   // outside the tensor: zeros
+        if (gr < rows && gc + q * kElemsPerPiece < cols) w[j].w[q] = src[q];
+      }
     }
 #pragma unroll
     for (int j = 0; j < kRowBlocksPerLane; ++j) {
       const int unit = t + j * kThreads;
-      uint4 *dst = reinterpret_cast<uint4 *>(tile) + unit * 2;
-      dst[0] = w[j][0];
-      dst[1] = w[j][1];
+      uint4 *dst = reinterpret_cast<uint4 *>(tile) + unit * Raw::kPieces;
+#pragma unroll
+      for (int q = 0; q < Raw::kPieces; ++q) dst[q] = w[j].w[q];
     }
   }
   ScaleConsts sc{};
@@ -398,8 +438,11 @@ __global__ __launch_bounds__(kThreads) void k_tile(
       const int64_t gr = r0 + row, gc = c0 + rbk * 16;
       if (gr < rows && gc < cols) {
         float v[16], u[16];
-        const uint4 *own = reinterpret_cast<const uint4 *>(tile) + unit * 2;
-        unpack16(own[0], own[1], v);
+        const uint4 *own = reinterpret_cast<const uint4 *>(tile) + unit * Raw::kPieces;
+        Raw mine;
+#pragma unroll
+        for (int q = 0; q < Raw::kPieces; ++q) mine.w[q] = own[q];
+        unpack16(mine, v);
         const int64_t k = gr * nb_per_row + (gc >> 4);
         if (ROUNDING != kRTN) {
 #pragma unroll
@@ -427,9 +470,15 @@ __global__ __launch_bounds__(kThreads) void k_tile(
     float va[16], vb[16], ua[16], ub[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const uint32_t pair = tile[(rb * 16 + i) * kColPairs + cp];
-      va[i] = bf16_lo(pair);
-      vb[i] = bf16_hi(pair);
+      if constexpr (XF32) {
+        const uint2 pair = reinterpret_cast<const uint2 *>(tile)[(rb * 16 + i) * kColPairs + cp];
+        va[i] = u2f(pair.x);
+        vb[i] = u2f(pair.y);
+      } else {
+        const uint32_t pair = tile[(rb * 16 + i) * kColPairs + cp];
+        va[i] = bf16_lo(pair);
+        vb[i] = bf16_hi(pair);
+      }
     }
     if (RHT) {
       const uint32_t sw = rht_sign_word(rht_seed, (uint64_t)(gr >> 4));
@@ -480,8 +529,10 @@ __global__ __launch_bounds__(kThreads) void k_tile(
 #pragma unroll
         for (int i = 0; i < 8; ++i) Db[8 + i] = h[i];
       }
+      // the BF16 pair takes the first word of the pair's slot
 #pragma unroll
-      for (int i = 0; i < 16; ++i) tile[(rb * 16 + i) * kColPairs + cp] = pack_bf16x2(Da[i], Db[i]);
+      for (int i = 0; i < 16; ++i)
+        tile[((rb * 16 + i) * kColPairs + cp) * kXW] = pack_bf16x2(Da[i], Db[i]);
     }
   }
   if (OUT == kOutAmax) {
@@ -510,9 +561,13 @@ __global__ __launch_bounds__(kThreads) void k_tile(
       const int idx = t + j * kThreads;
       const int row = idx / (TC / 8), seg = idx % (TC / 8);
       const int64_t gr = r0 + row, gc = c0 + seg * 8;
-      if (gr < rows && gc < cols)
-        store_as<kNtBf16>(reinterpret_cast<uint4 *>(out_bf16 + gr * cols + gc),
-                          reinterpret_cast<const uint4 *>(tile)[idx]);
+      if (gr < rows && gc < cols) {
+        // piece idx = the four column pairs 4*idx .. 4*idx+3 of the tile
+        const uint4 piece = XF32 ? make_uint4(tile[8 * idx], tile[8 * idx + 2], tile[8 * idx + 4],
+                                              tile[8 * idx + 6])
+                                 : reinterpret_cast<const uint4 *>(tile)[idx];
+        store_as<kNtBf16>(reinterpret_cast<uint4 *>(out_bf16 + gr * cols + gc), piece);
+      }
     }
   }
 }
@@ -570,9 +625,9 @@ __global__ __launch_bounds__(kThreads) void k_dequant_col(const uint8_t *__restr
 // each half, then the two halves), which is the order of the shuffles 4, 2, 1, 8.
 // Lane -> (tile, row): lanes 0-15 are the rows of one tile, the next sixteen lanes the
 // tile to its right, so four lanes 16 apart read 128 contiguous bytes of one row.
-template <int ROUNDING, int SELECT, int OUT>
+template <bool XF32, int ROUNDING, int SELECT, int OUT>
 __global__ __launch_bounds__(kThreads) void k_block2d(
-    const uint16_t *__restrict__ x, const float *__restrict__ alpha_p, uint8_t *__restrict__ codes,
+    const void *__restrict__ x_any, const float *__restrict__ alpha_p, uint8_t *__restrict__ codes,
     uint8_t *__restrict__ scales, uint8_t *__restrict__ choice, uint16_t *__restrict__ out_bf16,
     int64_t rows, int64_t cols, uint64_t sr_seed) {
   __shared__ ScaleTable tab;
@@ -587,9 +642,10 @@ __global__ __launch_bounds__(kThreads) void k_block2d(
     const int64_t tr = T / ncb, tc = T - tr * ncb;
     const int64_t row = tr * 16 + r_in_tile;
     const int64_t first = row * cols + tc * 16;           // flat index of the lane's first element
-    const uint4 *src = reinterpret_cast<const uint4 *>(x + first);
+    RawBlock<XF32> raw;
+    load_block<XF32>(static_cast<const uint4 *>(x_any) + first / (XF32 ? 4 : 8), raw);
     float v[16], u[16];
-    unpack16(src[0], src[1], v);
+    unpack16(raw, v);
     if (ROUNDING != kRTN) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) sr_uniforms4(sr_seed, (uint64_t)(first >> 2) + j, &u[4 * j]);
@@ -749,6 +805,7 @@ static int launch_status() { return hipGetLastError() == hipSuccess ? NVFP4_OK :
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 struct FlatArgs {
+  bool xf32;        // x holds fp32 values instead of BF16
   const uint4 *x;
   const float *alpha;
   uint2 *codes;
@@ -772,9 +829,14 @@ static void launch_flat(const FlatArgs &a) {
     const int period = (int)(a.nb_per_row / g);
     if (period <= grid / 2) grid -= grid % period;
   }
-  hipLaunchKernelGGL((k_flat<ROUNDING, SELECT, RHT, OUT>), dim3(grid), dim3(kThreads), 0, a.stream,
-                     a.x, a.alpha, a.codes, a.scales, a.choice, a.out, a.amax, a.nblocks,
-                     a.nb_per_row, a.sr_seed, a.rht_seed);
+  if (a.xf32)
+    hipLaunchKernelGGL((k_flat<true, ROUNDING, SELECT, RHT, OUT>), dim3(grid), dim3(kThreads), 0,
+                       a.stream, a.x, a.alpha, a.codes, a.scales, a.choice, a.out, a.amax,
+                       a.nblocks, a.nb_per_row, a.sr_seed, a.rht_seed);
+  else
+    hipLaunchKernelGGL((k_flat<false, ROUNDING, SELECT, RHT, OUT>), dim3(grid), dim3(kThreads), 0,
+                       a.stream, a.x, a.alpha, a.codes, a.scales, a.choice, a.out, a.amax,
+                       a.nblocks, a.nb_per_row, a.sr_seed, a.rht_seed);
 }
 
 template <int ROUNDING, int SELECT, bool RHT>
@@ -817,7 +879,8 @@ static void dispatch_flat(const FlatArgs &a, uint32_t rounding, uint32_t select,
 }
 
 struct TileArgs {
-  const uint16_t *x;
+  bool xf32;
+  const void *x;
   const float *alpha;
   uint8_t *codes_row, *scales_row, *choice_row, *codes_col, *scales_col, *choice_col;
   uint16_t *out;
@@ -834,10 +897,17 @@ static int tile_grid(int64_t rows, int64_t cols) {
 
 template <int ROUNDING, int SELECT, bool RHT, bool WANT_ROW, int OUT>
 static void launch_tile(const TileArgs &a) {
-  hipLaunchKernelGGL((k_tile<ROUNDING, SELECT, RHT, WANT_ROW, OUT>), dim3(tile_grid(a.rows, a.cols)),
-                     dim3(kThreads), 0, a.stream, a.x, a.alpha, a.codes_row, a.scales_row,
-                     a.choice_row, a.codes_col, a.scales_col, a.choice_col, a.out, a.amax, a.rows,
-                     a.cols, a.sr_seed, a.rht_seed);
+  const dim3 grid(tile_grid(a.rows, a.cols));
+  if (a.xf32)
+    hipLaunchKernelGGL((k_tile<true, ROUNDING, SELECT, RHT, WANT_ROW, OUT>), grid, dim3(kThreads), 0,
+                       a.stream, a.x, a.alpha, a.codes_row, a.scales_row, a.choice_row, a.codes_col,
+                       a.scales_col, a.choice_col, a.out, a.amax, a.rows, a.cols, a.sr_seed,
+                       a.rht_seed);
+  else
+    hipLaunchKernelGGL((k_tile<false, ROUNDING, SELECT, RHT, WANT_ROW, OUT>), grid, dim3(kThreads),
+                       0, a.stream, a.x, a.alpha, a.codes_row, a.scales_row, a.choice_row,
+                       a.codes_col, a.scales_col, a.choice_col, a.out, a.amax, a.rows, a.cols,
+                       a.sr_seed, a.rht_seed);
 }
 
 // variant: 0 = columnwise codes, 1 = columnwise codes + rht, 2 = both orientations,
@@ -869,7 +939,8 @@ static void dispatch_tile(const TileArgs &a, uint32_t rounding, uint32_t select,
 }
 
 struct Block2dArgs {
-  const uint16_t *x;
+  bool xf32;
+  const void *x;
   const float *alpha;
   uint8_t *codes, *scales, *choice;
   uint16_t *out;
@@ -882,14 +953,17 @@ template <int ROUNDING, int SELECT>
 static void launch_block2d(const Block2dArgs &a, int out) {
   const int64_t tiles = (a.rows / 16) * (a.cols / 16);
   const int grid = grid_for(tiles * 16, 16);
-  if (out == kOutCodes)
-    hipLaunchKernelGGL((k_block2d<ROUNDING, SELECT, kOutCodes>), dim3(grid), dim3(kThreads), 0,
-                       a.stream, a.x, a.alpha, a.codes, a.scales, a.choice, a.out, a.rows, a.cols,
-                       a.sr_seed);
-  else
-    hipLaunchKernelGGL((k_block2d<ROUNDING, SELECT, kOutFake>), dim3(grid), dim3(kThreads), 0,
-                       a.stream, a.x, a.alpha, a.codes, a.scales, a.choice, a.out, a.rows, a.cols,
-                       a.sr_seed);
+  auto go = [&](auto kernel) {
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), 0, a.stream, a.x, a.alpha, a.codes,
+                       a.scales, a.choice, a.out, a.rows, a.cols, a.sr_seed);
+  };
+  if (out == kOutCodes) {
+    if (a.xf32) go(k_block2d<true, ROUNDING, SELECT, kOutCodes>);
+    else go(k_block2d<false, ROUNDING, SELECT, kOutCodes>);
+  } else {
+    if (a.xf32) go(k_block2d<true, ROUNDING, SELECT, kOutFake>);
+    else go(k_block2d<false, ROUNDING, SELECT, kOutFake>);
+  }
 }
 
 template <int ROUNDING>
@@ -913,7 +987,8 @@ static int check_params(const void *x, const nvfp4_46_params *p, bool one_layout
   if (p->rows <= 0 || p->cols <= 0) return NVFP4_ERR_SHAPE;
   if (p->layout < 1u || p->layout > 3u) return NVFP4_ERR_PARAM;
   if (one_layout_only && p->layout == 3u) return NVFP4_ERR_PARAM;
-  if (p->rounding > NVFP4_SR_AFTER_RTN_SELECT || p->select > NVFP4_SEL_46_ABSMAX || p->rht > 1u || p->block2d > 1u)
+  if (p->rounding > NVFP4_SR_AFTER_RTN_SELECT || p->select > NVFP4_SEL_46_ABSMAX || p->rht > 1u ||
+      p->block2d > 1u || p->x_dtype > NVFP4_X_F32)
     return NVFP4_ERR_PARAM;
   if (!(p->fp8_max > 0.0f) || !(p->fp8_max <= 448.0f)) return NVFP4_ERR_PARAM;
   if ((p->layout & NVFP4_ROWWISE) && (p->cols % 16) != 0) return NVFP4_ERR_SHAPE;
@@ -937,25 +1012,31 @@ using namespace nvfp4_46;
 
 extern "C" {
 
-int nvfp4_46_tensor_scale(const void *x_bf16, const nvfp4_46_params *p, float *alpha,
-                          void *stream) {
+int nvfp4_46_tensor_scale(const void *x, const nvfp4_46_params *p, float *alpha, void *stream) {
   if (!alpha) return NVFP4_ERR_NULL;
-  int rc = check_params(x_bf16, p, false);
+  int rc = check_params(x, p, false);
   if (rc != NVFP4_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   uint32_t *amax = reinterpret_cast<uint32_t *>(alpha);
   hipLaunchKernelGGL(k_store_u32, dim3(1), dim3(1), 0, s, amax, 0u);
   const int64_t n = p->rows * p->cols;
+  const bool xf32 = p->x_dtype == NVFP4_X_F32;
   if (!p->rht) {
-    const int64_t n16 = n / 8;  // 128-bit pieces (n is a multiple of 8 by the shape checks)
-    hipLaunchKernelGGL(k_amax_plain, dim3(grid_for(n16, NVFP4_46_AMAX_WG_PER_CU)), dim3(kThreads), 0, s,
-                       static_cast<const uint4 *>(x_bf16), n16, amax);
+    // 128-bit pieces (n is a multiple of 8 by the shape checks)
+    const int64_t n16 = xf32 ? n / 4 : n / 8;
+    const dim3 grid(grid_for(n16, NVFP4_46_AMAX_WG_PER_CU));
+    if (xf32)
+      hipLaunchKernelGGL(k_amax_plain<true>, grid, dim3(kThreads), 0, s,
+                         static_cast<const uint4 *>(x), n16, amax);
+    else
+      hipLaunchKernelGGL(k_amax_plain<false>, grid, dim3(kThreads), 0, s,
+                         static_cast<const uint4 *>(x), n16, amax);
   } else if (p->layout == NVFP4_ROWWISE) {
-    FlatArgs a{static_cast<const uint4 *>(x_bf16), nullptr, nullptr, nullptr, nullptr, nullptr, amax,
+    FlatArgs a{xf32, static_cast<const uint4 *>(x), nullptr, nullptr, nullptr, nullptr, nullptr, amax,
                n / 16, (uint32_t)(p->cols / 16), 0, p->rht_seed, s};
     launch_flat<kRTN, kSel46, true, kOutAmax>(a);
   } else {
-    TileArgs a{static_cast<const uint16_t *>(x_bf16), nullptr, nullptr, nullptr, nullptr, nullptr,
+    TileArgs a{xf32, x, nullptr, nullptr, nullptr, nullptr, nullptr,
                nullptr, nullptr, nullptr, amax, p->rows, p->cols, 0, p->rht_seed, s};
     launch_tile<kRTN, kSel46, true, false, kOutAmax>(a);
   }
@@ -963,12 +1044,13 @@ int nvfp4_46_tensor_scale(const void *x_bf16, const nvfp4_46_params *p, float *a
   return launch_status();
 }
 
-int nvfp4_46_quantize(const void *x_bf16, const nvfp4_46_params *p, const float *alpha,
+int nvfp4_46_quantize(const void *x, const nvfp4_46_params *p, const float *alpha,
                       void *codes_row, void *scales_row, void *codes_col, void *scales_col,
                       void *choice_row, void *choice_col, void *stream) {
   if (!alpha) return NVFP4_ERR_NULL;
-  int rc = check_params(x_bf16, p, false);
+  int rc = check_params(x, p, false);
   if (rc != NVFP4_OK) return rc;
+  const bool xf32 = p->x_dtype == NVFP4_X_F32;
   const bool want_row = p->layout & NVFP4_ROWWISE, want_col = p->layout & NVFP4_COLWISE;
   if (want_row && (!codes_row || !scales_row)) return NVFP4_ERR_NULL;
   if (want_col && (!codes_col || !scales_col)) return NVFP4_ERR_NULL;
@@ -979,19 +1061,19 @@ int nvfp4_46_quantize(const void *x_bf16, const nvfp4_46_params *p, const float 
     return NVFP4_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (p->block2d) {
-    Block2dArgs a{static_cast<const uint16_t *>(x_bf16), alpha, static_cast<uint8_t *>(codes_row),
+    Block2dArgs a{xf32, x, alpha, static_cast<uint8_t *>(codes_row),
                   static_cast<uint8_t *>(scales_row), static_cast<uint8_t *>(choice_row), nullptr,
                   p->rows, p->cols, p->sr_seed, s};
     dispatch_block2d(a, p->rounding, p->select, kOutCodes);
     return launch_status();
   }
   if (!want_col) {
-    FlatArgs a{static_cast<const uint4 *>(x_bf16), alpha, static_cast<uint2 *>(codes_row),
+    FlatArgs a{xf32, static_cast<const uint4 *>(x), alpha, static_cast<uint2 *>(codes_row),
                static_cast<uint8_t *>(scales_row), static_cast<uint8_t *>(choice_row), nullptr,
                nullptr, p->rows * p->cols / 16, (uint32_t)(p->cols / 16), p->sr_seed, p->rht_seed, s};
     dispatch_flat(a, p->rounding, p->select, p->rht != 0, kOutCodes);
   } else {
-    TileArgs a{static_cast<const uint16_t *>(x_bf16), alpha, static_cast<uint8_t *>(codes_row),
+    TileArgs a{xf32, x, alpha, static_cast<uint8_t *>(codes_row),
                static_cast<uint8_t *>(scales_row), static_cast<uint8_t *>(choice_row),
                static_cast<uint8_t *>(codes_col), static_cast<uint8_t *>(scales_col),
                static_cast<uint8_t *>(choice_col), nullptr, nullptr, p->rows, p->cols, p->sr_seed,
@@ -1032,26 +1114,27 @@ int nvfp4_46_dequantize(const void *codes, const void *scales, const float *alph
   return launch_status();
 }
 
-int nvfp4_46_fake_quant(const void *x_bf16, const nvfp4_46_params *p, const float *alpha,
+int nvfp4_46_fake_quant(const void *x, const nvfp4_46_params *p, const float *alpha,
                         void *out_bf16, void *stream) {
   if (!alpha || !out_bf16) return NVFP4_ERR_NULL;
-  int rc = check_params(x_bf16, p, true);
+  int rc = check_params(x, p, true);
   if (rc != NVFP4_OK) return rc;
+  const bool xf32 = p->x_dtype == NVFP4_X_F32;
   if (!aligned16(out_bf16)) return NVFP4_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (p->block2d) {
-    Block2dArgs a{static_cast<const uint16_t *>(x_bf16), alpha, nullptr, nullptr, nullptr,
+    Block2dArgs a{xf32, x, alpha, nullptr, nullptr, nullptr,
                   static_cast<uint16_t *>(out_bf16), p->rows, p->cols, p->sr_seed, s};
     dispatch_block2d(a, p->rounding, p->select, kOutFake);
     return launch_status();
   }
   if (p->layout == NVFP4_ROWWISE) {
-    FlatArgs a{static_cast<const uint4 *>(x_bf16), alpha, nullptr, nullptr, nullptr,
+    FlatArgs a{xf32, static_cast<const uint4 *>(x), alpha, nullptr, nullptr, nullptr,
                static_cast<uint4 *>(out_bf16), nullptr, p->rows * p->cols / 16,
                (uint32_t)(p->cols / 16), p->sr_seed, p->rht_seed, s};
     dispatch_flat(a, p->rounding, p->select, p->rht != 0, kOutFake);
   } else {
-    TileArgs a{static_cast<const uint16_t *>(x_bf16), alpha, nullptr, nullptr, nullptr, nullptr,
+    TileArgs a{xf32, x, alpha, nullptr, nullptr, nullptr, nullptr,
                nullptr, nullptr, static_cast<uint16_t *>(out_bf16), nullptr, p->rows, p->cols,
                p->sr_seed, p->rht_seed, s};
     dispatch_tile(a, p->rounding, p->select, p->rht ? 4 : 3);

@@ -28,14 +28,16 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_params_struct_layout_matches_header():
-    assert C.sizeof(B.Params) == 56
+    assert C.sizeof(B.Params) == 64
     offs = {f[0]: getattr(B.Params, f[0]).offset for f in B.Params._fields_}
     assert offs == {"rows": 0, "cols": 8, "layout": 16, "rounding": 20, "select": 24, "rht": 28,
-                    "sr_seed": 32, "rht_seed": 40, "fp8_max": 48, "block2d": 52}
+                    "sr_seed": 32, "rht_seed": 40, "fp8_max": 48, "block2d": 52,
+                    "x_dtype": 56}
     # enum values quoted in the header
     for name, val in (("NVFP4_ROWWISE", 1), ("NVFP4_COLWISE", 2), ("NVFP4_RTN", 0), ("NVFP4_SR", 1), ("NVFP4_SR_AFTER_RTN_SELECT", 2),
                       ("NVFP4_SEL_46_MSE", 0), ("NVFP4_SEL_FORCE6", 1), ("NVFP4_SEL_FORCE4", 2),
-                      ("NVFP4_SEL_46_MAE", 3), ("NVFP4_SEL_46_ABSMAX", 4)):
+                      ("NVFP4_SEL_46_MAE", 3), ("NVFP4_SEL_46_ABSMAX", 4), ("NVFP4_X_BF16", 0),
+                      ("NVFP4_X_F32", 1)):
         assert re.search(rf"{name} = {val}\b", HEADER), name
 
 
@@ -65,6 +67,7 @@ def test_quantize_validation_codes():
     assert _q(B.make_params(32, 64, layout=0)) == 4 and _q(B.make_params(32, 64, layout=4)) == 4
     assert _q(B.make_params(32, 64, rounding=3)) == 4 and _q(B.make_params(32, 64, select=5)) == 4
     assert _q(B.make_params(32, 64, rht=2)) == 4
+    assert _q(B.make_params(32, 64, x_dtype=2)) == 4
     assert _q(B.make_params(32, 64, fp8_max=0.0)) == 4
     assert _q(B.make_params(32, 64, fp8_max=449.0)) == 4
     assert _q(B.make_params(32, 64, fp8_max=float("nan"))) == 4

@@ -39,7 +39,7 @@ def check_case(x: torch.Tensor, layout=B.ROWWISE, rounding=B.RTN, select=B.SEL_4
     rows, cols = x.shape
     _log(f"case {tag} shape={rows}x{cols} layout={layout} rounding={rounding} select={select} "
          f"rht={rht} fp8_max={fp8_max}")
-    xb = wl.bf16_bits(x)
+    xb = wl.host_array(x)          # BF16 bit patterns, or the fp32 values themselves
     xd = x.cuda()
     kw = dict(rounding=rounding, select=select, rht=rht, sr_seed=SR_SEED, rht_seed=RHT_SEED)
     layouts = [l for l in (B.ROWWISE, B.COLWISE) if layout & l]
@@ -203,6 +203,76 @@ def test_block2d_transpose_consistency_on_gpu():
     assert torch.equal(dt, d.t().contiguous())
 
 
+# ------------------------------------------------------------------ fp32 input (FP32 master weights)
+
+@pytest.mark.parametrize("shape", [(16, 16), (144, 272), (257, 48), (1000, 4112)])
+def test_fp32_input_rowwise(shape):
+    check_case(wl.make("c2", *shape, dtype=torch.float32), tag="c2-f32-row")
+
+
+@pytest.mark.parametrize("shape", [(16, 8), (144, 264), (272, 136), (1008, 4104)])
+def test_fp32_input_columnwise(shape):
+    check_case(wl.make("c2", *shape, dtype=torch.float32), layout=B.COLWISE, tag="c2-f32-col")
+
+
+@pytest.mark.parametrize("shape", [(48, 176), (256, 384), (1008, 2064)])
+def test_fp32_input_both_layouts(shape):
+    check_case(wl.make("c4", *shape, dtype=torch.float32), layout=B.BOTH, tag="c4-f32-both")
+
+
+@pytest.mark.parametrize("layout", [B.ROWWISE, B.COLWISE])
+@pytest.mark.parametrize("select", [B.SEL_46_MSE, B.SEL_FORCE4, B.SEL_46_MAE, B.SEL_46_ABSMAX])
+@pytest.mark.parametrize("rounding,rht", [(B.RTN, 0), (B.SR, 1), (B.SR_AFTER_RTN_SELECT, 0),
+                                          (B.RTN, 1)])
+def test_fp32_input_option_matrix(layout, select, rounding, rht):
+    check_case(wl.make("c5", 160, 304, dtype=torch.float32), layout=layout, rounding=rounding,
+               select=select, rht=rht, tag="c5-f32-matrix")
+
+
+@pytest.mark.parametrize("kind", ["zeros", "neg_zeros", "one_hot", "tiny", "wide_range", "ties",
+                                  "bf16_small", "bf16_large"])
+def test_fp32_input_adversarial(kind):
+    check_case(wl.adversarial(kind, dtype=torch.float32), layout=B.BOTH, tag=f"adv-f32-{kind}")
+
+
+def test_fp32_input_decision_stress():
+    x = wl.adversarial("decision_stress", 1024, 2048, dtype=torch.float32)
+    out = check_case(x, layout=B.BOTH, tag="decision-stress-f32")
+    assert 0.02 < float(_np(out["choice_row"]).mean()) < 0.9
+
+
+def test_fp32_input_sees_the_low_mantissa_bits():
+    """The fp32 path must not round x to BF16 on the way in: its result differs from that of
+    the BF16-rounded tensor, and equals it when the values are BF16 values to begin with."""
+    xf = wl.make("c2", 256, 512, dtype=torch.float32)
+    xr = xf.to(torch.bfloat16)
+    alpha = B.nvfp4_46_tensor_scale(xf.cuda())
+    o32 = B.nvfp4_46_quantize(xf.cuda(), alpha)
+    o16 = B.nvfp4_46_quantize(xr.cuda(), alpha)
+    assert not torch.equal(o32["codes_row"], o16["codes_row"])
+    o16f = B.nvfp4_46_quantize(xr.float().cuda(), alpha)
+    for k in ("codes_row", "scales_row", "choice_row"):
+        assert torch.equal(o16f[k], o16[k])
+
+
+@pytest.mark.parametrize("select", [B.SEL_46_MSE, B.SEL_46_MAE])
+@pytest.mark.parametrize("rounding", [B.RTN, B.SR])
+def test_fp32_input_block2d(select, rounding):
+    x = wl.make("c2", 272, 400, dtype=torch.float32)
+    rows, cols = x.shape
+    xd = x.cuda()
+    alpha = B.nvfp4_46_tensor_scale(xd)
+    a = float(alpha.item())
+    assert _alpha_bits(a) == _alpha_bits(ref.tensor_scale(x.numpy()))
+    kw = dict(rounding=rounding, select=select, sr_seed=SR_SEED)
+    c_ref, s_ref, f_ref, d_ref = ref.quantize_2d(x.numpy(), a, **kw)
+    out = B.nvfp4_46_quantize(xd, alpha, block2d=1, **kw)
+    assert np.array_equal(_np(out["scales_row"]), s_ref)
+    assert np.array_equal(_np(out["choice_row"]), f_ref)
+    assert np.array_equal(_np(out["codes_row"]), c_ref)
+    assert np.array_equal(_bits(B.nvfp4_46_fake_quant(xd, alpha, block2d=1, **kw)), d_ref)
+
+
 def test_caller_supplied_alpha_replays_table3():
     # Table 3's blocks with the tensor scale written as 1: [10,20,30,40] -> 4, [15,30,120,180] -> 6
     x = torch.zeros((16, 32), dtype=torch.float32)
@@ -326,6 +396,11 @@ def test_workload_c2_full_rowwise_rtn_and_mse():
     mse6 = float(((B.nvfp4_46_fake_quant(xd, alpha, select=B.SEL_FORCE6).double() - xf) ** 2).mean())
     _log(f"c2: MSE 4/6 = {mse46:.6e}, MSE scale-to-6 = {mse6:.6e}, ratio {mse46 / mse6:.4f}")
     assert mse46 <= mse6
+
+
+def test_workload_c2_full_fp32_weights_both_layouts():
+    # the weight matrix of Fig. 3 as stored (FP32), both operand orientations from one read
+    check_case(wl.make("c2", dtype=torch.float32), layout=B.BOTH, tag="c2-f32-full")
 
 
 def test_workload_c3_full_fake_quant():
