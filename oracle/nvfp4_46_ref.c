@@ -631,6 +631,40 @@ int nvfp4_46_ref_block_errors(const uint16_t *x, int64_t rows, int64_t cols, int
                                        sr_seed, rht_seed, alpha, E6, E4);
 }
 
+/* Matrix product of two NVFP4 tensors, the consumer of the quantizer's output (Fig. 3: FPROP,
+ * DGRAD and WGRAD all multiply two NVFP4 operands quantized along the contraction axis):
+ *   C[m][n] = alpha_a * alpha_b * sum_k a[m][k] * b[n][k],
+ *   a[m][k] = grid(code_a[m][k]) * value(scale_a[m][k/16]), b likewise
+ * with both operands in the rowwise layout over the contraction axis K (codes [M][K/2] and
+ * [N][K/2], scales [M][K/16] and [N][K/16]).  The paper does not state the accumulation
+ * arithmetic of the matrix unit (READING): this is the plain definition, every product and the
+ * running sum in fp64 in the order k = 0, 1, ...; each product is exact in fp64 (at most 12
+ * significant bits) and so is alpha_a * alpha_b.  `C` gets the fp64 values; `Cabs` (optional)
+ * gets alpha_a * alpha_b * sum_k |a[m][k] * b[n][k]|, the quantity an error bound for a
+ * lower-precision accumulation is stated in. */
+int nvfp4_46_ref_gemm(const uint8_t *codes_a, const uint8_t *scales_a, float alpha_a,
+                      const uint8_t *codes_b, const uint8_t *scales_b, float alpha_b, int64_t M,
+                      int64_t N, int64_t K, double *C, double *Cabs) {
+  const int64_t KB = K / BLOCK;
+  const double alpha = (double)alpha_a * (double)alpha_b;
+#pragma omp parallel for schedule(static)
+  for (int64_t m = 0; m < M; ++m)
+    for (int64_t n = 0; n < N; ++n) {
+      double acc = 0.0, acc_abs = 0.0;
+      for (int64_t k = 0; k < K; ++k) {
+        uint8_t ba = codes_a[m * (K / 2) + k / 2], bb = codes_b[n * (K / 2) + k / 2];
+        uint8_t ca = (k & 1) ? (ba >> 4) : (ba & 15), cb = (k & 1) ? (bb >> 4) : (bb & 15);
+        double a = (double)ref_e2m1_decode(ca) * (double)ref_e4m3_decode(scales_a[m * KB + k / BLOCK]);
+        double b = (double)ref_e2m1_decode(cb) * (double)ref_e4m3_decode(scales_b[n * KB + k / BLOCK]);
+        acc += a * b;
+        acc_abs += fabs(a * b);
+      }
+      C[m * N + n] = alpha * acc;
+      if (Cabs) Cabs[m * N + n] = alpha * acc_abs;
+    }
+  return 0;
+}
+
 /* Range helpers for exhaustive comparisons of the scalar codecs: evaluate a
  * codec on n consecutive fp32 bit patterns starting at `first_bits`. */
 void ref_e2m1_rtn_bits_range(uint32_t first_bits, int64_t n, uint8_t *out) {
