@@ -8,7 +8,7 @@ from pathlib import Path
 
 PKG = Path(__file__).resolve().parent
 ROOT = PKG.parent
-SRC = PKG / "csrc" / "nvfp4_46.hip"
+SRCS = [PKG / "csrc" / "nvfp4_46.hip", PKG / "csrc" / "gemm.hip"]
 SO = PKG / "libnvfp4_46.so"
 
 # -ffp-contract=off: the method's arithmetic is one rounding per operation.
@@ -39,7 +39,7 @@ def build(out: Path | None = None, defines: dict | None = None, extra: list | No
     d.update(defines or {})
     tmp = out.with_suffix(f".tmp{os.getpid()}.so")
     cmd = [hipcc(), *HIPCC_FLAGS, *[f"-D{k}={v}" for k, v in d.items()], *(extra or []),
-           f"-I{ROOT / 'include'}", f"-I{PKG / 'csrc'}", str(SRC), "-o", str(tmp)]
+           f"-I{ROOT / 'include'}", f"-I{PKG / 'csrc'}", *map(str, SRCS), "-o", str(tmp)]
     subprocess.run(cmd, check=True)
     os.replace(tmp, out)
     return out

@@ -1,0 +1,240 @@
+// NVFP4 x NVFP4 matrix product for gfx950: C = alpha_a * alpha_b * A . B^T with both operands
+// in the quantizer's rowwise layout over the contraction axis (see include/nvfp4_46.h).
+//
+// gfx950's block-scaled FP4 matrix instructions take one power-of-two scale per 32 values;
+// NVFP4 carries an E4M3 scale (three mantissa bits) per 16, so the operands are expanded on
+// the way into the matrix unit instead: value(code) * value(scale) has at most six
+// significant bits and lies in [2^-10, 2688], hence is exact in FP16, and the FP16 matrix
+// instruction (v_mfma_f32_32x32x16_f16, fp32 accumulation) multiplies exact operands.  The
+// only rounding is in the fp32 accumulation and in the final scaling.
+//
+// Data movement: the operands stay packed (4 bits per value) all the way into registers.
+// A workgroup of four waves owns a 256 x 256 tile of C, each wave a 128 x 128 quarter
+// (4 x 4 matrix-instruction tiles, 256 accumulator registers per lane).  Per chunk of 128
+// contraction steps the workgroup copies 256 rows x 64 bytes of codes and 256 x 8 scale
+// bytes of each operand into LDS with coalesced loads (the next chunk's loads are in flight
+// while the current one is multiplied); a lane then reads 16 bytes (32 codes) per operand
+// tile from LDS and expands them with v_cvt_scalef32_pk_f16_fp4 (x 256, exact) and one
+// packed FP16 multiplication by the scale (times 2^-8, built from the scale byte by a
+// shift).  Which eight contraction indices a lane feeds to a given matrix instruction is
+// the same for A and for B, which is all the sum needs.
+#include <hip/hip_runtime.h>
+
+#include "codec.hpp"
+#include "nvfp4_46.h"
+
+namespace nvfp4_46 {
+
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kGemmThreads = 256;
+constexpr int GT = 256;                  // rows of A (and of B) per workgroup tile
+constexpr int GK = 128;                  // contraction steps per LDS chunk
+constexpr int kCodeRow = GK / 2 + 16;    // bytes per operand row in LDS: 64 of codes + 16 of padding,
+                                         // so that 16 lanes reading 16 bytes from 16 rows hit 16
+                                         // different bank groups (80 = 5 * 16, 5 coprime to 16)
+
+// Eight codes (one 32-bit word) times one scale -> eight FP16 values, exactly.
+// `sv` is the scale as FP16 bits (byte << 7), i.e. value(scale) * 2^-8; the conversion
+// multiplies by 2^8.
+NV_DEV h8 expand8(uint32_t word, uint32_t sv_bits) {
+  const _Float16 sv = __builtin_bit_cast(_Float16, (unsigned short)sv_bits);
+  const h2 s = {sv, sv};
+  const h2 p0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(word, 256.0f, 0) * s;
+  const h2 p1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(word, 256.0f, 1) * s;
+  const h2 p2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(word, 256.0f, 2) * s;
+  const h2 p3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(word, 256.0f, 3) * s;
+  return h8{p0.x, p0.y, p1.x, p1.y, p2.x, p2.y, p3.x, p3.y};
+}
+
+// KFULL: K is a multiple of 128, so every chunk is whole and scale rows are 8-byte aligned.
+template <bool KFULL, bool OUTF32>
+__global__ __launch_bounds__(kGemmThreads) void k_gemm(
+    const uint8_t *__restrict__ codes_a, const uint8_t *__restrict__ scales_a,
+    const float *__restrict__ alpha_a, const uint8_t *__restrict__ codes_b,
+    const uint8_t *__restrict__ scales_b, const float *__restrict__ alpha_b,
+    void *__restrict__ out, int64_t M, int64_t N, int64_t K, uint32_t tiles_n) {
+  __shared__ __align__(16) uint8_t lds_codes[2][GT * kCodeRow];   // [A, B][row][80]
+  __shared__ __align__(8) uint2 lds_scales[2][GT];                // [A, B][row] -> 8 scale bytes
+
+  const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+  const uint32_t r = lane & 31u, g = lane >> 5;        // row within a 32-row tile, half of K
+  const uint32_t wm = wave >> 1, wn = wave & 1u;       // the wave's quarter of the tile
+  const uint32_t tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_m * tiles_n;
+  const int64_t m0 = (int64_t)tile_m * GT, n0 = (int64_t)tile_n * GT;
+  const int64_t row_codes = K / 2, row_scales = K / 16;
+
+  // ---- global -> registers -> LDS.  Codes: 1024 16-byte pieces per operand and chunk,
+  // four per thread (piece = row * 4 + unit, so four lanes read 64 contiguous bytes);
+  // scales: thread t fetches row t's eight bytes.  Rows past the end of an operand re-read
+  // its last row (their products are never stored).
+  uint4 ga[4], gb[4];
+  uint2 gsa, gsb;
+  const uint32_t ld_row = t >> 2, ld_unit = t & 3u;
+  auto clamp_row = [](int64_t row, int64_t n) { return row < n ? row : n - 1; };
+  auto fetch = [&](int64_t k0) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int64_t ra = clamp_row(m0 + ld_row + 64 * q, M), rb = clamp_row(n0 + ld_row + 64 * q, N);
+      const int64_t kb = k0 / 2 + ld_unit * 16;        // byte offset of the piece in its row
+      ga[q] = gb[q] = make_uint4(0, 0, 0, 0);
+      if (KFULL || k0 + ld_unit * 32 < K) {
+        ga[q] = *reinterpret_cast<const uint4 *>(codes_a + ra * row_codes + kb);
+        gb[q] = *reinterpret_cast<const uint4 *>(codes_b + rb * row_codes + kb);
+      }
+    }
+    const int64_t ra = clamp_row(m0 + t, M), rb = clamp_row(n0 + t, N);
+    if (KFULL) {
+      gsa = *reinterpret_cast<const uint2 *>(scales_a + ra * row_scales + k0 / 16);
+      gsb = *reinterpret_cast<const uint2 *>(scales_b + rb * row_scales + k0 / 16);
+    } else {
+      // two scale bytes (32 contraction steps) at a time; K is a multiple of 32
+      uint32_t wa[4], wb[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        wa[q] = wb[q] = 0;
+        if (k0 + 32 * q < K) {
+          wa[q] = *reinterpret_cast<const uint16_t *>(scales_a + ra * row_scales + k0 / 16 + 2 * q);
+          wb[q] = *reinterpret_cast<const uint16_t *>(scales_b + rb * row_scales + k0 / 16 + 2 * q);
+        }
+      }
+      gsa = make_uint2(wa[0] | (wa[1] << 16), wa[2] | (wa[3] << 16));
+      gsb = make_uint2(wb[0] | (wb[1] << 16), wb[2] | (wb[3] << 16));
+    }
+  };
+  auto stash = [&]() {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const uint32_t off = (ld_row + 64 * q) * kCodeRow + ld_unit * 16;
+      *reinterpret_cast<uint4 *>(&lds_codes[0][off]) = ga[q];
+      *reinterpret_cast<uint4 *>(&lds_codes[1][off]) = gb[q];
+    }
+    lds_scales[0][t] = gsa;
+    lds_scales[1][t] = gsb;
+  };
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  // ---- one chunk out of LDS: two halves of 64 contraction steps; in each, a lane takes
+  // 16 bytes (32 codes, two scale blocks) per operand tile and feeds four matrix steps
+  const uint32_t a_row0 = wm * 128 + r, b_row0 = wn * 128 + r;
+  auto multiply = [&]() {
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      uint4 ra[4], rb[4];
+      uint32_t sa[4], sb[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t rowa = a_row0 + 32 * i, rowb = b_row0 + 32 * i;
+        ra[i] = *reinterpret_cast<const uint4 *>(&lds_codes[0][rowa * kCodeRow + (2 * half + g) * 16]);
+        rb[i] = *reinterpret_cast<const uint4 *>(&lds_codes[1][rowb * kCodeRow + (2 * half + g) * 16]);
+        const uint2 wa = lds_scales[0][rowa], wb = lds_scales[1][rowb];
+        // the lane's two scale bytes of this half: blocks 4*half + 2*g and + 1
+        sa[i] = ((half ? wa.y : wa.x) >> (16 * g)) & 0xffffu;
+        sb[i] = ((half ? wb.y : wb.x) >> (16 * g)) & 0xffffu;
+      }
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        h8 fa[4], fb[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const uint32_t wa = s == 0 ? ra[i].x : s == 1 ? ra[i].y : s == 2 ? ra[i].z : ra[i].w;
+          const uint32_t wb = s == 0 ? rb[i].x : s == 1 ? rb[i].y : s == 2 ? rb[i].z : rb[i].w;
+          // scale byte s/2 of the pair, moved to FP16's exponent/mantissa position
+          const uint32_t va = s < 2 ? (sa[i] & 0xffu) << 7 : (sa[i] >> 1) & 0x7f80u;
+          const uint32_t vb = s < 2 ? (sb[i] & 0xffu) << 7 : (sb[i] >> 1) & 0x7f80u;
+          fa[i] = expand8(wa, va);
+          fb[i] = expand8(wb, vb);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+      }
+    }
+  };
+
+  const int64_t nchunks = (K + GK - 1) / GK;
+  fetch(0);
+  stash();
+  __syncthreads();
+  for (int64_t c = 0; c < nchunks; ++c) {
+    const bool more = c + 1 < nchunks;
+    if (more) fetch((c + 1) * GK);
+    multiply();
+    __syncthreads();          // everyone has read chunk c
+    if (more) stash();
+    __syncthreads();          // chunk c + 1 is in place
+  }
+
+  // ---- epilogue: accumulator element v of tile (i, j) is C[32 i + 8 (v / 4) + 4 g + v % 4]
+  // [32 j + r] within the wave's quarter
+  const float scale = alpha_a[0] * alpha_b[0];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int64_t col = n0 + wn * 128 + 32 * j + r;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int64_t row = m0 + wm * 128 + 32 * i + 8 * (v / 4) + 4 * g + (v % 4);
+        if (row < M && col < N) {
+          const float c = acc[i][j][v] * scale;
+          if (OUTF32)
+            static_cast<float *>(out)[row * N + col] = c;
+          else
+            static_cast<uint16_t *>(out)[row * N + col] = (uint16_t)pack_bf16x2(c, 0.0f);
+        }
+      }
+    }
+}
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace nvfp4_46
+
+using namespace nvfp4_46;
+
+extern "C" int nvfp4_46_gemm(const void *codes_a, const void *scales_a, const float *alpha_a,
+                             const void *codes_b, const void *scales_b, const float *alpha_b,
+                             int64_t M, int64_t N, int64_t K, uint32_t out_dtype, void *out,
+                             void *stream) {
+  if (!codes_a || !scales_a || !alpha_a || !codes_b || !scales_b || !alpha_b || !out)
+    return NVFP4_ERR_NULL;
+  if (M <= 0 || N <= 0 || K <= 0 || (K % 32) != 0) return NVFP4_ERR_SHAPE;
+  if (M > (int64_t)1 << 31 || N > (int64_t)1 << 31 || K > (int64_t)1 << 31 ||
+      M * K > (int64_t)1 << 40 || N * K > (int64_t)1 << 40 || M * N > (int64_t)1 << 40)
+    return NVFP4_ERR_SHAPE;
+  if (out_dtype > NVFP4_OUT_F32) return NVFP4_ERR_PARAM;
+  if (!aligned16(codes_a) || !aligned16(scales_a) || !aligned16(codes_b) || !aligned16(scales_b) ||
+      !aligned16(out))
+    return NVFP4_ERR_ALIGN;
+  const int64_t tiles_m = (M + GT - 1) / GT, tiles_n = (N + GT - 1) / GT;
+  if (tiles_m * tiles_n > (int64_t)1 << 30) return NVFP4_ERR_SHAPE;
+  const dim3 grid((uint32_t)(tiles_m * tiles_n)), block(kGemmThreads);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  auto go = [&](auto kernel) {
+    hipLaunchKernelGGL(kernel, grid, block, 0, s, static_cast<const uint8_t *>(codes_a),
+                       static_cast<const uint8_t *>(scales_a), alpha_a,
+                       static_cast<const uint8_t *>(codes_b), static_cast<const uint8_t *>(scales_b),
+                       alpha_b, out, M, N, K, (uint32_t)tiles_n);
+  };
+  const bool kfull = (K % GK) == 0, f32 = out_dtype == NVFP4_OUT_F32;
+  if (kfull) {
+    if (f32) go(k_gemm<true, true>);
+    else go(k_gemm<true, false>);
+  } else {
+    if (f32) go(k_gemm<false, true>);
+    else go(k_gemm<false, false>);
+  }
+  return hipGetLastError() == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+}

@@ -1,0 +1,177 @@
+"""GPU: the NVFP4 x NVFP4 matrix product against the CPU oracle, through the C ABI.
+
+The operands are expanded exactly and every product is exact; the matrix unit accumulates in
+fp32 in its own order.  Any fp32 summation of K exact products differs from the exact sum by
+at most (K - 1) 2^-24 sum|a b| (1 + O(K 2^-24)); the bound used is twice that, 2 K 2^-24, so
+that a matrix unit that truncates instead of rounding its partial sums still passes.  On top
+come the rounding of alpha_a * alpha_b and of the scaled result (2 * 2^-24 relative) and of
+the output (half an ulp: at most 2^-24 for fp32 and 2^-8 for BF16, relative to the result).  Where every partial sum
+is exactly representable the comparison is bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2512_02010_amd import binding as B
+from paper_2512_02010_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def _log(msg):
+    print(msg, flush=True)
+
+
+def _operand(name, rows, K, **kw):
+    """(codes, scales, alpha) of a synthetic tensor quantized by the oracle."""
+    bits = wl.bf16_bits(wl.make(name, rows, K))
+    alpha = ref.tensor_scale(bits)
+    codes, scales, _ = ref.quantize(bits, alpha, **kw)
+    return codes, scales, alpha
+
+
+def _dev(a):
+    return torch.from_numpy(a).cuda()
+
+
+def _alpha(a):
+    return torch.tensor([a], dtype=torch.float32, device="cuda")
+
+
+def _bf16_to_f64(t):
+    return t.float().double().cpu().numpy()
+
+
+def _tolerance(c_ref, c_abs, K, out_dtype):
+    out_eps = 2.0 ** -24 if out_dtype == B.OUT_F32 else 2.0 ** -8
+    return 2.0 * K * 2.0 ** -24 * c_abs + (out_eps + 2.0 ** -22) * np.abs(c_ref) + 1e-300
+
+
+def check_gemm(A, Bm, out_dtype, tag):
+    (ca, sa, aa), (cb, sb, ab) = A, Bm
+    M, N, K = ca.shape[0], cb.shape[0], ca.shape[1] * 2
+    _log(f"gemm case {tag} M={M} N={N} K={K} out_dtype={out_dtype}")
+    c_ref, c_abs = ref.gemm(ca, sa, aa, cb, sb, ab, want_abs=True)
+    got = B.nvfp4_46_gemm(_dev(ca), _dev(sa), _alpha(aa), _dev(cb), _dev(sb), _alpha(ab),
+                          out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    g = got.double().cpu().numpy() if out_dtype == B.OUT_F32 else _bf16_to_f64(got)
+    assert g.shape == (M, N)
+    err = np.abs(g - c_ref)
+    tol = _tolerance(c_ref, c_abs, K, out_dtype)
+    bad = np.argwhere(err > tol)
+    assert len(bad) == 0, (tag, len(bad), bad[:4].tolist(), g[tuple(bad[0])], c_ref[tuple(bad[0])])
+    # the bound is far from tight: typical errors sit near sqrt(K) 2^-24
+    _log(f"  max err / tol = {float((err / tol).max()):.3f}")
+    return g, c_ref
+
+
+SHAPES = [(32, 32, 32), (1, 1, 64), (100, 70, 160), (256, 256, 128), (257, 255, 384),
+          (300, 520, 1056), (512, 768, 2048)]
+
+
+@pytest.mark.parametrize("out_dtype", [B.OUT_F32, B.OUT_BF16])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_gemm_matches_oracle(shape, out_dtype):
+    M, N, K = shape
+    check_gemm(_operand("c3", M, K), _operand("c2", N, K), out_dtype, "c3xc2")
+
+
+@pytest.mark.parametrize("shape", [(64, 96, 256), (130, 260, 1120)])
+def test_gemm_wide_range_operands(shape):
+    # gradients with rows spread over many octaves (scale bytes down to subnormal E4M3)
+    # against a weight matrix with outlier columns; stochastic rounding on the gradient side
+    M, N, K = shape
+    A = _operand("c5", M, K, rounding=ref.SR, sr_seed=wl.C5_SR_SEED)
+    g, c_ref = check_gemm(A, _operand("c2", N, K), B.OUT_F32, "c5xc2")
+    if M >= 128:
+        assert (A[1] < 8).any()      # subnormal scale bytes do occur in this operand
+
+
+def test_gemm_is_exact_when_every_partial_sum_is_representable():
+    """Scale 1, codes on small multiples of 0.5: every product is a multiple of 0.25 below
+    36, every partial sum a multiple of 0.25 below 2^22, so fp32 accumulation is exact in any
+    order and the result must equal the oracle's bit for bit (alpha = 1)."""
+    rng = np.random.default_rng(46)
+    M, N, K = 160, 288, 1024
+    ca = rng.integers(0, 256, (M, K // 2), dtype=np.uint8)
+    cb = rng.integers(0, 256, (N, K // 2), dtype=np.uint8)
+    sa = rng.choice(np.array([0x30, 0x38, 0x40], np.uint8), (M, K // 16))    # 0.5, 1, 2
+    sb = rng.choice(np.array([0x38, 0x40, 0x48], np.uint8), (N, K // 16))    # 1, 2, 4
+    c_ref = ref.gemm(ca, sa, 1.0, cb, sb, 1.0)
+    assert np.array_equal(c_ref, c_ref.astype(np.float32).astype(np.float64))
+    got = B.nvfp4_46_gemm(_dev(ca), _dev(sa), _alpha(1.0), _dev(cb), _dev(sb), _alpha(1.0),
+                          out_dtype=B.OUT_F32)
+    assert np.array_equal(got.cpu().numpy().astype(np.float64), c_ref)
+    # and the BF16 output is the round-to-nearest-even of those exact values
+    got16 = B.nvfp4_46_gemm(_dev(ca), _dev(sa), _alpha(1.0), _dev(cb), _dev(sb), _alpha(1.0),
+                            out_dtype=B.OUT_BF16)
+    want16 = torch.from_numpy(c_ref.astype(np.float32)).to(torch.bfloat16)
+    assert torch.equal(got16.cpu(), want16)
+
+
+def test_gemm_every_scale_byte_and_code():
+    """Each of the 127 scale bytes 0x00..0x7E and all sixteen codes, one at a time against a
+    unit operand: C[m][n] = 16 * value(code) * value(scale) exactly."""
+    K = 32
+    ca = np.zeros((127 * 16, K // 2), np.uint8)
+    sa = np.zeros((127 * 16, K // 16), np.uint8)
+    for s in range(127):
+        for c in range(16):
+            ca[s * 16 + c, :8] = c | (c << 4)        # sixteen copies of code c in block 0
+            sa[s * 16 + c, 0] = s
+    cb = np.full((40, K // 2), 0x22, np.uint8)       # all 1.0
+    sb = np.full((40, K // 16), 0x38, np.uint8)
+    c_ref = ref.gemm(ca, sa, 1.0, cb, sb, 1.0)
+    got = B.nvfp4_46_gemm(_dev(ca), _dev(sa), _alpha(1.0), _dev(cb), _dev(sb), _alpha(1.0),
+                          out_dtype=B.OUT_F32).cpu().numpy().astype(np.float64)
+    assert np.array_equal(got, c_ref)
+    assert got[0x7E * 16 + 7, 0] == 16 * 6 * 448 and got[1 * 16 + 1, 3] == 16 * 0.5 * 2.0 ** -9
+
+
+def test_gemm_is_reproducible_and_runs_on_a_side_stream():
+    A, Bm = _operand("c1", 300, 512), _operand("c4", 200, 512)
+    args = [_dev(A[0]), _dev(A[1]), _alpha(A[2]), _dev(Bm[0]), _dev(Bm[1]), _alpha(Bm[2])]
+    first = B.nvfp4_46_gemm(*args, out_dtype=B.OUT_F32)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        again = [B.nvfp4_46_gemm(*args, out_dtype=B.OUT_F32, stream=s) for _ in range(3)]
+    s.synchronize()
+    for o in again:
+        assert torch.equal(o, first)
+
+
+def test_gemm_error_paths():
+    A = _operand("c1", 32, 64)
+    args = [_dev(A[0]), _dev(A[1]), _alpha(A[2]), _dev(A[0]), _dev(A[1]), _alpha(A[2])]
+    out = torch.full((32, 32), 7.0, dtype=torch.float32, device="cuda")
+    assert B.gemm_raw(*args, 32, 32, 48, B.OUT_F32, out) == 2          # K % 32 != 0
+    assert B.gemm_raw(*args, 0, 32, 64, B.OUT_F32, out) == 2
+    assert B.gemm_raw(*args, 32, 32, 64, 2, out) == 4
+    assert B.gemm_raw(args[0], None, *args[2:], 32, 32, 64, B.OUT_F32, out) == 1
+    assert B.gemm_raw(*args, 32, 32, 64, B.OUT_F32, out.data_ptr() + 4) == 3
+    torch.cuda.synchronize()
+    assert bool((out == 7.0).all())
+
+
+def test_gemm_full_size_sampled():
+    """8192 x 8192 x 8192 (activations c3-like rows against the c2 weight matrix) in the
+    configuration the benchmark times; the oracle recomputes 96 x 96 sampled outputs."""
+    K = 8192
+    A = _operand("c3", 8192, K)
+    Bm = _operand("c2", 8192, K)
+    got = B.nvfp4_46_gemm(_dev(A[0]), _dev(A[1]), _alpha(A[2]), _dev(Bm[0]), _dev(Bm[1]),
+                          _alpha(Bm[2]), out_dtype=B.OUT_BF16)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(8192)
+    rows = np.sort(np.concatenate([rng.choice(8192, 90, replace=False), [0, 255, 256, 4095, 8191, 31]]))
+    cols = np.sort(np.concatenate([rng.choice(8192, 90, replace=False), [0, 127, 128, 4096, 8191, 63]]))
+    c_ref, c_abs = ref.gemm(np.ascontiguousarray(A[0][rows]), np.ascontiguousarray(A[1][rows]),
+                            A[2], np.ascontiguousarray(Bm[0][cols]),
+                            np.ascontiguousarray(Bm[1][cols]), Bm[2], want_abs=True)
+    g = _bf16_to_f64(got[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
+    err = np.abs(g - c_ref)
+    tol = _tolerance(c_ref, c_abs, K, B.OUT_BF16)
+    assert (err <= tol).all(), float((err / tol).max())
+    _log(f"  full size: max err / tol = {float((err / tol).max()):.3f}")
