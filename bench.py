@@ -52,6 +52,8 @@ def parse():
     ap.add_argument("--cols", type=int, default=8192)
     ap.add_argument("--buffers", type=int, default=4, help="independent buffer sets rotated over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-gemm", action="store_true",
+                    help="skip the consumer-side leg (NVFP4 x NVFP4 matrix product, 8192^3)")
     ap.add_argument("--other-workloads", action="store_true",
                     help="also time the c3 (fake-quant), c4 (both orientations) and c5 "
                          "(Hadamard + stochastic rounding) steps at their full sizes and add "
@@ -184,6 +186,68 @@ def cpu_baseline(x_host):
             "kind": "oracle",
             "sample": f"{reps} full passes (tensor scale + quantize + dequantize) over the same "
                       f"{rows}x{cols} tensor in {dt:.1f} s, OpenMP over rows"}
+
+
+MFMA_F16_PEAK_TFLOPS = 2500.0
+
+
+def time_gemm(w_host, iters=20):
+    """The consumer of the quantizer's output (Fig. 3, FPROP): y = x W^T with x a c3-like
+    activation batch [8192][8192] and W the c2 weight matrix, both quantized rowwise (along
+    the contraction axis) by this library, multiplied by nvfp4_46_gemm into BF16.  For
+    context the same product of the dequantized FP16 operands by the vendor library
+    (torch.matmul): what the matrix units sustain here without any operand expansion."""
+    st = torch.cuda.current_stream()
+    he = hip_events()
+    n, k = w_host.shape
+    m = 8192
+    ops = []
+    for x in (wl.make("c3", m, k).cuda(), w_host.cuda()):
+        alpha = B.nvfp4_46_tensor_scale(x)
+        o = B.nvfp4_46_quantize(x, alpha, want_choice=False)
+        ops += [o["codes_row"], o["scales_row"], alpha]
+        del x
+    out = torch.empty((m, n), dtype=torch.bfloat16, device="cuda")
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        evs = [(he.new(), he.new()) for _ in range(iters)]
+        torch.cuda.synchronize()
+        for a, b in evs:
+            he.record(a, st)
+            fn()
+            he.record(b, st)
+        torch.cuda.synchronize()
+        ts = sorted(he.elapsed_ms(a, b) for a, b in evs)
+        for pair in evs:
+            he.free(pair)
+        return sum(ts) / len(ts), ts[len(ts) // 2]
+
+    def ours():
+        rc = B.gemm_raw(*ops, m, n, k, B.OUT_BF16, out, st)
+        if rc:
+            raise RuntimeError(f"nvfp4_46_gemm failed with status {rc}")
+
+    t_avg, t_med = timed(ours)
+    one = torch.ones(1, dtype=torch.float32, device="cuda")
+    a16 = B.nvfp4_46_dequantize(ops[0], ops[1], one, m, k).to(torch.float16)
+    b16 = B.nvfp4_46_dequantize(ops[3], ops[4], one, n, k).to(torch.float16)
+    lib_avg, lib_med = timed(lambda: torch.matmul(a16, b16.t(), out=out.view(torch.float16)))
+    flops = 2.0 * m * n * k
+    return {
+        "what": f"{m}x{n}x{k}: c3-like activations x c2 weights, both 4/6-quantized rowwise, "
+                "BF16 output",
+        "us_avg": t_avg * 1e3, "us_median": t_med * 1e3,
+        "roofline": {"bound": "mfma", "kernel": "k_gemm (v_mfma_f32_32x32x16_f16)",
+                     "achieved": flops / (t_avg * 1e-3) / 1e12, "peak": MFMA_F16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": flops / (t_avg * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS,
+                     "traffic": None},
+        "operand_bytes": (m + n) * (k // 2 + k // 16),
+        "library_fp16_gemm_on_expanded_operands": {
+            "us_median": lib_med * 1e3, "tflops": flops / (lib_avg * 1e-3) / 1e12,
+            "note": "torch.matmul on the same operands expanded to FP16 (4x the operand bytes)"},
+    }
 
 
 def time_other_workloads(iters=30):
@@ -448,8 +512,11 @@ def main():
                              "quantization on NVIDIA Blackwell (Sections 1, 3.2)",
         },
     }
+    del sets, graphs
+    torch.cuda.empty_cache()
+    if not args.no_gemm and (rows, cols) == (8192, 8192):
+        result["gemm"] = time_gemm(x_host)
     if args.other_workloads:
-        del sets, graphs
         torch.cuda.empty_cache()
         result["other_workloads"] = time_other_workloads()
     if not args.no_cpu_baseline:

@@ -49,15 +49,44 @@ NV_DEV h8 expand8(uint32_t word, uint32_t sv_bits) {
   return h8{p0.x, p0.y, p1.x, p1.y, p2.x, p2.y, p3.x, p3.y};
 }
 
+// LDS: two buffers (chunk c is multiplied out of one while chunk c + 1 is written into the
+// other), each holding both operands' codes and scales.
+struct GemmStage {
+  uint8_t codes[2][GT * kCodeRow];   // [A, B][row][80]
+  uint2 scales[2][GT];               // [A, B][row] -> the row's 8 scale bytes
+};
+constexpr size_t kGemmLdsBytes = 2 * sizeof(GemmStage);
+
+// What a lane holds of one half chunk (64 contraction steps): per operand tile 16 bytes of
+// codes and the two scale bytes that go with them.
+struct RawHalf {
+  uint4 a[4], b[4];
+  uint32_t sa[4], sb[4];
+};
+struct Frags {
+  h8 a[4], b[4];
+};
+
 // KFULL: K is a multiple of 128, so every chunk is whole and scale rows are 8-byte aligned.
+//
+// The main loop is a software pipeline over "steps" of 16 contraction indices (8 per chunk):
+// while the 16 matrix instructions of step s run, the lane expands the operands of step
+// s + 1 (64 vector instructions, issued in the matrix instructions' shadow).  Per chunk:
+//   step 1: read the second half's codes and scales from LDS;
+//   step 5: write the next chunk (fetched from global memory one chunk earlier) into the
+//           other LDS buffer and start fetching the chunk after it;
+//   step 6: barrier (every wave has finished reading this buffer and writing the other),
+//           then read the next chunk's first half from LDS;
+//   step 7: expand the next chunk's first step.
+// So the matrix unit is never left waiting for a barrier, an LDS read or an expansion.
 template <bool KFULL, bool OUTF32>
 __global__ __launch_bounds__(kGemmThreads) void k_gemm(
     const uint8_t *__restrict__ codes_a, const uint8_t *__restrict__ scales_a,
     const float *__restrict__ alpha_a, const uint8_t *__restrict__ codes_b,
     const uint8_t *__restrict__ scales_b, const float *__restrict__ alpha_b,
     void *__restrict__ out, int64_t M, int64_t N, int64_t K, uint32_t tiles_n) {
-  __shared__ __align__(16) uint8_t lds_codes[2][GT * kCodeRow];   // [A, B][row][80]
-  __shared__ __align__(8) uint2 lds_scales[2][GT];                // [A, B][row] -> 8 scale bytes
+  extern __shared__ __align__(16) uint8_t lds_raw[];
+  GemmStage *stage = reinterpret_cast<GemmStage *>(lds_raw);
 
   const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
   const uint32_t r = lane & 31u, g = lane >> 5;        // row within a 32-row tile, half of K
@@ -74,21 +103,26 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm(
   uint2 gsa, gsb;
   const uint32_t ld_row = t >> 2, ld_unit = t & 3u;
   auto clamp_row = [](int64_t row, int64_t n) { return row < n ? row : n - 1; };
+  const uint8_t *pa[4], *pb[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    pa[q] = codes_a + clamp_row(m0 + ld_row + 64 * q, M) * row_codes + ld_unit * 16;
+    pb[q] = codes_b + clamp_row(n0 + ld_row + 64 * q, N) * row_codes + ld_unit * 16;
+  }
+  const uint8_t *psa = scales_a + clamp_row(m0 + t, M) * row_scales;
+  const uint8_t *psb = scales_b + clamp_row(n0 + t, N) * row_scales;
   auto fetch = [&](int64_t k0) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const int64_t ra = clamp_row(m0 + ld_row + 64 * q, M), rb = clamp_row(n0 + ld_row + 64 * q, N);
-      const int64_t kb = k0 / 2 + ld_unit * 16;        // byte offset of the piece in its row
       ga[q] = gb[q] = make_uint4(0, 0, 0, 0);
       if (KFULL || k0 + ld_unit * 32 < K) {
-        ga[q] = *reinterpret_cast<const uint4 *>(codes_a + ra * row_codes + kb);
-        gb[q] = *reinterpret_cast<const uint4 *>(codes_b + rb * row_codes + kb);
+        ga[q] = *reinterpret_cast<const uint4 *>(pa[q] + k0 / 2);
+        gb[q] = *reinterpret_cast<const uint4 *>(pb[q] + k0 / 2);
       }
     }
-    const int64_t ra = clamp_row(m0 + t, M), rb = clamp_row(n0 + t, N);
     if (KFULL) {
-      gsa = *reinterpret_cast<const uint2 *>(scales_a + ra * row_scales + k0 / 16);
-      gsb = *reinterpret_cast<const uint2 *>(scales_b + rb * row_scales + k0 / 16);
+      gsa = *reinterpret_cast<const uint2 *>(psa + k0 / 16);
+      gsb = *reinterpret_cast<const uint2 *>(psb + k0 / 16);
     } else {
       // two scale bytes (32 contraction steps) at a time; K is a multiple of 32
       uint32_t wa[4], wb[4];
@@ -96,23 +130,52 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm(
       for (int q = 0; q < 4; ++q) {
         wa[q] = wb[q] = 0;
         if (k0 + 32 * q < K) {
-          wa[q] = *reinterpret_cast<const uint16_t *>(scales_a + ra * row_scales + k0 / 16 + 2 * q);
-          wb[q] = *reinterpret_cast<const uint16_t *>(scales_b + rb * row_scales + k0 / 16 + 2 * q);
+          wa[q] = *reinterpret_cast<const uint16_t *>(psa + k0 / 16 + 2 * q);
+          wb[q] = *reinterpret_cast<const uint16_t *>(psb + k0 / 16 + 2 * q);
         }
       }
       gsa = make_uint2(wa[0] | (wa[1] << 16), wa[2] | (wa[3] << 16));
       gsb = make_uint2(wb[0] | (wb[1] << 16), wb[2] | (wb[3] << 16));
     }
   };
-  auto stash = [&]() {
+  auto stash = [&](GemmStage &st) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const uint32_t off = (ld_row + 64 * q) * kCodeRow + ld_unit * 16;
-      *reinterpret_cast<uint4 *>(&lds_codes[0][off]) = ga[q];
-      *reinterpret_cast<uint4 *>(&lds_codes[1][off]) = gb[q];
+      *reinterpret_cast<uint4 *>(&st.codes[0][off]) = ga[q];
+      *reinterpret_cast<uint4 *>(&st.codes[1][off]) = gb[q];
     }
-    lds_scales[0][t] = gsa;
-    lds_scales[1][t] = gsb;
+    st.scales[0][t] = gsa;
+    st.scales[1][t] = gsb;
+  };
+
+  // ---- LDS -> registers: 16 bytes (32 codes, two scale blocks) per operand tile and half
+  const uint32_t a_row0 = wm * 128 + r, b_row0 = wn * 128 + r;
+  auto read_half = [&](const GemmStage &st, int half, RawHalf &h) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t rowa = a_row0 + 32 * i, rowb = b_row0 + 32 * i;
+      h.a[i] = *reinterpret_cast<const uint4 *>(&st.codes[0][rowa * kCodeRow + (2 * half + g) * 16]);
+      h.b[i] = *reinterpret_cast<const uint4 *>(&st.codes[1][rowb * kCodeRow + (2 * half + g) * 16]);
+      // the lane's two scale bytes of this half: blocks 4*half + 2*g and + 1
+      const uint32_t *wa = reinterpret_cast<const uint32_t *>(&st.scales[0][rowa]);
+      const uint32_t *wb = reinterpret_cast<const uint32_t *>(&st.scales[1][rowb]);
+      h.sa[i] = wa[half] >> (16 * g);
+      h.sb[i] = wb[half] >> (16 * g);
+    }
+  };
+  // operands of step s (0..3) of a half: word s of the 16 bytes, scale byte s / 2
+  auto expand = [&](const RawHalf &h, int s, Frags &f) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t wa = s == 0 ? h.a[i].x : s == 1 ? h.a[i].y : s == 2 ? h.a[i].z : h.a[i].w;
+      const uint32_t wb = s == 0 ? h.b[i].x : s == 1 ? h.b[i].y : s == 2 ? h.b[i].z : h.b[i].w;
+      // the scale byte moved to FP16's exponent/mantissa position
+      const uint32_t va = s < 2 ? (h.sa[i] & 0xffu) << 7 : (h.sa[i] >> 1) & 0x7f80u;
+      const uint32_t vb = s < 2 ? (h.sb[i] & 0xffu) << 7 : (h.sb[i] >> 1) & 0x7f80u;
+      f.a[i] = expand8(wa, va);
+      f.b[i] = expand8(wb, vb);
+    }
   };
 
   f32x16 acc[4][4];
@@ -123,58 +186,59 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm(
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  // ---- one chunk out of LDS: two halves of 64 contraction steps; in each, a lane takes
-  // 16 bytes (32 codes, two scale blocks) per operand tile and feeds four matrix steps
-  const uint32_t a_row0 = wm * 128 + r, b_row0 = wn * 128 + r;
-  auto multiply = [&]() {
+  auto mfma16 = [&](const Frags &f) {
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      uint4 ra[4], rb[4];
-      uint32_t sa[4], sb[4];
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const uint32_t rowa = a_row0 + 32 * i, rowb = b_row0 + 32 * i;
-        ra[i] = *reinterpret_cast<const uint4 *>(&lds_codes[0][rowa * kCodeRow + (2 * half + g) * 16]);
-        rb[i] = *reinterpret_cast<const uint4 *>(&lds_codes[1][rowb * kCodeRow + (2 * half + g) * 16]);
-        const uint2 wa = lds_scales[0][rowa], wb = lds_scales[1][rowb];
-        // the lane's two scale bytes of this half: blocks 4*half + 2*g and + 1
-        sa[i] = ((half ? wa.y : wa.x) >> (16 * g)) & 0xffffu;
-        sb[i] = ((half ? wb.y : wb.x) >> (16 * g)) & 0xffffu;
-      }
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+  };
+  // ask the scheduler to issue four vector instructions behind every matrix instruction
+  auto interleave = [&]() {
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        h8 fa[4], fb[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const uint32_t wa = s == 0 ? ra[i].x : s == 1 ? ra[i].y : s == 2 ? ra[i].z : ra[i].w;
-          const uint32_t wb = s == 0 ? rb[i].x : s == 1 ? rb[i].y : s == 2 ? rb[i].z : rb[i].w;
-          // scale byte s/2 of the pair, moved to FP16's exponent/mantissa position
-          const uint32_t va = s < 2 ? (sa[i] & 0xffu) << 7 : (sa[i] >> 1) & 0x7f80u;
-          const uint32_t vb = s < 2 ? (sb[i] & 0xffu) << 7 : (sb[i] >> 1) & 0x7f80u;
-          fa[i] = expand8(wa, va);
-          fb[i] = expand8(wb, vb);
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-      }
+    for (int q = 0; q < 16; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
     }
   };
 
   const int64_t nchunks = (K + GK - 1) / GK;
+  RawHalf h0, h1;
+  Frags f0, f1;
   fetch(0);
-  stash();
+  stash(stage[0]);
   __syncthreads();
-  for (int64_t c = 0; c < nchunks; ++c) {
-    const bool more = c + 1 < nchunks;
-    if (more) fetch((c + 1) * GK);
-    multiply();
-    __syncthreads();          // everyone has read chunk c
-    if (more) stash();
-    __syncthreads();          // chunk c + 1 is in place
-  }
+  fetch(nchunks > 1 ? GK : 0);
+  read_half(stage[0], 0, h0);
+  expand(h0, 0, f0);
+
+  // one chunk; `last` = no chunk follows (nothing to write, read or expand ahead)
+  auto chunk = [&](int64_t c, bool last) {
+    GemmStage &cur = stage[c & 1], &nxt = stage[(c + 1) & 1];
+#pragma unroll
+    for (int st = 0; st < 8; ++st) {
+      Frags &fc = (st & 1) ? f1 : f0, &fn = (st & 1) ? f0 : f1;
+      if (st == 1) read_half(cur, 1, h1);
+      if (st == 5 && !last) {
+        stash(nxt);
+        const int64_t c2 = c + 2 < nchunks ? c + 2 : nchunks - 1;   // past the end: a harmless re-read
+        fetch(c2 * GK);
+      }
+      if (st == 6) {
+        // keep each step's instructions on their own side of the barrier
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        if (!last) read_half(nxt, 0, h0);
+      }
+      if (st < 7) expand(st < 3 ? h0 : h1, (st + 1) & 3, fn);
+      else if (!last) expand(h0, 0, fn);
+      mfma16(fc);
+      interleave();
+    }
+  };
+  for (int64_t c = 0; c + 1 < nchunks; ++c) chunk(c, false);
+  chunk(nchunks - 1, true);
 
   // ---- epilogue: accumulator element v of tile (i, j) is C[32 i + 8 (v / 4) + 4 g + v % 4]
   // [32 j + r] within the wave's quarter
@@ -223,7 +287,12 @@ extern "C" int nvfp4_46_gemm(const void *codes_a, const void *scales_a, const fl
   const dim3 grid((uint32_t)(tiles_m * tiles_n)), block(kGemmThreads);
   hipStream_t s = static_cast<hipStream_t>(stream);
   auto go = [&](auto kernel) {
-    hipLaunchKernelGGL(kernel, grid, block, 0, s, static_cast<const uint8_t *>(codes_a),
+    // more LDS than the 64 KiB a kernel gets without asking
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)kGemmLdsBytes) != hipSuccess)
+      return;
+    hipLaunchKernelGGL(kernel, grid, block, kGemmLdsBytes, s, static_cast<const uint8_t *>(codes_a),
                        static_cast<const uint8_t *>(scales_a), alpha_a,
                        static_cast<const uint8_t *>(codes_b), static_cast<const uint8_t *>(scales_b),
                        alpha_b, out, M, N, K, (uint32_t)tiles_n);
