@@ -37,10 +37,9 @@ constexpr int kCodeRow = GK / 2 + 16;    // bytes per operand row in LDS: 64 of 
                                          // different bank groups (80 = 5 * 16, 5 coprime to 16)
 
 // Eight codes (one 32-bit word) times one scale -> eight FP16 values, exactly.
-// `sv` is the scale as FP16 bits (byte << 7), i.e. value(scale) * 2^-8; the conversion
-// multiplies by 2^8.
-NV_DEV h8 expand8(uint32_t word, uint32_t sv_bits) {
-  const _Float16 sv = __builtin_bit_cast(_Float16, (unsigned short)sv_bits);
+// `sv` is the FP16 with the bit pattern (scale byte << 7), i.e. value(scale) * 2^-8 (also for
+// the subnormal scale bytes); the conversion multiplies by 2^8.
+NV_DEV h8 expand8(uint32_t word, _Float16 sv) {
   const h2 s = {sv, sv};
   const h2 p0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(word, 256.0f, 0) * s;
   const h2 p1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(word, 256.0f, 1) * s;
@@ -53,7 +52,8 @@ NV_DEV h8 expand8(uint32_t word, uint32_t sv_bits) {
 // other), each holding both operands' codes and scales.
 struct GemmStage {
   uint8_t codes[2][GT * kCodeRow];   // [A, B][row][80]
-  uint2 scales[2][GT];               // [A, B][row] -> the row's 8 scale bytes
+  uint4 scales[2][GT];               // [A, B][row] -> the row's 8 scales as FP16 bit patterns
+                                     // (byte << 7 = value * 2^-8), ready to multiply with
 };
 constexpr size_t kGemmLdsBytes = 2 * sizeof(GemmStage);
 
@@ -145,8 +145,10 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm(
       *reinterpret_cast<uint4 *>(&st.codes[0][off]) = ga[q];
       *reinterpret_cast<uint4 *>(&st.codes[1][off]) = gb[q];
     }
-    st.scales[0][t] = gsa;
-    st.scales[1][t] = gsb;
+    // scale bytes -> FP16 bit patterns, two per word
+    auto widen = [](uint32_t two_bytes) { return ((two_bytes & 0xffu) << 7) | ((two_bytes & 0xff00u) << 15); };
+    st.scales[0][t] = make_uint4(widen(gsa.x), widen(gsa.x >> 16), widen(gsa.y), widen(gsa.y >> 16));
+    st.scales[1][t] = make_uint4(widen(gsb.x), widen(gsb.x >> 16), widen(gsb.y), widen(gsb.y >> 16));
   };
 
   // ---- LDS -> registers: 16 bytes (32 codes, two scale blocks) per operand tile and half
@@ -157,11 +159,11 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm(
       const uint32_t rowa = a_row0 + 32 * i, rowb = b_row0 + 32 * i;
       h.a[i] = *reinterpret_cast<const uint4 *>(&st.codes[0][rowa * kCodeRow + (2 * half + g) * 16]);
       h.b[i] = *reinterpret_cast<const uint4 *>(&st.codes[1][rowb * kCodeRow + (2 * half + g) * 16]);
-      // the lane's two scale bytes of this half: blocks 4*half + 2*g and + 1
+      // the lane's two scales of this half (blocks 4*half + 2*g and + 1), one word
       const uint32_t *wa = reinterpret_cast<const uint32_t *>(&st.scales[0][rowa]);
       const uint32_t *wb = reinterpret_cast<const uint32_t *>(&st.scales[1][rowb]);
-      h.sa[i] = wa[half] >> (16 * g);
-      h.sb[i] = wb[half] >> (16 * g);
+      h.sa[i] = wa[2 * half + g];
+      h.sb[i] = wb[2 * half + g];
     }
   };
   // operands of step s (0..3) of a half: word s of the 16 bytes, scale byte s / 2
@@ -170,11 +172,10 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm(
     for (int i = 0; i < 4; ++i) {
       const uint32_t wa = s == 0 ? h.a[i].x : s == 1 ? h.a[i].y : s == 2 ? h.a[i].z : h.a[i].w;
       const uint32_t wb = s == 0 ? h.b[i].x : s == 1 ? h.b[i].y : s == 2 ? h.b[i].z : h.b[i].w;
-      // the scale byte moved to FP16's exponent/mantissa position
-      const uint32_t va = s < 2 ? (h.sa[i] & 0xffu) << 7 : (h.sa[i] >> 1) & 0x7f80u;
-      const uint32_t vb = s < 2 ? (h.sb[i] & 0xffu) << 7 : (h.sb[i] >> 1) & 0x7f80u;
-      f.a[i] = expand8(wa, va);
-      f.b[i] = expand8(wb, vb);
+      // the block's scale: low or high half of the pair read from LDS
+      const h2 pa2 = __builtin_bit_cast(h2, h.sa[i]), pb2 = __builtin_bit_cast(h2, h.sb[i]);
+      f.a[i] = expand8(wa, s < 2 ? pa2.x : pa2.y);
+      f.b[i] = expand8(wb, s < 2 ? pb2.x : pb2.y);
     }
   };
 
@@ -193,11 +194,15 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm(
       for (int j = 0; j < 4; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
   };
-  // ask the scheduler to issue four vector instructions behind every matrix instruction
-  auto interleave = [&]() {
+  // ask the scheduler to issue four vector instructions behind every matrix instruction, and
+  // the step's LDS / global accesses one at a time behind the first matrix instructions
+  auto interleave = [&](int lds_reads, int lds_writes, int vmem_reads) {
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (q < lds_reads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      if (q < lds_writes) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+      if (q < vmem_reads) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
     }
   };
@@ -234,7 +239,8 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm(
       if (st < 7) expand(st < 3 ? h0 : h1, (st + 1) & 3, fn);
       else if (!last) expand(h0, 0, fn);
       mfma16(fc);
-      interleave();
+      interleave(st == 1 || (st == 6 && !last) ? 16 : 0, st == 5 && !last ? 10 : 0,
+                 st == 5 && !last ? 10 : 0);
     }
   };
   for (int64_t c = 0; c + 1 < nchunks; ++c) chunk(c, false);
