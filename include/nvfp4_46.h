@@ -59,8 +59,10 @@ typedef enum {
 } nvfp4_status;
 
 /* layout bits; NVFP4_ROWWISE | NVFP4_COLWISE = both outputs from one read of x.
- * NVFP4_BLOCK2D is only a value of nvfp4_46_dequantize's `layout` argument: data written
- * with nvfp4_46_params.block2d = 1 (codes [rows][cols/2], scales [rows/16][cols/16]). */
+ * NVFP4_BLOCK2D only occurs in nvfp4_46_dequantize's `layout` argument, for data written
+ * with nvfp4_46_params.block2d = 1: NVFP4_BLOCK2D alone = the rowwise packing (codes
+ * [rows][cols/2], scales [rows/16][cols/16]), NVFP4_BLOCK2D | NVFP4_COLWISE = the packing for
+ * the transposed matrix (codes [cols][rows/2], scales [cols/16][rows/16]). */
 enum { NVFP4_ROWWISE = 1, NVFP4_COLWISE = 2, NVFP4_BLOCK2D = 4 };
 /* rounding of scaled values onto the E2M1 grid */
 enum { NVFP4_RTN = 0, NVFP4_SR = 1, NVFP4_SR_AFTER_RTN_SELECT = 2 };
@@ -101,9 +103,13 @@ typedef struct {
                           same scales.  The tile's maximum sets the two candidate scales, each
                           row of the tile is quantized with them, and the tile's error is the
                           sum (largest, for _ABSMAX) of its sixteen row errors in the same
-                          fixed order as within a row.  Needs layout = NVFP4_ROWWISE, rht = 0,
-                          rows % 16 == cols % 16 == 0; codes_row is [rows][cols/2] as usual,
-                          scales_row and choice_row are [rows/16][cols/16].                   */
+                          fixed order as within a row.  Needs rht = 0 and rows % 16 == cols % 16
+                          == 0; codes_row is [rows][cols/2] as usual, scales_row and choice_row
+                          are [rows/16][cols/16].  With NVFP4_COLWISE in `layout` the same tiles
+                          are also (or only) written for the transposed matrix: codes_col
+                          [cols][rows/2] holds the very same codes packed along the rows of x
+                          (even row in the low nibble), scales_col and choice_col are
+                          [cols/16][rows/16] -- the tiles are decided once, in x's orientation. */
   uint32_t x_dtype;    /* NVFP4_X_BF16, or NVFP4_X_F32: x holds fp32 values, which enter the
                           quantizer as they are -- the weights of Fig. 3, which are stored in
                           FP32 and quantized on every use.  Everything after the load is the
@@ -138,11 +144,11 @@ int nvfp4_46_quantize(const void *x, const nvfp4_46_params *p, const float *alph
                       void *choice_row, void *choice_col, void *stream);
 
 /* Table 3 lines 5 / 11 on stored data: out = bf16_rne(value(code) * (value(scale) * alpha)).
- *   codes, scales  in   in the layout named by `layout` (NVFP4_ROWWISE, NVFP4_COLWISE or
- *                       NVFP4_BLOCK2D)
+ *   codes, scales  in   in the layout named by `layout` (NVFP4_ROWWISE, NVFP4_COLWISE,
+ *                       NVFP4_BLOCK2D or NVFP4_BLOCK2D | NVFP4_COLWISE)
  *   out            out  [rows][cols] BF16, always row-major in the tensor's own orientation
  * Errors: NULL pointer -> ERR_NULL; bad dims -> ERR_SHAPE; misaligned -> ERR_ALIGN;
- * layout not one of the three values -> ERR_PARAM.                                    */
+ * layout not one of the four values -> ERR_PARAM.                                      */
 int nvfp4_46_dequantize(const void *codes, const void *scales, const float *alpha, int64_t rows,
                         int64_t cols, uint32_t layout, void *out_bf16, void *stream);
 

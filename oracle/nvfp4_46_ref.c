@@ -554,6 +554,46 @@ int nvfp4_46_ref_quantize_2d_f32(const float *x, int64_t rows, int64_t cols, int
                           choice, deq);
 }
 
+/* The same 2D-block quantization laid out for the transposed matrix (READING: "a matrix and
+ * its transpose are quantized consistently" is taken literally -- the tiles are decided once,
+ * in the matrix's own orientation, and W^T gets the very same codes and scales, only packed
+ * along its own rows): codes_col [cols][rows/2] with the element at the even ROW in the low
+ * nibble, scales_col and choice_col [cols/16][rows/16].  Pure re-indexing. */
+int nvfp4_46_ref_repack_2d_columnwise(const uint8_t *codes, const uint8_t *scales,
+                                      const uint8_t *choice, int64_t rows, int64_t cols,
+                                      uint8_t *codes_col, uint8_t *scales_col,
+                                      uint8_t *choice_col) {
+  int64_t TR = rows / BLOCK, TCB = cols / BLOCK;
+  for (int64_t c = 0; c < cols; ++c)
+    for (int64_t r = 0; r < rows; r += 2) {
+      uint8_t b0 = codes[r * (cols / 2) + c / 2], b1 = codes[(r + 1) * (cols / 2) + c / 2];
+      uint8_t q0 = (c & 1) ? (b0 >> 4) : (b0 & 15), q1 = (c & 1) ? (b1 >> 4) : (b1 & 15);
+      codes_col[c * (rows / 2) + r / 2] = (uint8_t)(q0 | (q1 << 4));
+    }
+  for (int64_t tr = 0; tr < TR; ++tr)
+    for (int64_t tc = 0; tc < TCB; ++tc) {
+      scales_col[tc * TR + tr] = scales[tr * TCB + tc];
+      if (choice && choice_col) choice_col[tc * TR + tr] = choice[tr * TCB + tc];
+    }
+  return 0;
+}
+
+/* Dequantize columnwise-packed 2D-block data into the matrix's own row-major order. */
+int nvfp4_46_ref_dequantize_2d_columnwise(const uint8_t *codes_col, const uint8_t *scales_col,
+                                          float alpha, int64_t rows, int64_t cols,
+                                          uint16_t *out) {
+  int64_t TR = rows / BLOCK;
+#pragma omp parallel for schedule(static)
+  for (int64_t r = 0; r < rows; ++r)
+    for (int64_t c = 0; c < cols; ++c) {
+      float dec = ref_e4m3_decode(scales_col[(c / BLOCK) * TR + r / BLOCK]) * alpha;
+      uint8_t byte = codes_col[c * (rows / 2) + r / 2];
+      uint8_t code = (r & 1) ? (byte >> 4) : (byte & 15);
+      out[r * cols + c] = ref_f32_to_bf16(ref_e2m1_decode(code) * dec);
+    }
+  return 0;
+}
+
 /* Dequantize 2D-block data: scales [rows/16][cols/16], codes as above. */
 int nvfp4_46_ref_dequantize_2d(const uint8_t *codes, const uint8_t *scales, float alpha,
                                int64_t rows, int64_t cols, uint16_t *out) {

@@ -91,6 +91,10 @@ def lib() -> C.CDLL:
         L.nvfp4_46_ref_quantize_2d.restype = i32
         L.nvfp4_46_ref_quantize_2d.argtypes = [u16p, i64, i64, i32, i32, u64, f32, u8p, u8p, u8p,
                                                u16p]
+        L.nvfp4_46_ref_repack_2d_columnwise.restype = i32
+        L.nvfp4_46_ref_repack_2d_columnwise.argtypes = [u8p, u8p, u8p, i64, i64, u8p, u8p, u8p]
+        L.nvfp4_46_ref_dequantize_2d_columnwise.restype = i32
+        L.nvfp4_46_ref_dequantize_2d_columnwise.argtypes = [u8p, u8p, f32, i64, i64, u16p]
         L.nvfp4_46_ref_dequantize_2d.restype = i32
         L.nvfp4_46_ref_dequantize_2d.argtypes = [u8p, u8p, f32, i64, i64, u16p]
         f64p = C.POINTER(C.c_double)
@@ -313,6 +317,33 @@ def quantize_2d(x_bits: np.ndarray, alpha: float, rounding: int = RTN, select: i
             _p(scales, C.c_uint8), _p(choice, C.c_uint8), _p(deq, C.c_uint16))
     assert rc == 0
     return codes, scales, choice, deq
+
+
+def repack_2d_columnwise(codes: np.ndarray, scales: np.ndarray, choice: np.ndarray):
+    """Row-packed 2D-block outputs -> the transposed matrix's packing:
+    (codes_col [cols][rows/2], scales_col, choice_col [cols/16][rows/16])."""
+    rows, cols = codes.shape[0], codes.shape[1] * 2
+    assert scales.shape == (rows // 16, cols // 16) and choice.shape == scales.shape
+    cc = np.zeros((cols, rows // 2), np.uint8)
+    sc = np.zeros((cols // 16, rows // 16), np.uint8)
+    fc = np.zeros((cols // 16, rows // 16), np.uint8)
+    rc = lib().nvfp4_46_ref_repack_2d_columnwise(_p(codes, C.c_uint8), _p(scales, C.c_uint8),
+                                                 _p(choice, C.c_uint8), rows, cols,
+                                                 _p(cc, C.c_uint8), _p(sc, C.c_uint8),
+                                                 _p(fc, C.c_uint8))
+    assert rc == 0
+    return cc, sc, fc
+
+
+def dequantize_2d_columnwise(codes_col: np.ndarray, scales_col: np.ndarray, alpha: float,
+                             rows: int, cols: int) -> np.ndarray:
+    assert codes_col.shape == (cols, rows // 2) and scales_col.shape == (cols // 16, rows // 16)
+    out = np.zeros((rows, cols), np.uint16)
+    rc = lib().nvfp4_46_ref_dequantize_2d_columnwise(_p(codes_col, C.c_uint8),
+                                                     _p(scales_col, C.c_uint8), alpha, rows, cols,
+                                                     _p(out, C.c_uint16))
+    assert rc == 0
+    return out
 
 
 def dequantize_2d(codes: np.ndarray, scales: np.ndarray, alpha: float, rows: int,

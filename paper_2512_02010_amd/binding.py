@@ -193,10 +193,11 @@ def alloc_outputs(rows: int, cols: int, layout: int, device, want_choice: bool =
         if want_choice:
             o["choice_row"] = torch.empty((srows, cols // 16), **u8)
     if layout & COLWISE:
+        scols = cols // 16 if block2d else cols
         o["codes_col"] = torch.empty((cols, rows // 2), **u8)
-        o["scales_col"] = torch.empty((cols, rows // 16), **u8)
+        o["scales_col"] = torch.empty((scols, rows // 16), **u8)
         if want_choice:
-            o["choice_col"] = torch.empty((cols, rows // 16), **u8)
+            o["choice_col"] = torch.empty((scols, rows // 16), **u8)
     return o
 
 

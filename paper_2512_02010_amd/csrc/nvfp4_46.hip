@@ -572,7 +572,9 @@ __global__ __launch_bounds__(kThreads) void k_tile(
   }
 }
 
-// Columnwise codes/scales -> row-major BF16, through an LDS tile.
+// Columnwise codes/scales -> row-major BF16, through an LDS tile.  TILE2D: the scales are
+// per 16x16 tile of the matrix, stored [cols/16][rows/16].
+template <bool TILE2D>
 __global__ __launch_bounds__(kThreads) void k_dequant_col(const uint8_t *__restrict__ codes,
                                                           const uint8_t *__restrict__ scales,
                                                           const float *__restrict__ alpha_p,
@@ -592,7 +594,8 @@ __global__ __launch_bounds__(kThreads) void k_dequant_col(const uint8_t *__restr
     const int64_t gc = c0 + cl, gr = r0 + rb * 16;
     if (gc < cols && gr < rows) {
       const uint2 c = *reinterpret_cast<const uint2 *>(codes + gc * col_codes + (gr >> 1));
-      const float dec = e4m3_decode_sw(scales[gc * col_scales + (gr >> 4)]) * alpha;
+      const float dec =
+          e4m3_decode_sw(scales[(TILE2D ? (gc >> 4) : gc) * col_scales + (gr >> 4)]) * alpha;
       float D[8];
       dequant8(c.x, dec, D);
 #pragma unroll
@@ -625,11 +628,39 @@ __global__ __launch_bounds__(kThreads) void k_dequant_col(const uint8_t *__restr
 // each half, then the two halves), which is the order of the shuffles 4, 2, 1, 8.
 // Lane -> (tile, row): lanes 0-15 are the rows of one tile, the next sixteen lanes the
 // tile to its right, so four lanes 16 apart read 128 contiguous bytes of one row.
+// Sixteen adjacent lanes each hold one row of a 16x16 matrix of 4-bit codes (lo = columns
+// 0-7, hi = columns 8-15, column j in bits 4j..4j+3); on return lane j of the sixteen holds
+// column j packed the same way (row i in bits 4i..4i+3).  The usual recursive transpose:
+// swap the off-diagonal 8x8 blocks between lanes 8 apart, then 4x4 blocks between lanes 4
+// apart inside every 8x8 block, and so on down to single codes.
+NV_DEV void transpose_codes16(uint32_t &lo, uint32_t &hi) {
+  const uint32_t lane = threadIdx.x;
+  {
+    const bool upper = lane & 8u;
+    const uint32_t got = __shfl_xor(upper ? lo : hi, 8, 64);
+    if (upper) lo = got; else hi = got;
+  }
+  auto stage = [&](uint32_t &w, uint32_t bit, uint32_t keep_low, int shift) {
+    // keep_low masks the groups a lane with (lane & bit) == 0 keeps in place
+    const bool upper = lane & bit;
+    const uint32_t give = upper ? (w & keep_low) : ((w >> shift) & keep_low);
+    const uint32_t got = __shfl_xor(give, (int)bit, 64);
+    w = upper ? ((w & ~keep_low) | got) : ((w & keep_low) | (got << shift));
+  };
+  stage(lo, 4u, 0x0000ffffu, 16);
+  stage(hi, 4u, 0x0000ffffu, 16);
+  stage(lo, 2u, 0x00ff00ffu, 8);
+  stage(hi, 2u, 0x00ff00ffu, 8);
+  stage(lo, 1u, 0x0f0f0f0fu, 4);
+  stage(hi, 1u, 0x0f0f0f0fu, 4);
+}
+
 template <bool XF32, int ROUNDING, int SELECT, int OUT>
 __global__ __launch_bounds__(kThreads) void k_block2d(
     const void *__restrict__ x_any, const float *__restrict__ alpha_p, uint8_t *__restrict__ codes,
-    uint8_t *__restrict__ scales, uint8_t *__restrict__ choice, uint16_t *__restrict__ out_bf16,
-    int64_t rows, int64_t cols, uint64_t sr_seed) {
+    uint8_t *__restrict__ scales, uint8_t *__restrict__ choice, uint8_t *__restrict__ codes_col,
+    uint8_t *__restrict__ scales_col, uint8_t *__restrict__ choice_col,
+    uint16_t *__restrict__ out_bf16, int64_t rows, int64_t cols, uint64_t sr_seed) {
   __shared__ ScaleTable tab;
   const ScaleConsts sc = build_scale_table(tab, *alpha_p);
   const uint32_t tid = threadIdx.x, r_in_tile = tid & 15u, grp = tid >> 4;
@@ -694,10 +725,24 @@ __global__ __launch_bounds__(kThreads) void k_block2d(
     if (ROUNDING == kSRAfterRtnSelect)
       (void)candidate<kSR, kErrNone>(v, u, res.dec, four ? enc4 : enc6, res.lo, res.hi);
     if (OUT == kOutCodes) {
-      *reinterpret_cast<uint2 *>(codes + row * (cols / 2) + tc * 8) = make_uint2(res.lo, res.hi);
-      if (r_in_tile == 0) {
-        scales[T] = (uint8_t)res.scale;
-        if (choice) choice[T] = (uint8_t)res.four;
+      if (codes) {
+        *reinterpret_cast<uint2 *>(codes + row * (cols / 2) + tc * 8) = make_uint2(res.lo, res.hi);
+        if (r_in_tile == 0) {
+          scales[T] = (uint8_t)res.scale;
+          if (choice) choice[T] = (uint8_t)res.four;
+        }
+      }
+      if (codes_col) {
+        // the same tile for the transposed matrix: column (tc*16 + lane) of x is its row
+        uint32_t lo = res.lo, hi = res.hi;
+        transpose_codes16(lo, hi);
+        const int64_t col = tc * 16 + r_in_tile;
+        *reinterpret_cast<uint2 *>(codes_col + col * (rows / 2) + tr * 8) = make_uint2(lo, hi);
+        if (r_in_tile == 0) {
+          const int64_t Tt = tc * (rows / 16) + tr;
+          scales_col[Tt] = (uint8_t)res.scale;
+          if (choice_col) choice_col[Tt] = (uint8_t)res.four;
+        }
       }
     } else {
       float D0[8], D1[8];
@@ -942,7 +987,7 @@ struct Block2dArgs {
   bool xf32;
   const void *x;
   const float *alpha;
-  uint8_t *codes, *scales, *choice;
+  uint8_t *codes, *scales, *choice, *codes_col, *scales_col, *choice_col;
   uint16_t *out;
   int64_t rows, cols;
   uint64_t sr_seed;
@@ -955,7 +1000,8 @@ static void launch_block2d(const Block2dArgs &a, int out) {
   const int grid = grid_for(tiles * 16, 16);
   auto go = [&](auto kernel) {
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), 0, a.stream, a.x, a.alpha, a.codes,
-                       a.scales, a.choice, a.out, a.rows, a.cols, a.sr_seed);
+                       a.scales, a.choice, a.codes_col, a.scales_col, a.choice_col, a.out, a.rows,
+                       a.cols, a.sr_seed);
   };
   if (out == kOutCodes) {
     if (a.xf32) go(k_block2d<true, ROUNDING, SELECT, kOutCodes>);
@@ -1001,7 +1047,7 @@ static int check_params(const void *x, const nvfp4_46_params *p, bool one_layout
   if (p->rht && p->layout == 3u) return NVFP4_ERR_UNSUPPORTED;
   if (p->block2d) {
     if ((p->rows % 16) != 0 || (p->cols % 16) != 0) return NVFP4_ERR_SHAPE;
-    if (p->layout != NVFP4_ROWWISE || p->rht) return NVFP4_ERR_UNSUPPORTED;
+    if (p->rht) return NVFP4_ERR_UNSUPPORTED;
   }
   return NVFP4_OK;
 }
@@ -1062,8 +1108,9 @@ int nvfp4_46_quantize(const void *x, const nvfp4_46_params *p, const float *alph
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (p->block2d) {
     Block2dArgs a{xf32, x, alpha, static_cast<uint8_t *>(codes_row),
-                  static_cast<uint8_t *>(scales_row), static_cast<uint8_t *>(choice_row), nullptr,
-                  p->rows, p->cols, p->sr_seed, s};
+                  static_cast<uint8_t *>(scales_row), static_cast<uint8_t *>(choice_row),
+                  static_cast<uint8_t *>(codes_col), static_cast<uint8_t *>(scales_col),
+                  static_cast<uint8_t *>(choice_col), nullptr, p->rows, p->cols, p->sr_seed, s};
     dispatch_block2d(a, p->rounding, p->select, kOutCodes);
     return launch_status();
   }
@@ -1087,9 +1134,10 @@ int nvfp4_46_dequantize(const void *codes, const void *scales, const float *alph
                         int64_t cols, uint32_t layout, void *out_bf16, void *stream) {
   if (!codes || !scales || !alpha || !out_bf16) return NVFP4_ERR_NULL;
   if (rows <= 0 || cols <= 0) return NVFP4_ERR_SHAPE;
-  if (layout != NVFP4_ROWWISE && layout != NVFP4_COLWISE && layout != NVFP4_BLOCK2D)
+  if (layout != NVFP4_ROWWISE && layout != NVFP4_COLWISE && layout != NVFP4_BLOCK2D &&
+      layout != (NVFP4_BLOCK2D | NVFP4_COLWISE))
     return NVFP4_ERR_PARAM;
-  if (layout == NVFP4_BLOCK2D && ((rows % 16) != 0 || (cols % 16) != 0)) return NVFP4_ERR_SHAPE;
+  if ((layout & NVFP4_BLOCK2D) && ((rows % 16) != 0 || (cols % 16) != 0)) return NVFP4_ERR_SHAPE;
   if (layout == NVFP4_ROWWISE && (cols % 16) != 0) return NVFP4_ERR_SHAPE;
   if (layout == NVFP4_COLWISE && ((rows % 16) != 0 || (cols % 8) != 0)) return NVFP4_ERR_SHAPE;
   if (rows > (int64_t)1 << 31 || cols > (int64_t)1 << 31 || rows * cols > (int64_t)1 << 40)
@@ -1106,8 +1154,12 @@ int nvfp4_46_dequantize(const void *codes, const void *scales, const float *alph
     hipLaunchKernelGGL(k_dequant_flat, dim3(grid_for(n8, 16)), dim3(kThreads), 0, s,
                        static_cast<const uint32_t *>(codes), static_cast<const uint8_t *>(scales),
                        alpha, static_cast<uint4 *>(out_bf16), n8);
+  } else if (layout == NVFP4_COLWISE) {
+    hipLaunchKernelGGL(k_dequant_col<false>, dim3(tile_grid(rows, cols)), dim3(kThreads), 0, s,
+                       static_cast<const uint8_t *>(codes), static_cast<const uint8_t *>(scales),
+                       alpha, static_cast<uint16_t *>(out_bf16), rows, cols);
   } else {
-    hipLaunchKernelGGL(k_dequant_col, dim3(tile_grid(rows, cols)), dim3(kThreads), 0, s,
+    hipLaunchKernelGGL(k_dequant_col<true>, dim3(tile_grid(rows, cols)), dim3(kThreads), 0, s,
                        static_cast<const uint8_t *>(codes), static_cast<const uint8_t *>(scales),
                        alpha, static_cast<uint16_t *>(out_bf16), rows, cols);
   }
@@ -1123,7 +1175,7 @@ int nvfp4_46_fake_quant(const void *x, const nvfp4_46_params *p, const float *al
   if (!aligned16(out_bf16)) return NVFP4_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (p->block2d) {
-    Block2dArgs a{xf32, x, alpha, nullptr, nullptr, nullptr,
+    Block2dArgs a{xf32, x, alpha, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
                   static_cast<uint16_t *>(out_bf16), p->rows, p->cols, p->sr_seed, s};
     dispatch_block2d(a, p->rounding, p->select, kOutFake);
     return launch_status();

@@ -74,10 +74,11 @@ def test_quantize_validation_codes():
     bad = B.make_params(32, 64)
     bad.block2d = 2
     assert _q(bad) == 4
-    # 16x16 tiles: both dims multiples of 16, rowwise only, no transform
+    # 16x16 tiles: both dims multiples of 16, no transform
     assert _q(B.make_params(40, 64, block2d=1)) == 2
     assert _q(B.make_params(32, 64, block2d=1, rht=1)) == 5
-    assert _q(B.make_params(32, 64, layout=B.COLWISE, block2d=1), cr=None, sr=None, cc=P, sc=P) == 5
+    # 2D blocks packed for the transposed matrix only: row outputs are then not allowed
+    assert _q(B.make_params(32, 64, layout=B.COLWISE, block2d=1), cr=P, sr=P, cc=P, sc=P) == 4
     # outputs for a layout that was not asked for
     assert _q(ok, cc=P, sc=P) == 4 and _q(ok, hc=P) == 4
     # columnwise requested but its outputs are missing

@@ -175,3 +175,50 @@ def test_gemm_full_size_sampled():
     tol = _tolerance(c_ref, c_abs, K, B.OUT_BF16)
     assert (err <= tol).all(), float((err / tol).max())
     _log(f"  full size: max err / tol = {float((err / tol).max()):.3f}")
+
+
+def test_linear_layer_three_products_of_figure_3():
+    """FPROP, DGRAD and WGRAD of one linear layer (Fig. 3), each as quantize -> NVFP4 product on
+    the GPU, against the oracle's quantize -> product; the operand that a product needs along
+    its other axis is the quantizer's columnwise output.  Gradients use stochastic rounding,
+    the weight-gradient operands the random Hadamard transform (which cancels in the product
+    because both operands carry the same signs along the contraction axis)."""
+    T, K, N = 192, 256, 160                       # tokens, in features, out features
+    x = wl.make("c3", T, K)
+    w = wl.make("c2", N, K)
+    dy = wl.make("c5", T, N)
+    SR_SEED, RHT_SEED = wl.C5_SR_SEED, wl.C5_RHT_SEED
+
+    def both_sides(t, layout, **kw):
+        """Quantize on the GPU and with the oracle; returns (gpu operand, oracle operand)."""
+        bits, td = wl.bf16_bits(t), t.cuda()
+        rht = kw.get("rht", 0)
+        a_gpu = B.nvfp4_46_tensor_scale(td, layout=layout, rht=rht, rht_seed=kw.get("rht_seed", 0))
+        a_ref = ref.tensor_scale(bits, layout=layout, rht=rht, rht_seed=kw.get("rht_seed", 0))
+        assert a_gpu.item() == a_ref
+        o = B.nvfp4_46_quantize(td, a_gpu, layout=layout, **kw)
+        sfx = "row" if layout == B.ROWWISE else "col"
+        c_ref, s_ref, _ = ref.quantize(bits, a_ref, layout=layout, **kw)
+        assert np.array_equal(o[f"codes_{sfx}"].cpu().numpy(), c_ref)
+        return (o[f"codes_{sfx}"], o[f"scales_{sfx}"], a_gpu), (c_ref, s_ref, a_ref)
+
+    def product(A, Bm, exact, what, rel):
+        (ga, ra), (gb, rb) = A, Bm
+        got = B.nvfp4_46_gemm(*ga, *gb, out_dtype=B.OUT_F32).double().cpu().numpy()
+        c_ref, c_abs = ref.gemm(*ra, *rb, want_abs=True)
+        Kc = ra[0].shape[1] * 2
+        assert (np.abs(got - c_ref) <= _tolerance(c_ref, c_abs, Kc, B.OUT_F32)).all(), what
+        err = np.sqrt(((got - exact) ** 2).mean()) / np.sqrt((exact ** 2).mean())
+        _log(f"  {what}: relative RMS error against the unquantized product {err:.3f}")
+        assert err < rel, (what, err)
+
+    xd, wd, dyd = x.double().numpy(), w.double().numpy(), dy.double().numpy()
+    sr = dict(rounding=B.SR, sr_seed=SR_SEED)
+    rht = dict(rht=1, rht_seed=RHT_SEED)
+    # FPROP  y = x w^T          (contraction over K: x rowwise, w rowwise)
+    product(both_sides(x, B.ROWWISE), both_sides(w, B.ROWWISE), xd @ wd.T, "FPROP", 0.25)
+    # DGRAD  dx = dy w          (over N: dy rowwise with SR, w columnwise)
+    product(both_sides(dy, B.ROWWISE, **sr), both_sides(w, B.COLWISE), dyd @ wd, "DGRAD", 0.25)
+    # WGRAD  dw = dy^T x        (over T: dy columnwise with RHT + SR, x columnwise with RHT)
+    product(both_sides(dy, B.COLWISE, **sr, **rht), both_sides(x, B.COLWISE, **rht), dyd.T @ xd,
+            "WGRAD", 0.25)

@@ -193,6 +193,37 @@ def test_block2d_matches_oracle(select, rounding):
         assert np.array_equal(_bits(fq), d_ref)
 
 
+@pytest.mark.parametrize("layout", [B.BOTH, B.COLWISE])
+@pytest.mark.parametrize("select,rounding", [(B.SEL_46_MSE, B.RTN), (B.SEL_46_MAE, B.SR),
+                                             (B.SEL_FORCE6, B.SR_AFTER_RTN_SELECT)])
+def test_block2d_packing_for_the_transposed_matrix(layout, select, rounding):
+    """16x16 tiles are decided once; the columnwise outputs are the same codes and scales
+    packed for W^T (oracle: plain re-indexing of its rowwise 2D outputs)."""
+    for name, shape, dt in (("c2", (272, 400), torch.bfloat16), ("c4", (512, 1024), torch.float32)):
+        x = wl.make(name, *shape, dtype=dt)
+        rows, cols = shape
+        xh, xd = wl.host_array(x), x.cuda()
+        alpha = B.nvfp4_46_tensor_scale(xd)
+        a = float(alpha.item())
+        kw = dict(rounding=rounding, select=select, sr_seed=SR_SEED)
+        c_ref, s_ref, f_ref, d_ref = ref.quantize_2d(xh, a, **kw)
+        cc_ref, sc_ref, fc_ref = ref.repack_2d_columnwise(c_ref, s_ref, f_ref)
+        out = B.nvfp4_46_quantize(xd, alpha, layout=layout, block2d=1, **kw)
+        assert out["scales_col"].shape == (cols // 16, rows // 16)
+        assert np.array_equal(_np(out["codes_col"]), cc_ref)
+        assert np.array_equal(_np(out["scales_col"]), sc_ref)
+        assert np.array_equal(_np(out["choice_col"]), fc_ref)
+        if layout & B.ROWWISE:
+            assert np.array_equal(_np(out["codes_row"]), c_ref)
+            assert np.array_equal(_np(out["scales_row"]), s_ref)
+        else:
+            assert out["codes_row"] is None
+        deq = B.nvfp4_46_dequantize(out["codes_col"], out["scales_col"], alpha, rows, cols,
+                                    layout=B.BLOCK2D | B.COLWISE)
+        assert np.array_equal(_bits(deq), d_ref)
+        assert np.array_equal(ref.dequantize_2d_columnwise(cc_ref, sc_ref, a, rows, cols), d_ref)
+
+
 def test_block2d_transpose_consistency_on_gpu():
     # under a fixed scale rule, quantizing W^T with 16x16 tiles is the transpose of quantizing W
     x = wl.make("c2", 512, 768)

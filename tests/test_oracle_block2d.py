@@ -115,3 +115,28 @@ def test_2d_with_stochastic_rounding_modes():
                                        ref.SR, u)
         packed = codes[row, 8 * tc:8 * tc + 8]
         assert list(packed & 15) == list(q[0::2]) and list(packed >> 4) == list(q[1::2])
+
+
+def test_columnwise_packing_of_2d_blocks_is_the_transposed_matrix():
+    """The tiles are decided once; W^T gets the same codes and scales packed along its rows."""
+    x = wl.bf16_bits(wl.make("c2", 64, 96))
+    alpha = ref.tensor_scale(x)
+    codes, scales, choice, deq = ref.quantize_2d(x, alpha)
+    cc, sc, fc = ref.repack_2d_columnwise(codes, scales, choice)
+    assert cc.shape == (96, 32) and sc.shape == (6, 4)
+    # nibble by nibble: code of element (r, c)
+    lo, hi = codes & 15, codes >> 4
+    q = np.stack([lo, hi], axis=-1).reshape(64, 96)
+    qt = np.stack([cc & 15, cc >> 4], axis=-1).reshape(96, 64)
+    assert np.array_equal(qt, q.T)
+    assert np.array_equal(sc, scales.T) and np.array_equal(fc, choice.T)
+    # both packings dequantize to the same matrix
+    assert np.array_equal(ref.dequantize_2d_columnwise(cc, sc, alpha, 64, 96), deq)
+    # and it is what a rowwise-packed dequantizer makes of W^T
+    assert np.array_equal(ref.dequantize_2d(cc, sc, alpha, 96, 64), deq.T)
+    # under a fixed scale rule nothing depends on the order of the error sums, so this equals
+    # quantizing the transposed matrix outright
+    c6, s6, f6, _ = ref.quantize_2d(x, alpha, select=ref.SEL_FORCE6)
+    ct, st, ft, _ = ref.quantize_2d(np.ascontiguousarray(x.T), alpha, select=ref.SEL_FORCE6)
+    cc6, sc6, fc6 = ref.repack_2d_columnwise(c6, s6, f6)
+    assert np.array_equal(cc6, ct) and np.array_equal(sc6, st) and np.array_equal(fc6, ft)
