@@ -18,6 +18,11 @@
 // packed FP16 multiplication by the scale (times 2^-8, built from the scale byte by a
 // shift).  Which eight contraction indices a lane feeds to a given matrix instruction is
 // the same for A and for B, which is all the sum needs.
+//
+// Two kernels share this plan: k_gemm (any K that is a multiple of 32; the workgroup stages
+// chunks through registers into shared LDS buffers, one barrier per chunk) and k_gemm_dma
+// (K a multiple of 128; every wave fills its own LDS with asynchronous global -> LDS copies
+// and never meets a barrier).
 #include <hip/hip_runtime.h>
 
 #include "codec.hpp"
@@ -28,6 +33,12 @@ namespace nvfp4_46 {
 typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// 1: products with K a multiple of 128 use the variant with asynchronous global -> LDS copies
+// (k_gemm_dma); 0: every product uses the variant that stages through registers (k_gemm)
+#ifndef NVFP4_46_GEMM_DMA
+#define NVFP4_46_GEMM_DMA 1
+#endif
 
 constexpr int kGemmThreads = 256;
 constexpr int GT = 256;                  // rows of A (and of B) per workgroup tile
@@ -268,6 +279,201 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm(
     }
 }
 
+// ----------------------------------------------------------------------------------------
+// The same product with wave-private LDS filled by asynchronous global -> LDS loads
+// (global_load_lds_dwordx4): no staging registers, no LDS write instructions and no
+// workgroup barrier at all.  Each wave copies the 128 rows of A and the 128 rows of B that its
+// own quarter of the tile needs (the two waves that share rows each fetch them; operand
+// bytes are small) into its own 2 x 18 KiB of LDS:
+//   per stage: A codes [128][64 B], B codes [128][64 B], A scales [128][8 B], B scales [128][8 B]
+// A load instruction writes its 64 lanes' 16 (or 4) bytes to consecutive LDS addresses, so
+// the LDS layout is plain row-major; to keep the later 16-byte reads of 16 lanes on 16
+// different bank groups, lane (row, position p) of a copy fetches the row's 16-byte unit
+// p ^ ((row >> 2) & 3), and readers look unit u up at position u ^ ((row >> 2) & 3).
+// The copies are issued with inline assembly (the compiler then neither reorders LDS reads
+// around them nor waits for all of them at every LDS read) and waited for with explicit
+// s_waitcnt vmcnt: the kernel issues no other vector-memory loads inside the loop.
+// Only for K a multiple of 128 (whole chunks) and K <= 2^24 (32-bit lane offsets).
+constexpr uint32_t kDmaStage = 2 * 128 * 64 + 2 * 128 * 8;   // 18432 bytes per wave and stage
+constexpr uint32_t kDmaWave = 2 * kDmaStage;
+[[maybe_unused]] constexpr size_t kGemmDmaLdsBytes = 4 * kDmaWave;   // 147456
+
+// M0 = LDS byte address of lane 0's piece; %1 = the lane's 32-bit byte offset (vector
+// register), %2 = the 64-bit base address (scalar register pair).
+#define NV_DMA16(lds_sgpr, imm, voff, gbase)                                                  \
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"                          \
+               :: "s"(lds_sgpr), "v"(voff), "s"(gbase) : "memory", "m0")
+#define NV_DMA4(lds_sgpr, imm, voff, gbase)                                                   \
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2"                            \
+               :: "s"(lds_sgpr), "v"(voff), "s"(gbase) : "memory", "m0")
+
+template <bool OUTF32>
+__global__ __launch_bounds__(kGemmThreads) void k_gemm_dma(
+    const uint8_t *__restrict__ codes_a, const uint8_t *__restrict__ scales_a,
+    const float *__restrict__ alpha_a, const uint8_t *__restrict__ codes_b,
+    const uint8_t *__restrict__ scales_b, const float *__restrict__ alpha_b,
+    void *__restrict__ out, int64_t M, int64_t N, int64_t K, uint32_t tiles_n) {
+  extern __shared__ __align__(16) uint8_t lds_raw[];
+  const uint32_t t = threadIdx.x, lane = t & 63u;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const uint32_t r = lane & 31u, g = lane >> 5;
+  const uint32_t wm = wave >> 1, wn = wave & 1u;
+  const uint32_t tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_m * tiles_n;
+  const int64_t m0 = (int64_t)tile_m * GT + wm * 128, n0 = (int64_t)tile_n * GT + wn * 128;
+  const int64_t row_codes = K / 2, row_scales = K / 16;
+
+  const uint8_t *wl = lds_raw + wave * kDmaWave;   // the wave's LDS, for reading
+  const uint32_t lds_wave =
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds_raw + wave * kDmaWave;
+
+  // first rows of the wave's operand slices (a slice that starts past the end re-reads the
+  // last row; nothing of it is stored), and each lane's byte offset from there for every
+  // copy instruction of a chunk
+  const int64_t a_base = m0 < M ? m0 : M - 1, b_base = n0 < N ? n0 : N - 1;
+  // (wave-uniform by construction; read through readfirstlane so that they live in scalar
+  // registers, which is where the copy instruction takes its base address from)
+  auto uniform = [](const uint8_t *p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const uint8_t *>(((uint64_t)hi << 32) | lo);
+  };
+  const uint8_t *gca = uniform(codes_a + a_base * row_codes), *gcb = uniform(codes_b + b_base * row_codes);
+  const uint8_t *gsa = uniform(scales_a + a_base * row_scales), *gsb = uniform(scales_b + b_base * row_scales);
+  uint32_t oca[8], ocb[8], osa[4], osb[4];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    const uint32_t row = 16 * q + (lane >> 2), unit = (lane & 3u) ^ ((row >> 2) & 3u);
+    const int64_t ra = a_base + row < M ? row : M - 1 - a_base;
+    const int64_t rb = b_base + row < N ? row : N - 1 - b_base;
+    oca[q] = (uint32_t)(ra * row_codes) + unit * 16;
+    ocb[q] = (uint32_t)(rb * row_codes) + unit * 16;
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const uint32_t row = 32 * q + (lane >> 1), half = lane & 1u;
+    const int64_t ra = a_base + row < M ? row : M - 1 - a_base;
+    const int64_t rb = b_base + row < N ? row : N - 1 - b_base;
+    osa[q] = (uint32_t)(ra * row_scales) + half * 4;
+    osb[q] = (uint32_t)(rb * row_scales) + half * 4;
+  }
+  // the 24 copy instructions of a chunk, numbered so that they can be issued one at a time
+  auto copy_one = [&](int64_t c, uint32_t stage, int n) {
+    const uint32_t lds = lds_wave + stage * kDmaStage;
+    if (n < 8) NV_DMA16(lds + n * 1024, 0, oca[n], gca + c * (GK / 2));
+    else if (n < 16) NV_DMA16(lds + 8192 + (n - 8) * 1024, 0, ocb[n - 8], gcb + c * (GK / 2));
+    else if (n < 20) NV_DMA4(lds + 16384 + (n - 16) * 256, 0, osa[n - 16], gsa + c * (GK / 16));
+    else NV_DMA4(lds + 17408 + (n - 20) * 256, 0, osb[n - 20], gsb + c * (GK / 16));
+  };
+  auto copy_chunk = [&](int64_t c, uint32_t stage) {
+#pragma unroll
+    for (int n = 0; n < 24; ++n) copy_one(c, stage, n);
+  };
+
+  // ---- LDS -> registers, one operand tile at a time (u = 0..3: A tiles, 4..7: B tiles)
+  const uint32_t swz = (r >> 2) & 3u;
+  auto read_tile = [&](uint32_t stage, int half, int u, RawHalf &h) {
+    const uint8_t *st = wl + stage * kDmaStage + (u < 4 ? 0 : 8192);
+    const uint8_t *sc = wl + stage * kDmaStage + (u < 4 ? 16384 : 17408);
+    const uint32_t row = 32 * (u & 3) + r, pos = ((2 * half + g) ^ swz) * 16;
+    const uint4 codes = *reinterpret_cast<const uint4 *>(st + row * 64 + pos);
+    // the lane's two scale bytes of this half (blocks 4*half + 2*g and + 1), still raw
+    const uint32_t two = *reinterpret_cast<const uint16_t *>(sc + row * 8 + 4 * half + 2 * g);
+    if (u < 4) { h.a[u] = codes; h.sa[u] = two; } else { h.b[u - 4] = codes; h.sb[u - 4] = two; }
+  };
+  // operands of step s (0..3) of a half for tile u; at s == 0 the two scale bytes are turned
+  // into two FP16 bit patterns (byte << 7) in one word
+  auto expand_tile = [&](RawHalf &h, int s, int u, Frags &f) {
+    const uint4 &w4 = u < 4 ? h.a[u] : h.b[u - 4];
+    uint32_t &sc = u < 4 ? h.sa[u] : h.sb[u - 4];
+    if (s == 0) sc = __builtin_amdgcn_perm(0u, sc, 0x0c010c00u) << 7;
+    const uint32_t w = s == 0 ? w4.x : s == 1 ? w4.y : s == 2 ? w4.z : w4.w;
+    const h2 pair = __builtin_bit_cast(h2, sc);
+    const h8 e = expand8(w, s < 2 ? pair.x : pair.y);
+    if (u < 4) f.a[u] = e; else f.b[u - 4] = e;
+  };
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  const int64_t nchunks = K / GK;
+  RawHalf h0, h1;
+  Frags f0, f1;
+  copy_chunk(0, 0);
+  copy_chunk(nchunks > 1 ? 1 : 0, 1);
+  asm volatile("s_waitcnt vmcnt(24)" ::: "memory");      // chunk 0 is in LDS
+#pragma unroll
+  for (int u = 0; u < 8; ++u) read_tile(0, 0, u, h0);
+#pragma unroll
+  for (int u = 0; u < 8; ++u) expand_tile(h0, 0, u, f0);
+
+  // Chunk c sits in stage c & 1.  A step is eight units of two matrix instructions; unit u
+  // also expands operand tile u for the next step and carries the step's share of LDS
+  // reads and copy instructions, so that everything issues in the matrix unit's shadow:
+  //   step 1        reads the chunk's second half (then the stage is free);
+  //   steps 3-5     start the 24 copies of chunk c + 2 into this stage, one per unit;
+  //   step 6        waits until only those 24 are outstanding (chunk c + 1 has landed in the
+  //                 other stage) and reads its first half;
+  //   step 7        expands the next chunk's first step.
+  auto chunk = [&](int64_t c, bool last) {
+    const uint32_t cur = (uint32_t)c & 1u, nxt = cur ^ 1u;
+    const int64_t c2 = c + 2 < nchunks ? c + 2 : nchunks - 1;   // past the end: a harmless re-read
+#pragma unroll
+    for (int st = 0; st < 8; ++st) {
+      Frags &fc = (st & 1) ? f1 : f0, &fn = (st & 1) ? f0 : f1;
+      if (st == 3 && !last) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      if (st == 6 && !last) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (st == 1) read_tile(cur, 1, u, h1);
+        if (st >= 3 && st <= 5 && !last) copy_one(c2, cur, 8 * (st - 3) + u);
+        if (st == 6 && !last) read_tile(nxt, 0, u, h0);
+        if (st < 7) expand_tile(st < 3 ? h0 : h1, (st + 1) & 3, u, fn);
+        else if (!last) expand_tile(h0, 0, u, fn);
+#pragma unroll
+        for (int q = 2 * u; q < 2 * u + 2; ++q)
+          acc[q >> 2][q & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fc.a[q >> 2], fc.b[q & 3],
+                                                                      acc[q >> 2][q & 3], 0, 0, 0);
+        const bool reads = st == 1 || (st == 6 && !last);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (reads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (reads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  };
+  for (int64_t c = 0; c + 1 < nchunks; ++c) chunk(c, false);
+  chunk(nchunks - 1, true);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // nothing may still be writing LDS
+
+  const float scale = alpha_a[0] * alpha_b[0];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int64_t col = n0 + 32 * j + r;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int64_t row = m0 + 32 * i + 8 * (v / 4) + 4 * g + (v % 4);
+        if (row < M && col < N) {
+          const float c = acc[i][j][v] * scale;
+          if (OUTF32)
+            static_cast<float *>(out)[row * N + col] = c;
+          else
+            static_cast<uint16_t *>(out)[row * N + col] = (uint16_t)pack_bf16x2(c, 0.0f);
+        }
+      }
+    }
+}
+
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace nvfp4_46
@@ -304,6 +510,24 @@ extern "C" int nvfp4_46_gemm(const void *codes_a, const void *scales_a, const fl
                        alpha_b, out, M, N, K, (uint32_t)tiles_n);
   };
   const bool kfull = (K % GK) == 0, f32 = out_dtype == NVFP4_OUT_F32;
+#if NVFP4_46_GEMM_DMA
+  if (kfull && K <= ((int64_t)1 << 24)) {
+    auto go_dma = [&](auto kernel) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)kGemmDmaLdsBytes) != hipSuccess)
+        return;
+      hipLaunchKernelGGL(kernel, grid, block, kGemmDmaLdsBytes, s,
+                         static_cast<const uint8_t *>(codes_a), static_cast<const uint8_t *>(scales_a),
+                         alpha_a, static_cast<const uint8_t *>(codes_b),
+                         static_cast<const uint8_t *>(scales_b), alpha_b, out, M, N, K,
+                         (uint32_t)tiles_n);
+    };
+    if (f32) go_dma(k_gemm_dma<true>);
+    else go_dma(k_gemm_dma<false>);
+    return hipGetLastError() == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+  }
+#endif
   if (kfull) {
     if (f32) go(k_gemm<true, true>);
     else go(k_gemm<true, false>);
