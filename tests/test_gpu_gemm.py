@@ -222,3 +222,24 @@ def test_linear_layer_three_products_of_figure_3():
     # WGRAD  dw = dy^T x        (over T: dy columnwise with RHT + SR, x columnwise with RHT)
     product(both_sides(dy, B.COLWISE, **sr, **rht), both_sides(x, B.COLWISE, **rht), dyd.T @ xd,
             "WGRAD", 0.25)
+
+
+@pytest.mark.parametrize("K", [512, 544])      # the copy-based and the register-staged kernel
+def test_gemm_can_be_captured_in_a_graph_and_replayed(K):
+    A, Bm = _operand("c3", 320, K), _operand("c2", 272, K)
+    args = [_dev(A[0]), _dev(A[1]), _alpha(A[2]), _dev(Bm[0]), _dev(Bm[1]), _alpha(Bm[2])]
+    out = torch.empty((320, 272), dtype=torch.float32, device="cuda")
+    want = B.nvfp4_46_gemm(*args, out_dtype=B.OUT_F32).clone()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        B.nvfp4_46_gemm(*args, out_dtype=B.OUT_F32, out=out, stream=s)     # warm-up
+    s.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        B.nvfp4_46_gemm(*args, out_dtype=B.OUT_F32, out=out, stream=torch.cuda.current_stream())
+    for _ in range(3):
+        out.zero_()                     # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want)
