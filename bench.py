@@ -62,6 +62,10 @@ def parse():
                     help="launch a calibration copy and each kernel of the step a few times and "
                          "exit (for `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE -- python3 bench.py "
                          "--counter-pass`); prints no benchmark line")
+    ap.add_argument("--counter-pass-gemm", action="store_true",
+                    help="launch nvfp4_46_gemm (8192^3, random codes, scale bytes 0x30..0x47) four "
+                         "times and exit (for `rocprofv3 --pmc ... -- python3 bench.py "
+                         "--counter-pass-gemm`); prints no benchmark line")
     return ap.parse_args()
 
 
@@ -361,6 +365,23 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     B.lib()
+    if args.counter_pass_gemm:
+        g = torch.Generator(device="cuda")
+        g.manual_seed(1)
+        m = 8192
+        u8 = dict(dtype=torch.uint8, device="cuda", generator=g)
+        ops = []
+        for _ in range(2):
+            ops += [torch.randint(0, 256, (m, m // 2), **u8), torch.randint(0x30, 0x48, (m, m // 16), **u8),
+                    torch.ones(1, dtype=torch.float32, device="cuda")]
+        out = torch.empty((m, m), dtype=torch.bfloat16, device="cuda")
+        for _ in range(4):
+            rc = B.gemm_raw(*ops, m, m, m, B.OUT_BF16, out, torch.cuda.current_stream())
+            if rc:
+                raise RuntimeError(f"nvfp4_46_gemm failed with status {rc}")
+        torch.cuda.synchronize()
+        print("counter pass done: 4 products 8192 x 8192 x 8192")
+        return
     rows, cols = args.rows, args.cols
     n = rows * cols
     x_host = wl.make("c2", rows, cols)
