@@ -161,6 +161,9 @@ int nvfp4_46_fake_quant(const void *x, const nvfp4_46_params *p, const float *al
 
 /* element type of nvfp4_46_gemm's output */
 enum { NVFP4_OUT_BF16 = 0, NVFP4_OUT_F32 = 1 };
+/* nvfp4_46_gemm flags: the operand was quantized with block2d = 1, i.e. its scales are one
+ * line per 16 rows, [rows/16][K/16] (rows must then be a multiple of 16) */
+enum { NVFP4_GEMM_A_TILE_SCALES = 1, NVFP4_GEMM_B_TILE_SCALES = 2 };
 
 /* The consumer of the quantizer's output: the product of two NVFP4 tensors (Fig. 3: FPROP,
  * DGRAD and WGRAD each multiply two operands quantized along the contraction axis),
@@ -171,17 +174,20 @@ enum { NVFP4_OUT_BF16 = 0, NVFP4_OUT_F32 = 1 };
  * C agrees with the exactly rounded result to within 2 K 2^-24 alpha_a alpha_b
  * sum_k |a b| plus the output rounding, and is bit-reproducible from call to call.
  *   codes_a  in   [M][K/2]   rowwise NVFP4 codes of A   (nvfp4_46_quantize's codes_row)
- *   scales_a in   [M][K/16]  E4M3 scale bytes of A, each <= 0x7E
+ *   scales_a in   [M][K/16]  E4M3 scale bytes of A, each <= 0x7E ([M/16][K/16] with
+ *                            NVFP4_GEMM_A_TILE_SCALES in `flags`; likewise for B)
  *   codes_b, scales_b  in    the same for B, which is [N][K] -- for y = x W^T pass the
  *                            rowwise quantization of W [N][K]; an operand that is needed
  *                            transposed is the columnwise output of the quantizer
  *   alpha_a, alpha_b   in    1 float each (device): the operands' tensor scales
  *   out      out  [M][N] row-major, BF16 (round to nearest even) or fp32 per `out_dtype`
- * K must be a multiple of 32.  Errors: NULL pointer -> ERR_NULL; non-positive dims or
- * K % 32 != 0 -> ERR_SHAPE; misaligned buffer -> ERR_ALIGN; bad out_dtype -> ERR_PARAM. */
+ * K must be a multiple of 32.  Errors: NULL pointer -> ERR_NULL; non-positive dims,
+ * K % 32 != 0 or a tile-scaled operand whose rows are not a multiple of 16 -> ERR_SHAPE;
+ * misaligned buffer -> ERR_ALIGN; bad out_dtype or flags -> ERR_PARAM. */
 int nvfp4_46_gemm(const void *codes_a, const void *scales_a, const float *alpha_a,
                   const void *codes_b, const void *scales_b, const float *alpha_b, int64_t M,
-                  int64_t N, int64_t K, uint32_t out_dtype, void *out, void *stream);
+                  int64_t N, int64_t K, uint32_t out_dtype, uint32_t flags, void *out,
+                  void *stream);
 
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *nvfp4_46_status_string(int status);

@@ -681,10 +681,12 @@ int nvfp4_46_ref_block_errors(const uint16_t *x, int64_t rows, int64_t cols, int
  * running sum in fp64 in the order k = 0, 1, ...; each product is exact in fp64 (at most 12
  * significant bits) and so is alpha_a * alpha_b.  `C` gets the fp64 values; `Cabs` (optional)
  * gets alpha_a * alpha_b * sum_k |a[m][k] * b[n][k]|, the quantity an error bound for a
- * lower-precision accumulation is stated in. */
+ * lower-precision accumulation is stated in.
+ * tiles_a / tiles_b = 1: that operand was quantized with 16x16 tiles (Section 4.1), so its
+ * scales are [rows/16][K/16] and row m uses line m / 16. */
 int nvfp4_46_ref_gemm(const uint8_t *codes_a, const uint8_t *scales_a, float alpha_a,
                       const uint8_t *codes_b, const uint8_t *scales_b, float alpha_b, int64_t M,
-                      int64_t N, int64_t K, double *C, double *Cabs) {
+                      int64_t N, int64_t K, int tiles_a, int tiles_b, double *C, double *Cabs) {
   const int64_t KB = K / BLOCK;
   const double alpha = (double)alpha_a * (double)alpha_b;
 #pragma omp parallel for schedule(static)
@@ -694,8 +696,9 @@ int nvfp4_46_ref_gemm(const uint8_t *codes_a, const uint8_t *scales_a, float alp
       for (int64_t k = 0; k < K; ++k) {
         uint8_t ba = codes_a[m * (K / 2) + k / 2], bb = codes_b[n * (K / 2) + k / 2];
         uint8_t ca = (k & 1) ? (ba >> 4) : (ba & 15), cb = (k & 1) ? (bb >> 4) : (bb & 15);
-        double a = (double)ref_e2m1_decode(ca) * (double)ref_e4m3_decode(scales_a[m * KB + k / BLOCK]);
-        double b = (double)ref_e2m1_decode(cb) * (double)ref_e4m3_decode(scales_b[n * KB + k / BLOCK]);
+        int64_t la = tiles_a ? m / BLOCK : m, lb = tiles_b ? n / BLOCK : n;
+        double a = (double)ref_e2m1_decode(ca) * (double)ref_e4m3_decode(scales_a[la * KB + k / BLOCK]);
+        double b = (double)ref_e2m1_decode(cb) * (double)ref_e4m3_decode(scales_b[lb * KB + k / BLOCK]);
         acc += a * b;
         acc_abs += fabs(a * b);
       }

@@ -99,7 +99,8 @@ def lib() -> C.CDLL:
         L.nvfp4_46_ref_dequantize_2d.argtypes = [u8p, u8p, f32, i64, i64, u16p]
         f64p = C.POINTER(C.c_double)
         L.nvfp4_46_ref_gemm.restype = i32
-        L.nvfp4_46_ref_gemm.argtypes = [u8p, u8p, f32, u8p, u8p, f32, i64, i64, i64, f64p, f64p]
+        L.nvfp4_46_ref_gemm.argtypes = [u8p, u8p, f32, u8p, u8p, f32, i64, i64, i64, i32, i32,
+                                        f64p, f64p]
         L.ref_e2m1_rtn_bits_range.restype = None
         L.ref_e2m1_rtn_bits_range.argtypes = [C.c_uint32, i64, u8p]
         L.ref_e4m3_encode_bits_range.restype = None
@@ -357,21 +358,25 @@ def dequantize_2d(codes: np.ndarray, scales: np.ndarray, alpha: float, rows: int
 
 
 def gemm(codes_a: np.ndarray, scales_a: np.ndarray, alpha_a: float, codes_b: np.ndarray,
-         scales_b: np.ndarray, alpha_b: float, want_abs: bool = False):
+         scales_b: np.ndarray, alpha_b: float, want_abs: bool = False, tiles_a: bool = False,
+         tiles_b: bool = False):
     """C [M][N] (float64) = alpha_a * alpha_b * A . B^T of two rowwise NVFP4 operands
-    (codes [M][K/2] / [N][K/2], scales [M][K/16] / [N][K/16]); with `want_abs` also the same
-    sum over the products' magnitudes."""
+    (codes [M][K/2] / [N][K/2], scales [M][K/16] / [N][K/16], or [rows/16][K/16] for an
+    operand quantized with 16x16 tiles); with `want_abs` also the same sum over the products'
+    magnitudes."""
     M, N = codes_a.shape[0], codes_b.shape[0]
     K = codes_a.shape[1] * 2
     assert codes_b.shape == (N, K // 2) and K % 16 == 0
-    assert scales_a.shape == (M, K // 16) and scales_b.shape == (N, K // 16)
+    assert scales_a.shape == ((M // 16 if tiles_a else M), K // 16)
+    assert scales_b.shape == ((N // 16 if tiles_b else N), K // 16)
     for a in (codes_a, scales_a, codes_b, scales_b):
         assert a.dtype == np.uint8
     out = np.zeros((M, N), np.float64)
     out_abs = np.zeros((M, N), np.float64) if want_abs else None
     rc = lib().nvfp4_46_ref_gemm(_p(codes_a, C.c_uint8), _p(scales_a, C.c_uint8), alpha_a,
                                  _p(codes_b, C.c_uint8), _p(scales_b, C.c_uint8), alpha_b, M, N, K,
-                                 _p(out, C.c_double), _p(out_abs, C.c_double))
+                                 int(tiles_a), int(tiles_b), _p(out, C.c_double),
+                                 _p(out_abs, C.c_double))
     assert rc == 0
     return (out, out_abs) if want_abs else out
 

@@ -21,6 +21,7 @@ RTN, SR, SR_AFTER_RTN_SELECT = 0, 1, 2
 SEL_46_MSE, SEL_FORCE6, SEL_FORCE4, SEL_46_MAE, SEL_46_ABSMAX = 0, 1, 2, 3, 4
 X_BF16, X_F32 = 0, 1
 OUT_BF16, OUT_F32 = 0, 1
+GEMM_A_TILE_SCALES, GEMM_B_TILE_SCALES = 1, 2
 
 STATUS_NAMES = {0: "NVFP4_OK", 1: "NVFP4_ERR_NULL", 2: "NVFP4_ERR_SHAPE", 3: "NVFP4_ERR_ALIGN",
                 4: "NVFP4_ERR_PARAM", 5: "NVFP4_ERR_UNSUPPORTED", 6: "NVFP4_ERR_HIP"}
@@ -75,7 +76,7 @@ def lib() -> C.CDLL:
         L.nvfp4_46_fake_quant.restype = C.c_int
         L.nvfp4_46_fake_quant.argtypes = [vp, pp, vp, vp, vp]
         L.nvfp4_46_gemm.restype = C.c_int
-        L.nvfp4_46_gemm.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, u32, vp, vp]
+        L.nvfp4_46_gemm.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, u32, u32, vp, vp]
         L.nvfp4_46_status_string.restype = C.c_char_p
         L.nvfp4_46_status_string.argtypes = [C.c_int]
         L.nvfp4_46_debug_e2m1_rtn_range.restype = C.c_int
@@ -151,10 +152,10 @@ def fake_quant_raw(x, params, alpha, out, stream=None) -> int:
 
 
 def gemm_raw(codes_a, scales_a, alpha_a, codes_b, scales_b, alpha_b, M, N, K, out_dtype, out,
-             stream=None) -> int:
+             stream=None, flags: int = 0) -> int:
     return lib().nvfp4_46_gemm(_ptr(codes_a), _ptr(scales_a), _ptr(alpha_a), _ptr(codes_b),
-                               _ptr(scales_b), _ptr(alpha_b), M, N, K, out_dtype, _ptr(out),
-                               _stream(stream))
+                               _ptr(scales_b), _ptr(alpha_b), M, N, K, out_dtype, flags,
+                               _ptr(out), _stream(stream))
 
 
 # ---- the same calls with output allocation and error checking ---------------------------
@@ -244,16 +245,18 @@ def nvfp4_46_fake_quant(x: torch.Tensor, alpha: torch.Tensor, layout: int = ROWW
 def nvfp4_46_gemm(codes_a: torch.Tensor, scales_a: torch.Tensor, alpha_a: torch.Tensor,
                   codes_b: torch.Tensor, scales_b: torch.Tensor, alpha_b: torch.Tensor,
                   out_dtype: int = OUT_BF16, out: torch.Tensor | None = None,
-                  stream=None) -> torch.Tensor:
-    """C [M][N] = alpha_a alpha_b A B^T of two rowwise-quantized operands A [M][K], B [N][K]."""
+                  stream=None, flags: int = 0) -> torch.Tensor:
+    """C [M][N] = alpha_a alpha_b A B^T of two rowwise-quantized operands A [M][K], B [N][K];
+    `flags` marks operands whose scales come per 16x16 tile ([rows/16][K/16])."""
     M, N, K = int(codes_a.shape[0]), int(codes_b.shape[0]), int(codes_a.shape[1]) * 2
     assert codes_b.shape[1] * 2 == K
-    assert tuple(scales_a.shape) == (M, K // 16) and tuple(scales_b.shape) == (N, K // 16)
+    assert tuple(scales_a.shape) == (M // 16 if flags & GEMM_A_TILE_SCALES else M, K // 16)
+    assert tuple(scales_b.shape) == (N // 16 if flags & GEMM_B_TILE_SCALES else N, K // 16)
     if out is None:
         out = torch.empty((M, N), device=codes_a.device,
                           dtype=torch.float32 if out_dtype == OUT_F32 else torch.bfloat16)
     _check(gemm_raw(codes_a, scales_a, alpha_a, codes_b, scales_b, alpha_b, M, N, K, out_dtype,
-                    out, stream), "nvfp4_46_gemm")
+                    out, stream, flags), "nvfp4_46_gemm")
     return out
 
 

@@ -95,7 +95,8 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm(
     const uint8_t *__restrict__ codes_a, const uint8_t *__restrict__ scales_a,
     const float *__restrict__ alpha_a, const uint8_t *__restrict__ codes_b,
     const uint8_t *__restrict__ scales_b, const float *__restrict__ alpha_b,
-    void *__restrict__ out, int64_t M, int64_t N, int64_t K, uint32_t tiles_n) {
+    void *__restrict__ out, int64_t M, int64_t N, int64_t K, uint32_t tiles_n, uint32_t sha,
+    uint32_t shb) {
   extern __shared__ __align__(16) uint8_t lds_raw[];
   GemmStage *stage = reinterpret_cast<GemmStage *>(lds_raw);
 
@@ -120,8 +121,9 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm(
     pa[q] = codes_a + clamp_row(m0 + ld_row + 64 * q, M) * row_codes + ld_unit * 16;
     pb[q] = codes_b + clamp_row(n0 + ld_row + 64 * q, N) * row_codes + ld_unit * 16;
   }
-  const uint8_t *psa = scales_a + clamp_row(m0 + t, M) * row_scales;
-  const uint8_t *psb = scales_b + clamp_row(n0 + t, N) * row_scales;
+  // a row's scale line: the row itself, or row / 16 for an operand quantized in 16x16 tiles
+  const uint8_t *psa = scales_a + (clamp_row(m0 + t, M) >> sha) * row_scales;
+  const uint8_t *psb = scales_b + (clamp_row(n0 + t, N) >> shb) * row_scales;
   auto fetch = [&](int64_t k0) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -312,7 +314,8 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm_dma(
     const uint8_t *__restrict__ codes_a, const uint8_t *__restrict__ scales_a,
     const float *__restrict__ alpha_a, const uint8_t *__restrict__ codes_b,
     const uint8_t *__restrict__ scales_b, const float *__restrict__ alpha_b,
-    void *__restrict__ out, int64_t M, int64_t N, int64_t K, uint32_t tiles_n) {
+    void *__restrict__ out, int64_t M, int64_t N, int64_t K, uint32_t tiles_n, uint32_t sha,
+    uint32_t shb) {
   extern __shared__ __align__(16) uint8_t lds_raw[];
   const uint32_t t = threadIdx.x, lane = t & 63u;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -339,7 +342,9 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm_dma(
     return reinterpret_cast<const uint8_t *>(((uint64_t)hi << 32) | lo);
   };
   const uint8_t *gca = uniform(codes_a + a_base * row_codes), *gcb = uniform(codes_b + b_base * row_codes);
-  const uint8_t *gsa = uniform(scales_a + a_base * row_scales), *gsb = uniform(scales_b + b_base * row_scales);
+  // (a row's scale line: the row itself, or row / 16 for an operand quantized in 16x16 tiles)
+  const uint8_t *gsa = uniform(scales_a + (a_base >> sha) * row_scales);
+  const uint8_t *gsb = uniform(scales_b + (b_base >> shb) * row_scales);
   uint32_t oca[8], ocb[8], osa[4], osb[4];
 #pragma unroll
   for (int q = 0; q < 8; ++q) {
@@ -354,8 +359,8 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm_dma(
     const uint32_t row = 32 * q + (lane >> 1), half = lane & 1u;
     const int64_t ra = a_base + row < M ? row : M - 1 - a_base;
     const int64_t rb = b_base + row < N ? row : N - 1 - b_base;
-    osa[q] = (uint32_t)(ra * row_scales) + half * 4;
-    osb[q] = (uint32_t)(rb * row_scales) + half * 4;
+    osa[q] = (uint32_t)((((a_base + ra) >> sha) - (a_base >> sha)) * row_scales) + half * 4;
+    osb[q] = (uint32_t)((((b_base + rb) >> shb) - (b_base >> shb)) * row_scales) + half * 4;
   }
   // the 24 copy instructions of a chunk, numbered so that they can be issued one at a time
   auto copy_one = [&](int64_t c, uint32_t stage, int n) {
@@ -482,15 +487,21 @@ using namespace nvfp4_46;
 
 extern "C" int nvfp4_46_gemm(const void *codes_a, const void *scales_a, const float *alpha_a,
                              const void *codes_b, const void *scales_b, const float *alpha_b,
-                             int64_t M, int64_t N, int64_t K, uint32_t out_dtype, void *out,
-                             void *stream) {
+                             int64_t M, int64_t N, int64_t K, uint32_t out_dtype, uint32_t flags,
+                             void *out, void *stream) {
   if (!codes_a || !scales_a || !alpha_a || !codes_b || !scales_b || !alpha_b || !out)
     return NVFP4_ERR_NULL;
   if (M <= 0 || N <= 0 || K <= 0 || (K % 32) != 0) return NVFP4_ERR_SHAPE;
   if (M > (int64_t)1 << 31 || N > (int64_t)1 << 31 || K > (int64_t)1 << 31 ||
       M * K > (int64_t)1 << 40 || N * K > (int64_t)1 << 40 || M * N > (int64_t)1 << 40)
     return NVFP4_ERR_SHAPE;
-  if (out_dtype > NVFP4_OUT_F32) return NVFP4_ERR_PARAM;
+  if (out_dtype > NVFP4_OUT_F32 || flags > (NVFP4_GEMM_A_TILE_SCALES | NVFP4_GEMM_B_TILE_SCALES))
+    return NVFP4_ERR_PARAM;
+  if (((flags & NVFP4_GEMM_A_TILE_SCALES) && (M % 16) != 0) ||
+      ((flags & NVFP4_GEMM_B_TILE_SCALES) && (N % 16) != 0))
+    return NVFP4_ERR_SHAPE;
+  const uint32_t sha = (flags & NVFP4_GEMM_A_TILE_SCALES) ? 4u : 0u;
+  const uint32_t shb = (flags & NVFP4_GEMM_B_TILE_SCALES) ? 4u : 0u;
   if (!aligned16(codes_a) || !aligned16(scales_a) || !aligned16(codes_b) || !aligned16(scales_b) ||
       !aligned16(out))
     return NVFP4_ERR_ALIGN;
@@ -507,7 +518,7 @@ extern "C" int nvfp4_46_gemm(const void *codes_a, const void *scales_a, const fl
     hipLaunchKernelGGL(kernel, grid, block, kGemmLdsBytes, s, static_cast<const uint8_t *>(codes_a),
                        static_cast<const uint8_t *>(scales_a), alpha_a,
                        static_cast<const uint8_t *>(codes_b), static_cast<const uint8_t *>(scales_b),
-                       alpha_b, out, M, N, K, (uint32_t)tiles_n);
+                       alpha_b, out, M, N, K, (uint32_t)tiles_n, sha, shb);
   };
   const bool kfull = (K % GK) == 0, f32 = out_dtype == NVFP4_OUT_F32;
 #if NVFP4_46_GEMM_DMA
@@ -521,7 +532,7 @@ extern "C" int nvfp4_46_gemm(const void *codes_a, const void *scales_a, const fl
                          static_cast<const uint8_t *>(codes_a), static_cast<const uint8_t *>(scales_a),
                          alpha_a, static_cast<const uint8_t *>(codes_b),
                          static_cast<const uint8_t *>(scales_b), alpha_b, out, M, N, K,
-                         (uint32_t)tiles_n);
+                         (uint32_t)tiles_n, sha, shb);
     };
     if (f32) go_dma(k_gemm_dma<true>);
     else go_dma(k_gemm_dma<false>);

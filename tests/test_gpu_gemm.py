@@ -243,3 +243,50 @@ def test_gemm_can_be_captured_in_a_graph_and_replayed(K):
         g.replay()
         torch.cuda.synchronize()
         assert torch.equal(out, want)
+
+
+@pytest.mark.parametrize("K", [256, 416])      # the copy-based and the register-staged kernel
+def test_gemm_with_weights_quantized_in_16x16_tiles(K):
+    """FPROP and DGRAD with a weight matrix quantized once in 16x16 tiles (Section 4.1): the
+    row packing multiplies activations, the packing for W^T multiplies gradients, and the
+    product only has to be told that the operand's scales come one line per 16 rows."""
+    T, N = 200, 320
+    w = wl.make("c2", N, K)
+    wb, wd = wl.bf16_bits(w), w.cuda()
+    aw = B.nvfp4_46_tensor_scale(wd)
+    a_w = float(aw.item())
+    qw = B.nvfp4_46_quantize(wd, aw, layout=B.BOTH, block2d=1)
+    c_ref, s_ref, f_ref, _ = ref.quantize_2d(wb, a_w)
+    cc_ref, sc_ref, _ = ref.repack_2d_columnwise(c_ref, s_ref, f_ref)
+    assert np.array_equal(qw["codes_row"].cpu().numpy(), c_ref)
+    assert np.array_equal(qw["codes_col"].cpu().numpy(), cc_ref)
+
+    def check(A, codes_w, scales_w, ref_w, flags_gpu, what, **tiles):
+        got = B.nvfp4_46_gemm(_dev(A[0]), _dev(A[1]), _alpha(A[2]), codes_w, scales_w, aw,
+                              out_dtype=B.OUT_F32, flags=flags_gpu).double().cpu().numpy()
+        c, c_abs = ref.gemm(A[0], A[1], A[2], ref_w[0], ref_w[1], a_w, want_abs=True, **tiles)
+        Kc = A[0].shape[1] * 2
+        assert (np.abs(got - c) <= _tolerance(c, c_abs, Kc, B.OUT_F32)).all(), what
+        return got
+
+    x = _operand("c3", T, K)
+    y = check(x, qw["codes_row"], qw["scales_row"], (c_ref, s_ref), B.GEMM_B_TILE_SCALES, "FPROP",
+              tiles_b=True)
+    assert y.shape == (T, N)
+    dy = _operand("c5", T, N, rounding=ref.SR, sr_seed=wl.C5_SR_SEED)
+    dx = check(dy, qw["codes_col"], qw["scales_col"], (cc_ref, sc_ref), B.GEMM_B_TILE_SCALES,
+               "DGRAD", tiles_b=True)
+    assert dx.shape == (T, K)
+    # the tile-scaled operand on the A side
+    got = B.nvfp4_46_gemm(qw["codes_row"], qw["scales_row"], aw, _dev(x[0]), _dev(x[1]),
+                          _alpha(x[2]), out_dtype=B.OUT_F32, flags=B.GEMM_A_TILE_SCALES)
+    c, c_abs = ref.gemm(c_ref, s_ref, a_w, x[0], x[1], x[2], want_abs=True, tiles_a=True)
+    assert (np.abs(got.double().cpu().numpy() - c) <= _tolerance(c, c_abs, K, B.OUT_F32)).all()
+
+
+def test_gemm_flag_validation():
+    A = _operand("c1", 40, 64)
+    args = [_dev(A[0]), _dev(A[1]), _alpha(A[2]), _dev(A[0]), _dev(A[1]), _alpha(A[2])]
+    out = torch.empty((40, 40), dtype=torch.float32, device="cuda")
+    assert B.gemm_raw(*args, 40, 40, 64, B.OUT_F32, out, flags=4) == 4
+    assert B.gemm_raw(*args, 40, 40, 64, B.OUT_F32, out, flags=B.GEMM_A_TILE_SCALES) == 2   # 40 % 16

@@ -105,3 +105,24 @@ def test_quantized_product_approximates_the_bf16_product():
         errs[sel] = float(np.sqrt(((got - exact) ** 2).mean()) / np.sqrt((exact ** 2).mean()))
     assert errs[ref.SEL_46_MSE] < 0.2 and errs[ref.SEL_FORCE6] < 0.2
     assert errs[ref.SEL_46_MSE] < errs[ref.SEL_FORCE6]
+
+
+def test_gemm_with_tile_scales_equals_gemm_with_the_scales_repeated_per_row():
+    """An operand quantized with 16x16 tiles carries one scale line per 16 rows; using it is
+    the same as repeating every line sixteen times."""
+    xw = wl.bf16_bits(wl.make("c2", 64, 128))
+    aw = ref.tensor_scale(xw)
+    cw, sw, _, _ = ref.quantize_2d(xw, aw)
+    _, ax, cx, sx = _quantized("c3", 40, 128)
+    got = ref.gemm(cx, sx, ax, cw, sw, aw, tiles_b=True)
+    want = ref.gemm(cx, sx, ax, cw, np.repeat(sw, 16, axis=0), aw)
+    assert np.array_equal(got, want)
+    assert np.array_equal(ref.gemm(cw, sw, aw, cx, sx, ax, tiles_a=True), want.T)
+    # the transposed packing multiplies from the other side: W^T [128][64] against a [24][64] operand
+    cc, sc, _ = ref.repack_2d_columnwise(cw, sw, np.zeros_like(sw))
+    _, ag, cg, sg = _quantized("c1", 24, 64)
+    got_t = ref.gemm(cg, sg, ag, cc, sc, aw, tiles_b=True)
+    w_deq = (ref.dequantize_2d(cw, sw, 1.0, 64, 128).astype(np.uint32) << 16).view(np.float32)
+    g_val = _values(cg, sg)
+    want_t = np.float64(np.float32(ag)) * np.float64(np.float32(aw)) * (g_val @ w_deq.astype(np.float64))
+    assert np.allclose(got_t, want_t, rtol=0, atol=1e-12 * np.abs(want_t).max())
