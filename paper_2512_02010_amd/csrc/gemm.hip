@@ -298,7 +298,7 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm(
 // Only for K a multiple of 128 (whole chunks) and K <= 2^24 (32-bit lane offsets).
 constexpr uint32_t kDmaStage = 2 * 128 * 64 + 2 * 128 * 8;   // 18432 bytes per wave and stage
 constexpr uint32_t kDmaWave = 2 * kDmaStage;
-[[maybe_unused]] constexpr size_t kGemmDmaLdsBytes = 4 * kDmaWave;   // 147456
+constexpr size_t kGemmDmaLdsBytes = 4 * kDmaWave;   // 147456
 
 // M0 = LDS byte address of lane 0's piece; %1 = the lane's 32-bit byte offset (vector
 // register), %2 = the 64-bit base address (scalar register pair).
@@ -509,42 +509,34 @@ extern "C" int nvfp4_46_gemm(const void *codes_a, const void *scales_a, const fl
   if (tiles_m * tiles_n > (int64_t)1 << 30) return NVFP4_ERR_SHAPE;
   const dim3 grid((uint32_t)(tiles_m * tiles_n)), block(kGemmThreads);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  auto go = [&](auto kernel) {
-    // more LDS than the 64 KiB a kernel gets without asking
+  // Both kernels need more LDS than the 64 KiB a kernel gets without asking.
+  bool attr_ok = true;
+  auto go = [&](auto kernel, size_t lds_bytes) {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)kGemmLdsBytes) != hipSuccess)
+                            (int)lds_bytes) != hipSuccess) {
+      attr_ok = false;
       return;
-    hipLaunchKernelGGL(kernel, grid, block, kGemmLdsBytes, s, static_cast<const uint8_t *>(codes_a),
+    }
+    hipLaunchKernelGGL(kernel, grid, block, lds_bytes, s, static_cast<const uint8_t *>(codes_a),
                        static_cast<const uint8_t *>(scales_a), alpha_a,
                        static_cast<const uint8_t *>(codes_b), static_cast<const uint8_t *>(scales_b),
                        alpha_b, out, M, N, K, (uint32_t)tiles_n, sha, shb);
   };
   const bool kfull = (K % GK) == 0, f32 = out_dtype == NVFP4_OUT_F32;
-#if NVFP4_46_GEMM_DMA
-  if (kfull && K <= ((int64_t)1 << 24)) {
-    auto go_dma = [&](auto kernel) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)kGemmDmaLdsBytes) != hipSuccess)
-        return;
-      hipLaunchKernelGGL(kernel, grid, block, kGemmDmaLdsBytes, s,
-                         static_cast<const uint8_t *>(codes_a), static_cast<const uint8_t *>(scales_a),
-                         alpha_a, static_cast<const uint8_t *>(codes_b),
-                         static_cast<const uint8_t *>(scales_b), alpha_b, out, M, N, K,
-                         (uint32_t)tiles_n, sha, shb);
-    };
-    if (f32) go_dma(k_gemm_dma<true>);
-    else go_dma(k_gemm_dma<false>);
-    return hipGetLastError() == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
-  }
-#endif
-  if (kfull) {
-    if (f32) go(k_gemm<true, true>);
-    else go(k_gemm<true, false>);
+  if (NVFP4_46_GEMM_DMA && kfull && K <= ((int64_t)1 << 24)) {
+    if (f32) go(k_gemm_dma<true>, kGemmDmaLdsBytes);
+    else go(k_gemm_dma<false>, kGemmDmaLdsBytes);
+  } else if (kfull) {
+    if (f32) go(k_gemm<true, true>, kGemmLdsBytes);
+    else go(k_gemm<true, false>, kGemmLdsBytes);
   } else {
-    if (f32) go(k_gemm<false, true>);
-    else go(k_gemm<false, false>);
+    if (f32) go(k_gemm<false, true>, kGemmLdsBytes);
+    else go(k_gemm<false, false>, kGemmLdsBytes);
+  }
+  if (!attr_ok) {
+    (void)hipGetLastError();
+    return NVFP4_ERR_HIP;
   }
   return hipGetLastError() == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
 }

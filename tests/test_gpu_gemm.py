@@ -290,3 +290,30 @@ def test_gemm_flag_validation():
     out = torch.empty((40, 40), dtype=torch.float32, device="cuda")
     assert B.gemm_raw(*args, 40, 40, 64, B.OUT_F32, out, flags=4) == 4
     assert B.gemm_raw(*args, 40, 40, 64, B.OUT_F32, out, flags=B.GEMM_A_TILE_SCALES) == 2   # 40 % 16
+
+
+def test_gemm_seeded_sweep_of_shapes():
+    """Twenty drawn (M, N, K, output type, tile-scale flags) combinations."""
+    rng = np.random.default_rng(4647)
+    for i in range(20):
+        flags = int(rng.integers(0, 4))
+        M = int(rng.integers(1, 38)) * 16 if flags & 1 else int(rng.integers(1, 600))
+        N = int(rng.integers(1, 38)) * 16 if flags & 2 else int(rng.integers(1, 600))
+        K = int(rng.integers(1, 24)) * 32
+        out_dtype = int(rng.integers(0, 2))
+        ops, ref_ops = [], []
+        for rows, tiled, name in ((M, flags & 1, "c3"), (N, flags & 2, "c2")):
+            bits = wl.bf16_bits(wl.make(name, rows, K, seed=7000 + i))
+            a = ref.tensor_scale(bits)
+            if tiled:
+                c, s, _, _ = ref.quantize_2d(bits, a)
+            else:
+                c, s, _ = ref.quantize(bits, a)
+            ref_ops += [c, s, a]
+            ops += [_dev(c), _dev(s), _alpha(a)]
+        _log(f"gemm sweep {i}: M={M} N={N} K={K} out_dtype={out_dtype} flags={flags}")
+        c_ref, c_abs = ref.gemm(*ref_ops, want_abs=True, tiles_a=bool(flags & 1),
+                                tiles_b=bool(flags & 2))
+        got = B.nvfp4_46_gemm(*ops, out_dtype=out_dtype, flags=flags)
+        g = got.double().cpu().numpy() if out_dtype == B.OUT_F32 else _bf16_to_f64(got)
+        assert (np.abs(g - c_ref) <= _tolerance(c_ref, c_abs, K, out_dtype)).all(), i

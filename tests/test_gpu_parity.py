@@ -444,3 +444,34 @@ def test_workload_c4_full_both_layouts():
 
 def test_workload_c5_full_rht_sr():
     check_case(wl.make("c5"), rounding=B.SR, rht=1, tag="c5-full")
+
+
+# ------------------------------------------------------------------ seeded sweep over shapes and options
+
+def _sweep_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < n:
+        layout = int(rng.choice([B.ROWWISE, B.COLWISE, B.BOTH]))
+        rht = int(rng.integers(0, 2)) if layout != B.BOTH else 0
+        rows = int(rng.integers(1, 40)) * 16 if layout != B.ROWWISE else int(rng.integers(1, 400))
+        cols = int(rng.integers(1, 70)) * 16 if layout & B.ROWWISE else int(rng.integers(1, 140)) * 8
+        cases.append(dict(
+            rows=rows, cols=cols, layout=layout, rht=rht,
+            rounding=int(rng.choice([B.RTN, B.SR, B.SR_AFTER_RTN_SELECT])),
+            select=int(rng.choice([B.SEL_46_MSE, B.SEL_FORCE6, B.SEL_FORCE4, B.SEL_46_MAE,
+                                   B.SEL_46_ABSMAX], p=[0.4, 0.1, 0.1, 0.2, 0.2])),
+            name=str(rng.choice(["c1", "c2", "c3", "c5"])),
+            f32=bool(rng.integers(0, 2)), fp8_max=float(rng.choice([256.0, 448.0], p=[0.8, 0.2]))))
+    return cases
+
+
+@pytest.mark.parametrize("chunk", range(6))
+def test_seeded_sweep_of_shapes_and_options(chunk):
+    """Sixty drawn combinations of shape, layout, rounding, rule, transform, input type and
+    Eq. (1) constant, ten per test, each compared element by element."""
+    for i, c in enumerate(_sweep_cases(60, 4646)[10 * chunk:10 * chunk + 10]):
+        x = wl.make(c["name"], c["rows"], c["cols"], seed=9000 + 10 * chunk + i,
+                    dtype=torch.float32 if c["f32"] else torch.bfloat16)
+        check_case(x, layout=c["layout"], rounding=c["rounding"], select=c["select"], rht=c["rht"],
+                   fp8_max=c["fp8_max"], tag=f"sweep-{chunk}-{i}-{c['name']}-f32={c['f32']}")
