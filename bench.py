@@ -305,6 +305,18 @@ def time_other_workloads(iters=30):
         res["c2_variants_main_us"][name] = med(
             lambda i: B.quantize_raw(xs[i % 2], p, alpha, os_[i % 2]["codes_row"],
                                      os_[i % 2]["scales_row"], None, None, None, None, st))
+    # quantization error of each block-scale rule on the same tensor (what Tables 2 and 4 of the
+    # paper measure in perplexity, here as normalised mean squared / mean absolute error)
+    xf = xs[0].double()
+    ref_sq, ref_abs = float((xf ** 2).mean()), float(xf.abs().mean())
+    res["c2_error_by_rule"] = {}
+    for name, sel in (("always 6 (standard NVFP4)", B.SEL_FORCE6), ("always 4", B.SEL_FORCE4),
+                      ("4/6 by squared error", B.SEL_46_MSE), ("4/6 by absolute error", B.SEL_46_MAE),
+                      ("4/6 by largest error", B.SEL_46_ABSMAX)):
+        d = B.nvfp4_46_fake_quant(xs[0], alpha, select=sel).double() - xf
+        res["c2_error_by_rule"][name] = {"nmse": float((d ** 2).mean()) / ref_sq,
+                                         "nmae": float(d.abs().mean()) / ref_abs}
+    del xf, d
     del xs, os_
     # c2 held as FP32 master weights (Fig. 3): 4 B read per element
     xh = wl.make("c2", dtype=torch.float32)
