@@ -352,16 +352,17 @@ void ref_quantize_block(const float v[BLOCK], float alpha, int rounding, int sel
 typedef struct {
   const void *p;
   int f32;
+  int64_t row0; /* the tensor handed in is rows row0.. of a taller one (0: it is the whole) */
 } xin;
 static float x_at(xin x, uint64_t g) {
   return x.f32 ? ((const float *)x.p)[g] : ref_bf16_to_f32(((const uint16_t *)x.p)[g]);
 }
 static xin x_bf16(const uint16_t *p) {
-  xin x = {p, 0};
+  xin x = {p, 0, 0};
   return x;
 }
 static xin x_f32(const float *p) {
-  xin x = {p, 1};
+  xin x = {p, 1, 0};
   return x;
 }
 
@@ -380,7 +381,12 @@ static void fetch_block(xin x, int64_t rows, int64_t cols, int layout, int64_t l
     g[i] = (uint64_t)r * (uint64_t)cols + (uint64_t)c;
     v[i] = x_at(x, g[i]);
   }
-  if (rht) ref_rht16(v, ref_rht_sign_word(rht_seed, (uint64_t)blk));
+  /* the sign vector belongs to the block's position along the blocked axis of the whole
+   * tensor */
+  if (rht)
+    ref_rht16(v, ref_rht_sign_word(rht_seed, (uint64_t)(blk + (layout == REF_ROWWISE
+                                                                   ? 0
+                                                                   : x.row0 / BLOCK))));
 }
 
 static int64_t n_lines(int64_t rows, int64_t cols, int layout) {
@@ -442,8 +448,11 @@ static int quantize_impl(xin x, int64_t rows, int64_t cols, int layout, int roun
       uint64_t g[BLOCK];
       uint8_t q[BLOCK], S, four;
       fetch_block(x, rows, cols, layout, line, blk, rht, rht_seed, v, g);
+      /* the uniform belongs to the element's flat index in the whole tensor */
       for (int i = 0; i < BLOCK; ++i)
-        u[i] = (rounding != REF_RTN) ? ref_sr_uniform(sr_seed, g[i]) : 0.0f;
+        u[i] = (rounding != REF_RTN)
+                   ? ref_sr_uniform(sr_seed, g[i] + (uint64_t)x.row0 * (uint64_t)cols)
+                   : 0.0f;
       ref_quantize_block(v, alpha, rounding, select, u, q, D, &S, &four, E);
       if (codes)
         for (int i = 0; i < BLOCK; i += 2)
@@ -460,6 +469,19 @@ int nvfp4_46_ref_quantize(const uint16_t *x, int64_t rows, int64_t cols, int lay
                           uint8_t *codes, uint8_t *scales, uint8_t *choice, uint16_t *deq) {
   return quantize_impl(x_bf16(x), rows, cols, layout, rounding, select, rht, sr_seed, rht_seed,
                        alpha, codes, scales, choice, deq);
+}
+/* Rows row0 .. row0 + rows - 1 of a taller [.][cols] BF16 tensor, handed in on their own:
+ * the result is that slice of the whole tensor's quantization (random numbers and sign
+ * vectors are keyed by positions in the whole tensor).  row0 must be a multiple of 16.
+ * Lets a test check a tensor of billions of elements a few rows at a time. */
+int nvfp4_46_ref_quantize_rows(const uint16_t *x, int64_t rows, int64_t cols, int64_t row0,
+                               int layout, int rounding, int select, int rht, uint64_t sr_seed,
+                               uint64_t rht_seed, float alpha, uint8_t *codes, uint8_t *scales,
+                               uint8_t *choice, uint16_t *deq) {
+  xin xi = x_bf16(x);
+  xi.row0 = row0;
+  return quantize_impl(xi, rows, cols, layout, rounding, select, rht, sr_seed, rht_seed, alpha,
+                       codes, scales, choice, deq);
 }
 /* The same for an fp32 tensor (FP32 master weights, Fig. 3). */
 int nvfp4_46_ref_quantize_f32(const float *x, int64_t rows, int64_t cols, int layout,

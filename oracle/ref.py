@@ -78,6 +78,9 @@ def lib() -> C.CDLL:
         L.nvfp4_46_ref_quantize_2d_f32.restype = i32
         L.nvfp4_46_ref_quantize_2d_f32.argtypes = [f32p, i64, i64, i32, i32, u64, f32, u8p, u8p,
                                                    u8p, u16p]
+        L.nvfp4_46_ref_quantize_rows.restype = i32
+        L.nvfp4_46_ref_quantize_rows.argtypes = [u16p, i64, i64, i64, i32, i32, i32, i32, u64, u64,
+                                                 f32, u8p, u8p, u8p, u16p]
         L.nvfp4_46_ref_dequantize.restype = i32
         L.nvfp4_46_ref_dequantize.argtypes = [u8p, u8p, f32, i64, i64, i32, u16p]
         L.nvfp4_46_ref_fake_quant.restype = i32
@@ -251,6 +254,24 @@ def quantize(x_bits: np.ndarray, alpha: float, layout: int = ROWWISE, rounding: 
             _p(deq, C.c_uint16))
     assert rc == 0
     return (codes, scales, choice, deq) if want_deq else (codes, scales, choice)
+
+
+def quantize_rows(x_bits: np.ndarray, row0: int, alpha: float, layout: int = ROWWISE,
+                  rounding: int = RTN, select: int = SEL_46_MSE, rht: int = 0, sr_seed: int = 0,
+                  rht_seed: int = 0):
+    """Quantize rows row0.. of a taller BF16 tensor (x_bits holds just those rows): the slice
+    of the whole tensor's (codes, scales, choice, deq)."""
+    assert x_bits.dtype == np.uint16 and row0 % 16 == 0
+    rows, cols = _check_x(x_bits)
+    cs, ss = _out_shapes(rows, cols, layout)
+    codes, scales, choice = np.zeros(cs, np.uint8), np.zeros(ss, np.uint8), np.zeros(ss, np.uint8)
+    deq = np.zeros((rows, cols), np.uint16)
+    rc = lib().nvfp4_46_ref_quantize_rows(_p(x_bits, C.c_uint16), rows, cols, row0, layout,
+                                          rounding, select, rht, sr_seed, rht_seed, alpha,
+                                          _p(codes, C.c_uint8), _p(scales, C.c_uint8),
+                                          _p(choice, C.c_uint8), _p(deq, C.c_uint16))
+    assert rc == 0
+    return codes, scales, choice, deq
 
 
 def dequantize(codes: np.ndarray, scales: np.ndarray, alpha: float, rows: int, cols: int,

@@ -317,3 +317,27 @@ def test_gemm_seeded_sweep_of_shapes():
         got = B.nvfp4_46_gemm(*ops, out_dtype=out_dtype, flags=flags)
         g = got.double().cpu().numpy() if out_dtype == B.OUT_F32 else _bf16_to_f64(got)
         assert (np.abs(g - c_ref) <= _tolerance(c_ref, c_abs, K, out_dtype)).all(), i
+
+
+def test_gemm_operand_larger_than_four_gibibytes():
+    """A [262,192][32,768]: 4.3 GB of codes, so byte offsets into A pass 2^32 (random codes and
+    moderate scale bytes drawn on the GPU); rows from the start, from around the 2^32-byte
+    mark and from the end are recomputed by the oracle."""
+    M, N, K = 262192, 200, 32768
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4651)
+    u8 = dict(dtype=torch.uint8, device="cuda", generator=g)
+    ca = torch.randint(0, 256, (M, K // 2), **u8)
+    sa = torch.randint(0x28, 0x48, (M, K // 16), **u8)
+    cb = torch.randint(0, 256, (N, K // 2), **u8)
+    sb = torch.randint(0x28, 0x48, (N, K // 16), **u8)
+    al = _alpha(0.5)
+    got = B.nvfp4_46_gemm(ca, sa, al, cb, sb, al, out_dtype=B.OUT_F32)
+    torch.cuda.synchronize()
+    mark = 2 ** 32 // (K // 2)                                 # first row past 2^32 bytes
+    rows = np.array([0, 1, 255, 256, mark - 1, mark, mark + 1, M - 129, M - 2, M - 1])
+    idx = torch.from_numpy(rows).cuda()
+    c_ref, c_abs = ref.gemm(ca[idx].cpu().numpy(), sa[idx].cpu().numpy(), 0.5, cb.cpu().numpy(),
+                            sb.cpu().numpy(), 0.5, want_abs=True)
+    gsel = got[idx].double().cpu().numpy()
+    assert (np.abs(gsel - c_ref) <= _tolerance(c_ref, c_abs, K, B.OUT_F32)).all()

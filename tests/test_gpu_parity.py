@@ -475,3 +475,56 @@ def test_seeded_sweep_of_shapes_and_options(chunk):
                     dtype=torch.float32 if c["f32"] else torch.bfloat16)
         check_case(x, layout=c["layout"], rounding=c["rounding"], select=c["select"], rht=c["rht"],
                    fp8_max=c["fp8_max"], tag=f"sweep-{chunk}-{i}-{c['name']}-f32={c['f32']}")
+
+
+# ------------------------------------------------------------------ beyond 2^32 bytes
+
+def test_tensor_larger_than_four_gibibytes():
+    """65,552 x 40,960 BF16 = 2.69 G elements, 5.4 GB: element indices pass 2^31 and byte offsets
+    2^32 inside one call.  The tensor is drawn on the GPU (seeded N(0,1), plus one planted
+    maximum near the end); the oracle computes the tensor scale over all of it and quantizes
+    32-row slices at the start, around the 2^31-byte, 2^32-byte and 2^31-element marks and at
+    the end, each compared with the same slice of the GPU's outputs: rowwise + columnwise in
+    one pass, and rowwise with the Hadamard transform and stochastic rounding (whose random
+    numbers are keyed by the 64-bit element index)."""
+    rows, cols = 65552, 40960
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4650)
+    x = torch.empty((rows, cols), dtype=torch.bfloat16, device="cuda")
+    for r0 in range(0, rows, 8192):                          # drawn in pieces to bound temporaries
+        n = min(8192, rows - r0)
+        x[r0:r0 + n] = torch.randn((n, cols), generator=g, device="cuda", dtype=torch.float32)
+    x[rows - 3, cols - 5] = 9.0
+    marks = [0, (2 ** 30 // cols) // 16 * 16, (2 ** 31 // cols) // 16 * 16 - 16, rows - 32]
+    marks.insert(2, (2 ** 31 // cols) // 16 * 16 // 2 * 2)   # 2^32 bytes = 2^31 elements
+    marks = sorted(set(marks))
+    _log(f"big tensor: slices at rows {marks}")
+
+    alpha = B.nvfp4_46_tensor_scale(x)
+    assert _alpha_bits(alpha.item()) == _alpha_bits(np.float32(9.0) / np.float32(1536.0))
+    a = float(alpha.item())
+    slices = {r0: x[r0:r0 + 32].cpu().view(torch.int16).numpy().view(np.uint16).copy() for r0 in marks}
+
+    out = B.nvfp4_46_quantize(x, alpha, layout=B.BOTH)
+    torch.cuda.synchronize()
+    for r0, xb in slices.items():
+        c, s, f, _ = ref.quantize_rows(xb, r0, a, layout=ref.ROWWISE)
+        assert np.array_equal(_np(out["codes_row"][r0:r0 + 32]), c), r0
+        assert np.array_equal(_np(out["scales_row"][r0:r0 + 32]), s), r0
+        assert np.array_equal(_np(out["choice_row"][r0:r0 + 32]), f), r0
+        c, s, f, _ = ref.quantize_rows(xb, r0, a, layout=ref.COLWISE)
+        assert np.array_equal(_np(out["codes_col"][:, r0 // 2:r0 // 2 + 16]), c), r0
+        assert np.array_equal(_np(out["scales_col"][:, r0 // 16:r0 // 16 + 2]), s), r0
+    del out
+    torch.cuda.empty_cache()
+
+    kw = dict(rounding=B.SR, rht=1, sr_seed=SR_SEED, rht_seed=RHT_SEED)
+    a_t = B.nvfp4_46_tensor_scale(x, rht=1, rht_seed=RHT_SEED)
+    out = B.nvfp4_46_quantize(x, a_t, want_choice=False, **kw)
+    fq = B.nvfp4_46_fake_quant(x, a_t, **kw)
+    torch.cuda.synchronize()
+    for r0, xb in slices.items():
+        c, s, _, d = ref.quantize_rows(xb, r0, float(a_t.item()), **kw)
+        assert np.array_equal(_np(out["codes_row"][r0:r0 + 32]), c), r0
+        assert np.array_equal(_np(out["scales_row"][r0:r0 + 32]), s), r0
+        assert np.array_equal(_bits(fq[r0:r0 + 32]), d), r0

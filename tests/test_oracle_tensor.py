@@ -185,3 +185,23 @@ def test_workload_generators_are_deterministic_and_shaped():
     for kind in wl.ADVERSARIAL_KINDS:
         t = wl.adversarial(kind)
         assert t.shape == (32, 64)
+
+
+@pytest.mark.parametrize("layout", [ref.ROWWISE, ref.COLWISE])
+def test_quantizing_a_slice_of_rows_gives_that_slice_of_the_whole(layout):
+    x = _small("c5", 96, 160)
+    alpha = ref.tensor_scale(x)
+    kw = dict(layout=layout, rounding=ref.SR, rht=1, sr_seed=wl.C5_SR_SEED, rht_seed=wl.C5_RHT_SEED)
+    c, s, f, d = ref.quantize(x, alpha, want_deq=True, **kw)
+    r0, n = 32, 48
+    cs, ss, fs, ds = ref.quantize_rows(np.ascontiguousarray(x[r0:r0 + n]), r0, alpha, **kw)
+    assert np.array_equal(ds, d[r0:r0 + n])
+    if layout == ref.ROWWISE:
+        assert np.array_equal(cs, c[r0:r0 + n]) and np.array_equal(ss, s[r0:r0 + n])
+        assert np.array_equal(fs, f[r0:r0 + n])
+    else:
+        assert np.array_equal(cs, c[:, r0 // 2:(r0 + n) // 2])
+        assert np.array_equal(ss, s[:, r0 // 16:(r0 + n) // 16])
+    # with the offset left out the random numbers differ, so the slice would not match
+    c0, _, _, _ = ref.quantize_rows(np.ascontiguousarray(x[r0:r0 + n]), 0, alpha, **kw)
+    assert not np.array_equal(c0, cs)
