@@ -334,7 +334,44 @@ def time_other_workloads(iters=30):
                                        os_[i % 2]["scales_col"], None, None, st))
     res["c2_fp32_both"] = entry(r * c, 4.0 + 1.125, t_s, t_m,
                                 "8192x8192 FP32 weights, both orientations, RTN 4/6")
-    del xs, os_, xh
+    del xs, os_
+    # one training step of an 8192 -> 8192 linear layer on 8192 tokens as in Fig. 3: the weight
+    # matrix (FP32, 16x16 tiles, both packings), three activations / gradient quantizations in
+    # four orientations, three NVFP4 products; against the three BF16 products of the vendor
+    # library on the unquantized tensors
+    from paper_2512_02010_amd import linear
+    xa = wl.make("c3", 8192, 8192).cuda()
+    wf = xh.cuda()
+    dy = wl.make("c1", 8192, 8192).cuda()
+
+    def layer_step():
+        qw = linear.quantize_weight(wf)
+        linear.fprop(xa, qw)
+        linear.dgrad(dy, qw, sr_seed=wl.C5_SR_SEED)
+        linear.wgrad(dy, xa, sr_seed=wl.C5_SR_SEED, rht_seed=wl.C5_RHT_SEED)
+
+    def wall(fn, n=10):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n * 1e6
+
+    wb = wf.to(torch.bfloat16)
+    t_layer = wall(layer_step)
+    t_bf16 = wall(lambda: (xa @ wb.t(), dy @ wb, dy.t() @ xa))
+    res["linear_layer_step"] = {
+        "what": "8192 tokens x (8192 -> 8192) linear layer, forward + both backward products "
+                "(Fig. 3): 1 weight + 4 activation/gradient quantizations, 3 NVFP4 products",
+        "us": t_layer, "tflops": 3 * 2.0 * 8192 ** 3 / t_layer / 1e6,
+        "bf16_products_only_us": t_bf16,
+        "note": "gfx950 has no NVFP4 matrix instruction (its FP4 MFMA takes E8M0 scales per 32), "
+                "so the NVFP4 products run at the FP16 MFMA rate after exact expansion"}
+    del xa, wf, dy, wb, xh
+    torch.cuda.empty_cache()
     # c3: activation batch, fake-quant round trip in one kernel (2 B read + 2 B written)
     xs = [wl.make("c3").cuda() for _ in range(2)]
     r, c = xs[0].shape

@@ -341,3 +341,36 @@ def test_gemm_operand_larger_than_four_gibibytes():
                             sb.cpu().numpy(), 0.5, want_abs=True)
     gsel = got[idx].double().cpu().numpy()
     assert (np.abs(gsel - c_ref) <= _tolerance(c_ref, c_abs, K, B.OUT_F32)).all()
+
+
+@pytest.mark.parametrize("block2d", [True, False])
+def test_linear_layer_module(block2d):
+    """paper_2512_02010_amd.linear strings the library calls together as Fig. 3 does; each
+    product must approximate the unquantized one to within NVFP4's quantization noise, and
+    FPROP must equal the same calls made by hand."""
+    from paper_2512_02010_amd import linear
+    T, K, N = 256, 512, 384
+    x = wl.make("c3", T, K).cuda()
+    w = wl.make("c2", N, K, dtype=torch.float32).cuda()
+    dy = wl.make("c1", T, N).cuda()
+    qw = linear.quantize_weight(w, block2d=block2d)
+    y = linear.fprop(x, qw)
+    dx = linear.dgrad(dy, qw, sr_seed=wl.C5_SR_SEED)
+    dw = linear.wgrad(dy, x, sr_seed=wl.C5_SR_SEED, rht_seed=wl.C5_RHT_SEED)
+    assert y.shape == (T, N) and y.dtype == torch.bfloat16
+    assert dx.shape == (T, K) and dw.shape == (N, K) and dw.dtype == torch.float32
+
+    def rel(got, want):
+        return float(((got.double() - want) ** 2).mean().sqrt() / (want ** 2).mean().sqrt())
+
+    xd, wd, gd = x.double(), w.double(), dy.double()
+    errs = {"FPROP": rel(y, xd @ wd.T), "DGRAD": rel(dx, gd @ wd), "WGRAD": rel(dw, gd.T @ xd)}
+    _log(f"  linear layer (block2d={block2d}): relative RMS errors {errs}")
+    assert all(e < 0.2 for e in errs.values()), errs
+
+    ax = B.nvfp4_46_tensor_scale(x)
+    qx = B.nvfp4_46_quantize(x, ax)
+    by_hand = B.nvfp4_46_gemm(qx["codes_row"], qx["scales_row"], ax, qw["codes_row"],
+                              qw["scales_row"], qw["alpha"],
+                              flags=B.GEMM_B_TILE_SCALES if block2d else 0)
+    assert torch.equal(by_hand, y)
