@@ -193,6 +193,9 @@ def cpu_baseline(x_host):
 
 
 MFMA_F16_PEAK_TFLOPS = 2500.0
+# HBM-side bytes of one 8192^3 product from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (profiles/gemm_8192_counters.txt): (221,602.7 KiB x 2.000 + 131,120.0 KiB x 1.000)
+GEMM_8192_TRAFFIC_BYTES = (221602.7 * 2.0 + 131120.0) * 1024.0
 
 
 def time_gemm(w_host, iters=20):
@@ -246,8 +249,10 @@ def time_gemm(w_host, iters=20):
         "roofline": {"bound": "mfma", "kernel": "k_gemm (v_mfma_f32_32x32x16_f16)",
                      "achieved": flops / (t_avg * 1e-3) / 1e12, "peak": MFMA_F16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": flops / (t_avg * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS,
-                     "traffic": None},
-        "operand_bytes": (m + n) * (k // 2 + k // 16),
+                     "traffic": GEMM_8192_TRAFFIC_BYTES if (m, n, k) == (8192, 8192, 8192) else None,
+                     "traffic_note": "from rocprofv3 counters at this shape (profiles/"
+                                     "gemm_8192_counters.txt), not re-measured in this run"},
+        "operand_bytes": (m + n) * (k // 2 + k // 16), "output_bytes": m * n * 2,
         "library_fp16_gemm_on_expanded_operands": {
             "us_median": lib_med * 1e3, "tflops": flops / (lib_avg * 1e-3) / 1e12,
             "note": "torch.matmul on the same operands expanded to FP16 (4x the operand bytes)"},
