@@ -623,11 +623,14 @@ __global__ __launch_bounds__(kThreads) void k_dequant_col(const uint8_t *__restr
 // One scale per 16x16 tile (the weight-matrix variant named in Section 4.1).  Sixteen
 // adjacent lanes own the sixteen rows of a tile (one row block each); the tile's
 // maximum, and the two candidates' errors, are combined across those lanes with XOR
-// shuffles.  Errors are evaluated as defined (no estimate): a row's sixteen terms in the
-// usual fixed order, then the sixteen row sums in the same order (strides 4, 2, 1 within
-// each half, then the two halves), which is the order of the shuffles 4, 2, 1, 8.
+// shuffles.  A tile's error is defined as a row's sixteen terms in the usual fixed order,
+// then the sixteen row sums in the same order (strides 4, 2, 1 within each half, then the
+// two halves), which is the order of the shuffles 4, 2, 1, 8; for the squared-error rule the
+// decision is first tried on cheap row estimates summed the same way and falls back to the
+// defined errors when the two sums are too close to call.
 // Lane -> (tile, row): lanes 0-15 are the rows of one tile, the next sixteen lanes the
 // tile to its right, so four lanes 16 apart read 128 contiguous bytes of one row.
+
 // Sixteen adjacent lanes each hold one row of a 16x16 matrix of 4-bit codes (lo = columns
 // 0-7, hi = columns 8-15, column j in bits 4j..4j+3); on return lane j of the sixteen holds
 // column j packed the same way (row i in bits 4i..4i+3).  The usual recursive transpose:
@@ -667,7 +670,9 @@ __global__ __launch_bounds__(kThreads) void k_block2d(
   const int64_t ncb = cols / 16, n_tiles = (rows / 16) * ncb;
   constexpr int kGroups = kThreads / 16;
   constexpr int kCandRounding = ROUNDING == kSRAfterRtnSelect ? kRTN : ROUNDING;
-  constexpr int kErr = SELECT == kSel46Mae ? kErrMae : SELECT == kSel46AbsMax ? kErrAbsMax : kErrNone;
+  constexpr int kErr = SELECT == kSel46     ? kErrMseEstimate
+                       : SELECT == kSel46Mae ? kErrMae
+                       : SELECT == kSel46AbsMax ? kErrAbsMax : kErrNone;
   for (int64_t T = (int64_t)blockIdx.x * kGroups + grp; T < n_tiles;
        T += (int64_t)gridDim.x * kGroups) {
     const int64_t tr = T / ncb, tc = T - tr * ncb;
@@ -687,39 +692,63 @@ __global__ __launch_bounds__(kThreads) void k_block2d(
 #pragma unroll
     for (int m = 1; m < 16; m <<= 1) b = fmaxf(b, __shfl_xor(b, m, 64));
 
+    // Eq. (2) for the tile: one multiplication, the division only where the scale byte could
+    // depend on the difference (as for 1x16 blocks; the same for all sixteen lanes of the tile)
+    const float q6 = b * sc.rc6, q4 = b * sc.rc4;
+    uint32_t S6 = e4m3_encode(q6), S4 = e4m3_encode(q4);
+    if (scale_byte_at_risk(q6) | scale_byte_at_risk(q4)) {
+      S6 = e4m3_encode(b / sc.c6);
+      S4 = e4m3_encode(b / sc.c4);
+    }
     BlockResult r6{}, r4{};
     float E6 = 0.0f, E4 = 0.0f, enc6 = 0.0f, enc4 = 0.0f;
     if (SELECT != kSelForce4) {
-      r6.scale = e4m3_encode(b / sc.c6);
+      r6.scale = S6;
       const float2 t = tab.e[r6.scale];
       r6.dec = t.x;
       enc6 = t.y;
-      if (!(ROUNDING == kSRAfterRtnSelect && SELECT == kSelForce6)) {
+      if (!(ROUNDING == kSRAfterRtnSelect && SELECT == kSelForce6))
         E6 = candidate<kCandRounding, kErr>(v, u, t.x, t.y, r6.lo, r6.hi);
-        if (SELECT == kSel46) E6 = exact_error(v, r6.lo, r6.hi, t.x);
-      }
     }
     if (SELECT != kSelForce6) {
-      r4.scale = e4m3_encode(b / sc.c4);
+      r4.scale = S4;
       r4.four = 1u;
       const float2 t = tab.e[r4.scale];
       r4.dec = t.x;
       enc4 = t.y;
-      if (!(ROUNDING == kSRAfterRtnSelect && SELECT == kSelForce4)) {
+      if (!(ROUNDING == kSRAfterRtnSelect && SELECT == kSelForce4))
         E4 = candidate<kCandRounding, kErr>(v, u, t.x, t.y, r4.lo, r4.hi);
-        if (SELECT == kSel46) E4 = exact_error(v, r4.lo, r4.hi, t.x);
-      }
     }
-    bool four = SELECT == kSelForce4;
-    if (SELECT == kSel46 || SELECT == kSel46Mae || SELECT == kSel46AbsMax) {
+    // the sixteen row values -> the tile's, in the fixed order; every lane ends with the same sum
+    auto over_tile = [&](float &e6, float &e4) {
       constexpr int order[4] = {4, 2, 1, 8};
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        const float o6 = __shfl_xor(E6, order[s], 64), o4 = __shfl_xor(E4, order[s], 64);
-        E6 = SELECT == kSel46AbsMax ? fmaxf(E6, o6) : E6 + o6;
-        E4 = SELECT == kSel46AbsMax ? fmaxf(E4, o4) : E4 + o4;
+        const float o6 = __shfl_xor(e6, order[s], 64), o4 = __shfl_xor(e4, order[s], 64);
+        e6 = SELECT == kSel46AbsMax ? fmaxf(e6, o6) : e6 + o6;
+        e4 = SELECT == kSel46AbsMax ? fmaxf(e4, o4) : e4 + o4;
       }
+    };
+    bool four = SELECT == kSelForce4;
+    if (SELECT == kSel46Mae || SELECT == kSel46AbsMax) {
+      over_tile(E6, E4);      // evaluated as defined
       four = E4 < E6;
+    } else if (SELECT == kSel46) {
+      // E6, E4 are row estimates (see decide_four): each within 2^-18 (max(dec^2, E') + E') of
+      // the row's defined error, so the tile sums differ from the defined tile errors by less
+      // than 2^-18 (16 dec^2 + 2 E't) plus the rounding of two 16-term trees (< 2^-20 E't).
+      // Outside that margin the estimates order the defined errors; inside it the defined
+      // errors are evaluated.  All sixteen lanes hold the same sums and take the same path.
+      over_tile(E6, E4);
+      const float tol = 0x1p-18f * ((16.0f * r6.dec * r6.dec + 3.0f * E6) +
+                                    (16.0f * r4.dec * r4.dec + 3.0f * E4));
+      const float diff = E4 - E6;
+      four = diff < 0.0f;
+      if (!(fabsf(diff) > tol)) {
+        float e6 = exact_error(v, r6.lo, r6.hi, r6.dec), e4 = exact_error(v, r4.lo, r4.hi, r4.dec);
+        over_tile(e6, e4);
+        four = e4 < e6;
+      }
     }
     BlockResult res = four ? r4 : r6;
     if (ROUNDING == kSRAfterRtnSelect)
