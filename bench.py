@@ -66,6 +66,10 @@ def parse():
                     help="launch nvfp4_46_gemm (8192^3, random codes, scale bytes 0x30..0x47) four "
                          "times and exit (for `rocprofv3 --pmc ... -- python3 bench.py "
                          "--counter-pass-gemm`); prints no benchmark line")
+    ap.add_argument("--layer-pass", action="store_true",
+                    help="run five steps of the Fig. 3 linear layer (8192 tokens, 8192 -> 8192) and "
+                         "exit (for `rocprofv3 --kernel-trace --stats -- python3 bench.py "
+                         "--layer-pass`); prints no benchmark line")
     return ap.parse_args()
 
 
@@ -435,6 +439,19 @@ def main():
                 raise RuntimeError(f"nvfp4_46_gemm failed with status {rc}")
         torch.cuda.synchronize()
         print("counter pass done: 4 products 8192 x 8192 x 8192")
+        return
+    if args.layer_pass:
+        from paper_2512_02010_amd import linear
+        xa = wl.make("c3", 8192, 8192).cuda()
+        wf = wl.make("c2", dtype=torch.float32).cuda()
+        dy = wl.make("c1", 8192, 8192).cuda()
+        for _ in range(5):
+            qw = linear.quantize_weight(wf)
+            linear.fprop(xa, qw)
+            linear.dgrad(dy, qw, sr_seed=wl.C5_SR_SEED)
+            linear.wgrad(dy, xa, sr_seed=wl.C5_SR_SEED, rht_seed=wl.C5_RHT_SEED)
+        torch.cuda.synchronize()
+        print("layer pass done: 5 steps")
         return
     rows, cols = args.rows, args.cols
     n = rows * cols
