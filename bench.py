@@ -381,6 +381,29 @@ def time_other_workloads(iters=30):
                 "so the NVFP4 products run at the FP16 MFMA rate after exact expansion"}
     del xa, wf, dy, wb, xh
     torch.cuda.empty_cache()
+    # few rows of A against the 8192 x 8192 weight matrix (a small batch at inference): bound by
+    # reading the weights once; rotating weight buffers keep them out of the memory-side cache
+    g = torch.Generator(device="cuda")
+    g.manual_seed(2)
+    u8 = dict(dtype=torch.uint8, device="cuda", generator=g)
+    ws = [(torch.randint(0, 256, (8192, 4096), **u8), torch.randint(0x30, 0x48, (8192, 512), **u8))
+          for _ in range(8)]
+    w16 = [torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16) for _ in range(3)]
+    one = torch.ones(1, dtype=torch.float32, device="cuda")
+    res["small_batch_products"] = {}
+    for m in (1, 16, 64, 128):
+        ca, sa = torch.randint(0, 256, (m, 4096), **u8), torch.randint(0x30, 0x48, (m, 512), **u8)
+        a16 = torch.randn(m, 8192, device="cuda", dtype=torch.bfloat16)
+        o = torch.empty((m, 8192), dtype=torch.bfloat16, device="cuda")
+        t_n = med(lambda i: B.gemm_raw(ca, sa, one, ws[i % 8][0], ws[i % 8][1], one, m, 8192, 8192,
+                                       B.OUT_BF16, o, st))
+        t_l = med(lambda i: torch.matmul(a16, w16[i % 3].t(), out=o))
+        wbytes = 8192 * (4096 + 512)
+        res["small_batch_products"][f"M={m}"] = {
+            "nvfp4_us": t_n, "weight_gb_s": wbytes / t_n / 1e3,
+            "frac_of_8tbs": wbytes / t_n / 1e3 / HBM_PEAK_GBS, "library_bf16_us": t_l}
+    del ws, w16
+    torch.cuda.empty_cache()
     # c3: activation batch, fake-quant round trip in one kernel (2 B read + 2 B written)
     xs = [wl.make("c3").cuda() for _ in range(2)]
     r, c = xs[0].shape

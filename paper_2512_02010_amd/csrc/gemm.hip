@@ -479,6 +479,144 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm_dma(
     }
 }
 
+// ----------------------------------------------------------------------------------------
+// Few rows of A (M <= 128: a small batch of activations against a weight matrix).  The product
+// is then bound by reading B once from HBM -- which is where four-bit operands pay on this
+// chip: 0.5625 bytes per weight instead of 2 -- so the plan changes: no LDS staging, every
+// workgroup owns 32 rows of B (32 columns of C) and all of A, its eight waves split the
+// contraction axis (wave w takes the chunks of 256 indices with chunk % 8 == w), each lane
+// streams 64 contiguous bytes of codes and 8 scale bytes per operand row and chunk straight
+// from global memory into registers, and the eight partial tiles are added through LDS at
+// the end.  What bounds the kernel is how many bytes of B a compute unit keeps in flight
+// (memory latency x bandwidth / 256 CUs is about 45 KB), hence eight waves and loads running
+// two chunks ahead of the arithmetic (one chunk with four tiles of A, for registers):
+// 8 waves x 64 lanes x 64 B x 2 = 64 KB of B per CU.  A is re-read by every workgroup, but
+// it is small and stays in L2.
+// MT = number of 32-row tiles of A (1, 2 or 4).  K must be a multiple of 256.
+constexpr int SK = 256;          // contraction indices per chunk
+// waves per workgroup: eight, or four with four tiles of A (whose registers need the larger
+// per-wave budget of a four-wave workgroup)
+constexpr int skinny_waves(int mt) { return mt <= 2 ? 8 : 4; }
+
+template <int MT, bool OUTF32>
+__global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
+    const uint8_t *__restrict__ codes_a, const uint8_t *__restrict__ scales_a,
+    const float *__restrict__ alpha_a, const uint8_t *__restrict__ codes_b,
+    const uint8_t *__restrict__ scales_b, const float *__restrict__ alpha_b,
+    void *__restrict__ out, int64_t M, int64_t N, int64_t K, uint32_t sha, uint32_t shb) {
+  constexpr int kSkinnyWaves = skinny_waves(MT);
+  __shared__ float part[kSkinnyWaves - 1][MT][16][64];   // partial tiles of the waves but the first
+  const uint32_t t = threadIdx.x, lane = t & 63u;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const uint32_t r = lane & 31u, g = lane >> 5;
+  const int64_t n0 = (int64_t)blockIdx.x * 32;
+  const int64_t row_codes = K / 2, row_scales = K / 16;
+
+  // row pointers (rows past the end re-read the last row; their results are not stored)
+  const int64_t nb = n0 + r < N ? n0 + r : N - 1;
+  const uint8_t *pcb = codes_b + nb * row_codes + 64 * g;
+  const uint8_t *psb = scales_b + (nb >> shb) * row_scales + 8 * g;
+  const uint8_t *pca[MT], *psa[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    const int64_t ma = 32 * i + r < M ? 32 * i + r : M - 1;
+    pca[i] = codes_a + ma * row_codes + 64 * g;
+    psa[i] = scales_a + (ma >> sha) * row_scales + 8 * g;
+  }
+
+  // one chunk of one operand row as the lane holds it: 128 codes and their 8 scales
+  struct Raw {
+    uint4 c[4];
+    uint2 s;
+  };
+  auto fetch = [&](const uint8_t *pc, const uint8_t *ps, int64_t chunk, Raw &x) {
+    const uint4 *c = reinterpret_cast<const uint4 *>(pc + chunk * (SK / 2));
+#pragma unroll
+    for (int q = 0; q < 4; ++q) x.c[q] = c[q];
+    x.s = *reinterpret_cast<const uint2 *>(ps + chunk * (SK / 16));
+  };
+  // the eight codes of matrix step s (0..15) of the chunk, expanded with their block's scale
+  auto expand = [&](const Raw &x, int s) {
+    const uint4 &q = x.c[s >> 2];
+    const uint32_t w = (s & 3) == 0 ? q.x : (s & 3) == 1 ? q.y : (s & 3) == 2 ? q.z : q.w;
+    const uint32_t word = (s >> 1) < 4 ? x.s.x : x.s.y;           // block s / 2 of the lane's eight
+    const uint32_t byte = (word >> (8 * ((s >> 1) & 3))) & 0xffu;
+    return expand8(w, __builtin_bit_cast(_Float16, (unsigned short)(byte << 7)));
+  };
+
+  f32x16 acc[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
+
+  const int64_t nchunks = K / SK;
+  constexpr int NS = MT <= 2 ? 3 : 2;            // register sets: loads run NS - 1 chunks ahead
+  Raw rb[NS], ra[NS][MT];
+  auto fetch_all = [&](int64_t c, Raw &b, Raw (&a)[MT]) {
+    const int64_t cc = c < nchunks ? c : nchunks - 1;               // past the end: a harmless re-read
+    fetch(pcb, psb, cc, b);
+#pragma unroll
+    for (int i = 0; i < MT; ++i) fetch(pca[i], psa[i], cc, a[i]);
+  };
+  auto multiply = [&](const Raw &b, const Raw (&a)[MT]) {
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+      const h8 fb = expand(b, s);
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(expand(a[i], s), fb, acc[i], 0, 0, 0);
+    }
+  };
+  // the scheduling barriers keep the compiler from sinking the loads down to their first use
+  int64_t c = wave;
+#pragma unroll
+  for (int p = 0; p < NS - 1; ++p) fetch_all(c + kSkinnyWaves * p, rb[p], ra[p]);
+  bool more = c < nchunks;
+  while (more) {
+#pragma unroll
+    for (int p = 0; p < NS; ++p) {
+      if (more) {
+        fetch_all(c + kSkinnyWaves * (NS - 1), rb[(p + NS - 1) % NS], ra[(p + NS - 1) % NS]);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(rb[p], ra[p]);
+        __builtin_amdgcn_sched_barrier(0);
+        c += kSkinnyWaves;
+        more = c < nchunks;
+      }
+    }
+  }
+
+  // ---- add the waves' tiles in a fixed order (wave 0 collects), scale, store
+  if (wave > 0) {
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) part[wave - 1][i][v][lane] = acc[i][v];
+  }
+  __syncthreads();
+  if (wave == 0) {
+    const float scale = alpha_a[0] * alpha_b[0];
+    const int64_t col = n0 + r;
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        float sum = acc[i][v];
+#pragma unroll
+        for (int w = 0; w < kSkinnyWaves - 1; ++w) sum += part[w][i][v][lane];
+        const int64_t row = 32 * i + 8 * (v / 4) + 4 * g + (v % 4);
+        if (row < M && col < N) {
+          const float cval = sum * scale;
+          if (OUTF32)
+            static_cast<float *>(out)[row * N + col] = cval;
+          else
+            static_cast<uint16_t *>(out)[row * N + col] = (uint16_t)pack_bf16x2(cval, 0.0f);
+        }
+      }
+  }
+}
+
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace nvfp4_46
@@ -524,6 +662,20 @@ extern "C" int nvfp4_46_gemm(const void *codes_a, const void *scales_a, const fl
                        alpha_b, out, M, N, K, (uint32_t)tiles_n, sha, shb);
   };
   const bool kfull = (K % GK) == 0, f32 = out_dtype == NVFP4_OUT_F32;
+  if (M <= 128 && (K % SK) == 0) {
+    // few rows of A: one workgroup per 32 columns of C, bound by streaming B
+    const dim3 sgrid((uint32_t)((N + 31) / 32));
+    auto sgo = [&](auto kernel) {
+      hipLaunchKernelGGL(kernel, sgrid, dim3(64 * skinny_waves(M <= 64 ? 2 : 4)), 0, s,
+                         static_cast<const uint8_t *>(codes_a), static_cast<const uint8_t *>(scales_a),
+                         alpha_a, static_cast<const uint8_t *>(codes_b),
+                         static_cast<const uint8_t *>(scales_b), alpha_b, out, M, N, K, sha, shb);
+    };
+    if (M <= 32) { if (f32) sgo(k_gemm_skinny<1, true>); else sgo(k_gemm_skinny<1, false>); }
+    else if (M <= 64) { if (f32) sgo(k_gemm_skinny<2, true>); else sgo(k_gemm_skinny<2, false>); }
+    else { if (f32) sgo(k_gemm_skinny<4, true>); else sgo(k_gemm_skinny<4, false>); }
+    return hipGetLastError() == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+  }
   if (NVFP4_46_GEMM_DMA && kfull && K <= ((int64_t)1 << 24)) {
     if (f32) go(k_gemm_dma<true>, kGemmDmaLdsBytes);
     else go(k_gemm_dma<false>, kGemmDmaLdsBytes);
