@@ -482,21 +482,37 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm_dma(
 // ----------------------------------------------------------------------------------------
 // Few rows of A (M <= 128: a small batch of activations against a weight matrix).  The product
 // is then bound by reading B once from HBM -- which is where four-bit operands pay on this
-// chip: 0.5625 bytes per weight instead of 2 -- so the plan changes: no LDS staging, every
-// workgroup owns 32 rows of B (32 columns of C) and all of A, its eight waves split the
-// contraction axis (wave w takes the chunks of 256 indices with chunk % 8 == w), each lane
-// streams 64 contiguous bytes of codes and 8 scale bytes per operand row and chunk straight
-// from global memory into registers, and the eight partial tiles are added through LDS at
-// the end.  What bounds the kernel is how many bytes of B a compute unit keeps in flight
-// (memory latency x bandwidth / 256 CUs is about 45 KB), hence eight waves and loads running
-// two chunks ahead of the arithmetic (one chunk with four tiles of A, for registers):
-// 8 waves x 64 lanes x 64 B x 2 = 64 KB of B per CU.  A is re-read by every workgroup, but
-// it is small and stays in L2.
-// MT = number of 32-row tiles of A (1, 2 or 4).  K must be a multiple of 256.
+// chip: 0.5625 bytes per weight instead of 2 -- so the plan changes: every workgroup owns 32
+// rows of B (32 columns of C) and all of A, and its waves split the contraction axis (wave w
+// takes the chunks of 256 indices with chunk % waves == w); the partial tiles are added
+// through LDS at the end in a fixed order.  A is re-read by every workgroup, but it is small
+// and stays in L2.
+//
+// The matrix instruction wants one operand row per lane, but a load instruction whose 64
+// lanes address 32 different rows is 64 separate 16-byte requests, and the kernel would be
+// bound by their number.  So each wave copies its chunk with asynchronous global -> LDS loads
+// in which eight neighbouring lanes fetch the 128 contiguous bytes of one row, into its own
+// piece of LDS, and then reads it back a row per lane (16-byte unit u of a row sits at
+// position u ^ ((row >> 1) & 7), which spreads 16 rows over 16 bank groups).  With one tile of
+// A there is room for two such pieces per wave and the copy of the chunk after next runs
+// while a chunk is multiplied; otherwise the next chunk's copy overlaps this chunk's
+// arithmetic and the other waves' work.
+// MT = number of 32-row tiles of A (1, 2 or 4).  K must be a multiple of 256 and <= 2^24.
 constexpr int SK = 256;          // contraction indices per chunk
 // waves per workgroup: eight, or four with four tiles of A (whose registers need the larger
 // per-wave budget of a four-wave workgroup)
 constexpr int skinny_waves(int mt) { return mt <= 2 ? 8 : 4; }
+constexpr int skinny_stages(int mt) { return mt == 1 ? 2 : 1; }
+constexpr uint32_t skinny_rows(int mt) { return 32u + 32u * mt; }        // B rows, then A rows
+constexpr uint32_t skinny_scale_rows(int mt) { return (skinny_rows(mt) + 63u) / 64u * 64u; }
+constexpr uint32_t skinny_stage_bytes(int mt) {
+  return skinny_rows(mt) * 128u + skinny_scale_rows(mt) * 16u;
+}
+constexpr size_t skinny_lds_bytes(int mt) {
+  const size_t stages = (size_t)skinny_waves(mt) * skinny_stages(mt) * skinny_stage_bytes(mt);
+  const size_t partials = (size_t)(skinny_waves(mt) - 1) * mt * 16 * 64 * sizeof(float);
+  return stages > partials ? stages : partials;
+}
 
 template <int MT, bool OUTF32>
 __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
@@ -504,36 +520,82 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
     const float *__restrict__ alpha_a, const uint8_t *__restrict__ codes_b,
     const uint8_t *__restrict__ scales_b, const float *__restrict__ alpha_b,
     void *__restrict__ out, int64_t M, int64_t N, int64_t K, uint32_t sha, uint32_t shb) {
-  constexpr int kSkinnyWaves = skinny_waves(MT);
-  __shared__ float part[kSkinnyWaves - 1][MT][16][64];   // partial tiles of the waves but the first
+  constexpr int W = skinny_waves(MT), NST = skinny_stages(MT);
+  constexpr uint32_t ROWS = skinny_rows(MT), STAGE = skinny_stage_bytes(MT);
+  constexpr int NC = ROWS / 8, NS = skinny_scale_rows(MT) / 64;   // copy instructions per chunk
+  extern __shared__ __align__(16) uint8_t lds_raw[];
   const uint32_t t = threadIdx.x, lane = t & 63u;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const uint32_t r = lane & 31u, g = lane >> 5;
   const int64_t n0 = (int64_t)blockIdx.x * 32;
   const int64_t row_codes = K / 2, row_scales = K / 16;
+  const uint8_t *wl = lds_raw + wave * (NST * STAGE);
+  const uint32_t lds_wave = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds_raw +
+                            wave * (NST * STAGE);
 
-  // row pointers (rows past the end re-read the last row; their results are not stored)
-  const int64_t nb = n0 + r < N ? n0 + r : N - 1;
-  const uint8_t *pcb = codes_b + nb * row_codes + 64 * g;
-  const uint8_t *psb = scales_b + (nb >> shb) * row_scales + 8 * g;
-  const uint8_t *pca[MT], *psa[MT];
+  // ---- copy instructions.  Codes: instruction q moves rows 8q .. 8q+7 of the stage, lane l
+  // the 16-byte unit (l & 7) ^ ((row >> 1) & 7) of row 8q + l / 8; rows 0-31 are B's, the rest
+  // A's (rows past the end of an operand re-read its last row).  Scales: one lane per row.
+  auto uniform = [](const uint8_t *p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const uint8_t *>(((uint64_t)hi << 32) | lo);
+  };
+  const int64_t b_base = n0 < N ? n0 : N - 1;
+  const uint8_t *gcb = uniform(codes_b + b_base * row_codes), *gca = uniform(codes_a);
+  uint32_t oc[NC];
 #pragma unroll
-  for (int i = 0; i < MT; ++i) {
-    const int64_t ma = 32 * i + r < M ? 32 * i + r : M - 1;
-    pca[i] = codes_a + ma * row_codes + 64 * g;
-    psa[i] = scales_a + (ma >> sha) * row_scales + 8 * g;
+  for (int q = 0; q < NC; ++q) {
+    const uint32_t row = 8 * q + (lane >> 3), unit = (lane & 7u) ^ ((row >> 1) & 7u);
+    int64_t line;
+    if (q < 4) line = b_base + row < N ? row : N - 1 - b_base;       // relative to b_base
+    else line = (int64_t)(row - 32) < M ? row - 32 : M - 1;
+    oc[q] = (uint32_t)(line * row_codes) + unit * 16;
   }
+  const uint8_t *ps[NS];
+#pragma unroll
+  for (int j = 0; j < NS; ++j) {
+    const uint32_t row = 64 * j + lane;
+    if (row < 32) {
+      const int64_t n = n0 + row < N ? n0 + row : N - 1;
+      ps[j] = scales_b + (n >> shb) * row_scales;
+    } else {
+      const int64_t m = (int64_t)(row - 32) < M ? row - 32 : M - 1;
+      ps[j] = scales_a + (m >> sha) * row_scales;
+    }
+  }
+  auto copy_chunk = [&](int64_t c, uint32_t stage) {
+    const int64_t cc = c < K / SK ? c : K / SK - 1;                  // past the end: a harmless re-read
+    const uint32_t lds = lds_wave + stage * STAGE;
+    const uint8_t *pb = gcb + cc * (SK / 2), *pa = gca + cc * (SK / 2);
+#pragma unroll
+    for (int q = 0; q < NC; ++q) {
+      if (q < 4) NV_DMA16(lds + q * 1024, 0, oc[q], pb);
+      else NV_DMA16(lds + q * 1024, 0, oc[q], pa);
+    }
+#pragma unroll
+    for (int j = 0; j < NS; ++j) {
+      const uint8_t *src = ps[j] + cc * (SK / 16);
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                   :: "s"(lds + ROWS * 128 + j * 1024), "v"(src) : "memory", "m0");
+    }
+  };
+  constexpr int kCopies = NC + NS;
 
   // one chunk of one operand row as the lane holds it: 128 codes and their 8 scales
   struct Raw {
     uint4 c[4];
     uint2 s;
   };
-  auto fetch = [&](const uint8_t *pc, const uint8_t *ps, int64_t chunk, Raw &x) {
-    const uint4 *c = reinterpret_cast<const uint4 *>(pc + chunk * (SK / 2));
+  const uint32_t swz = (r >> 1) & 7u;
+  auto read_tile = [&](uint32_t stage, int u, Raw &x) {             // u = 0: B, 1..MT: tiles of A
+    const uint8_t *st = wl + stage * STAGE;
+    const uint32_t row = 32 * u + r;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) x.c[q] = c[q];
-    x.s = *reinterpret_cast<const uint2 *>(ps + chunk * (SK / 16));
+    for (int q = 0; q < 4; ++q)
+      x.c[q] = *reinterpret_cast<const uint4 *>(st + row * 128 + (((4 * g + q) ^ swz) * 16));
+    x.s = *reinterpret_cast<const uint2 *>(st + ROWS * 128 + row * 16 + 8 * g);
   };
   // the eight codes of matrix step s (0..15) of the chunk, expanded with their block's scale
   auto expand = [&](const Raw &x, int s) {
@@ -550,44 +612,40 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
 
+  // The wave's chunks are wave, wave + W, ...  Copies are counted by hand (the kernel issues no
+  // other vector-memory loads in the loop): before a stage is read, all but the copies
+  // issued after it must have landed; before a stage is overwritten, its reads must be back.
   const int64_t nchunks = K / SK;
-  constexpr int NS = MT <= 2 ? 3 : 2;            // register sets: loads run NS - 1 chunks ahead
-  Raw rb[NS], ra[NS][MT];
-  auto fetch_all = [&](int64_t c, Raw &b, Raw (&a)[MT]) {
-    const int64_t cc = c < nchunks ? c : nchunks - 1;               // past the end: a harmless re-read
-    fetch(pcb, psb, cc, b);
-#pragma unroll
-    for (int i = 0; i < MT; ++i) fetch(pca[i], psa[i], cc, a[i]);
-  };
-  auto multiply = [&](const Raw &b, const Raw (&a)[MT]) {
-#pragma unroll
-    for (int s = 0; s < 16; ++s) {
-      const h8 fb = expand(b, s);
-#pragma unroll
-      for (int i = 0; i < MT; ++i)
-        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(expand(a[i], s), fb, acc[i], 0, 0, 0);
-    }
-  };
-  // the scheduling barriers keep the compiler from sinking the loads down to their first use
   int64_t c = wave;
 #pragma unroll
-  for (int p = 0; p < NS - 1; ++p) fetch_all(c + kSkinnyWaves * p, rb[p], ra[p]);
-  bool more = c < nchunks;
-  while (more) {
+  for (int p = 0; p < NST; ++p) copy_chunk(c + W * p, p);
+  uint32_t stage = 0;
+  while (c < nchunks) {
+    if (NST == 2) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(kCopies) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    Raw rb, ra[MT];
+    read_tile(stage, 0, rb);
 #pragma unroll
-    for (int p = 0; p < NS; ++p) {
-      if (more) {
-        fetch_all(c + kSkinnyWaves * (NS - 1), rb[(p + NS - 1) % NS], ra[(p + NS - 1) % NS]);
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(rb[p], ra[p]);
-        __builtin_amdgcn_sched_barrier(0);
-        c += kSkinnyWaves;
-        more = c < nchunks;
-      }
+    for (int i = 0; i < MT; ++i) read_tile(stage, 1 + i, ra[i]);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    copy_chunk(c + W * NST, stage);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+      const h8 fb = expand(rb, s);
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(expand(ra[i], s), fb, acc[i], 0, 0, 0);
     }
+    __builtin_amdgcn_sched_barrier(0);
+    c += W;
+    if (NST == 2) stage ^= 1u;
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // nothing may still be writing LDS
+  __syncthreads();                                       // ... of any wave: the stages are reused
 
   // ---- add the waves' tiles in a fixed order (wave 0 collects), scale, store
+  float (*part)[MT][16][64] = reinterpret_cast<float (*)[MT][16][64]>(lds_raw);
   if (wave > 0) {
 #pragma unroll
     for (int i = 0; i < MT; ++i)
@@ -604,7 +662,7 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
       for (int v = 0; v < 16; ++v) {
         float sum = acc[i][v];
 #pragma unroll
-        for (int w = 0; w < kSkinnyWaves - 1; ++w) sum += part[w][i][v][lane];
+        for (int w = 0; w < W - 1; ++w) sum += part[w][i][v][lane];
         const int64_t row = 32 * i + 8 * (v / 4) + 4 * g + (v % 4);
         if (row < M && col < N) {
           const float cval = sum * scale;
@@ -662,18 +720,29 @@ extern "C" int nvfp4_46_gemm(const void *codes_a, const void *scales_a, const fl
                        alpha_b, out, M, N, K, (uint32_t)tiles_n, sha, shb);
   };
   const bool kfull = (K % GK) == 0, f32 = out_dtype == NVFP4_OUT_F32;
-  if (M <= 128 && (K % SK) == 0) {
+  if (M <= 128 && (K % SK) == 0 && K <= ((int64_t)1 << 24)) {
     // few rows of A: one workgroup per 32 columns of C, bound by streaming B
     const dim3 sgrid((uint32_t)((N + 31) / 32));
-    auto sgo = [&](auto kernel) {
-      hipLaunchKernelGGL(kernel, sgrid, dim3(64 * skinny_waves(M <= 64 ? 2 : 4)), 0, s,
+    bool ok = true;
+    auto sgo = [&](auto kernel, int mt) {
+      const size_t lds = skinny_lds_bytes(mt);
+      if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+        ok = false;
+        return;
+      }
+      hipLaunchKernelGGL(kernel, sgrid, dim3(64 * skinny_waves(mt)), lds, s,
                          static_cast<const uint8_t *>(codes_a), static_cast<const uint8_t *>(scales_a),
                          alpha_a, static_cast<const uint8_t *>(codes_b),
                          static_cast<const uint8_t *>(scales_b), alpha_b, out, M, N, K, sha, shb);
     };
-    if (M <= 32) { if (f32) sgo(k_gemm_skinny<1, true>); else sgo(k_gemm_skinny<1, false>); }
-    else if (M <= 64) { if (f32) sgo(k_gemm_skinny<2, true>); else sgo(k_gemm_skinny<2, false>); }
-    else { if (f32) sgo(k_gemm_skinny<4, true>); else sgo(k_gemm_skinny<4, false>); }
+    if (M <= 32) { if (f32) sgo(k_gemm_skinny<1, true>, 1); else sgo(k_gemm_skinny<1, false>, 1); }
+    else if (M <= 64) { if (f32) sgo(k_gemm_skinny<2, true>, 2); else sgo(k_gemm_skinny<2, false>, 2); }
+    else { if (f32) sgo(k_gemm_skinny<4, true>, 4); else sgo(k_gemm_skinny<4, false>, 4); }
+    if (!ok) {
+      (void)hipGetLastError();
+      return NVFP4_ERR_HIP;
+    }
     return hipGetLastError() == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
   }
   if (NVFP4_46_GEMM_DMA && kfull && K <= ((int64_t)1 << 24)) {
