@@ -583,10 +583,11 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
   };
   constexpr int kCopies = NC + NS;
 
-  // one chunk of one operand row as the lane holds it: 128 codes and their 8 scales
+  // one chunk of one operand row as the lane holds it: 128 codes and their 8 scales, the
+  // scales already as FP16 bit patterns (byte << 7), two per word
   struct Raw {
     uint4 c[4];
-    uint2 s;
+    uint32_t s[4];
   };
   const uint32_t swz = (r >> 1) & 7u;
   auto read_tile = [&](uint32_t stage, int u, Raw &x) {             // u = 0: B, 1..MT: tiles of A
@@ -595,15 +596,18 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
 #pragma unroll
     for (int q = 0; q < 4; ++q)
       x.c[q] = *reinterpret_cast<const uint4 *>(st + row * 128 + (((4 * g + q) ^ swz) * 16));
-    x.s = *reinterpret_cast<const uint2 *>(st + ROWS * 128 + row * 16 + 8 * g);
+    const uint2 sc = *reinterpret_cast<const uint2 *>(st + ROWS * 128 + row * 16 + 8 * g);
+    x.s[0] = __builtin_amdgcn_perm(0u, sc.x, 0x0c010c00u) << 7;
+    x.s[1] = __builtin_amdgcn_perm(0u, sc.x, 0x0c030c02u) << 7;
+    x.s[2] = __builtin_amdgcn_perm(0u, sc.y, 0x0c010c00u) << 7;
+    x.s[3] = __builtin_amdgcn_perm(0u, sc.y, 0x0c030c02u) << 7;
   };
   // the eight codes of matrix step s (0..15) of the chunk, expanded with their block's scale
   auto expand = [&](const Raw &x, int s) {
     const uint4 &q = x.c[s >> 2];
     const uint32_t w = (s & 3) == 0 ? q.x : (s & 3) == 1 ? q.y : (s & 3) == 2 ? q.z : q.w;
-    const uint32_t word = (s >> 1) < 4 ? x.s.x : x.s.y;           // block s / 2 of the lane's eight
-    const uint32_t byte = (word >> (8 * ((s >> 1) & 3))) & 0xffu;
-    return expand8(w, __builtin_bit_cast(_Float16, (unsigned short)(byte << 7)));
+    const h2 pair = __builtin_bit_cast(h2, x.s[s >> 2]);          // blocks 2 (s / 4) and + 1
+    return expand8(w, (s & 2) ? pair.y : pair.x);                  // block s / 2 of the lane's eight
   };
 
   f32x16 acc[MT];
