@@ -62,10 +62,11 @@ def parse():
                     help="launch a calibration copy and each kernel of the step a few times and "
                          "exit (for `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE -- python3 bench.py "
                          "--counter-pass`); prints no benchmark line")
-    ap.add_argument("--counter-pass-gemm", action="store_true",
-                    help="launch nvfp4_46_gemm (8192^3, random codes, scale bytes 0x30..0x47) four "
-                         "times and exit (for `rocprofv3 --pmc ... -- python3 bench.py "
-                         "--counter-pass-gemm`); prints no benchmark line")
+    ap.add_argument("--counter-pass-gemm", nargs="?", const=8192, type=int, default=None, metavar="M",
+                    help="launch nvfp4_46_gemm (M x 8192 x 8192, M = 8192 unless given; random "
+                         "codes, scale bytes 0x30..0x47; eight rotating weight operands) sixteen "
+                         "times (four when M = 8192) and exit (for `rocprofv3 --pmc ... -- python3 "
+                         "bench.py --counter-pass-gemm [M]`); prints no benchmark line")
     ap.add_argument("--layer-pass", action="store_true",
                     help="run five steps of the Fig. 3 linear layer (8192 tokens, 8192 -> 8192) and "
                          "exit (for `rocprofv3 --kernel-trace --stats -- python3 bench.py "
@@ -449,19 +450,25 @@ def main():
     if args.counter_pass_gemm:
         g = torch.Generator(device="cuda")
         g.manual_seed(1)
-        m = 8192
+        m, nk = args.counter_pass_gemm, 8192
         u8 = dict(dtype=torch.uint8, device="cuda", generator=g)
-        ops = []
-        for _ in range(2):
-            ops += [torch.randint(0, 256, (m, m // 2), **u8), torch.randint(0x30, 0x48, (m, m // 16), **u8),
-                    torch.ones(1, dtype=torch.float32, device="cuda")]
-        out = torch.empty((m, m), dtype=torch.bfloat16, device="cuda")
-        for _ in range(4):
-            rc = B.gemm_raw(*ops, m, m, m, B.OUT_BF16, out, torch.cuda.current_stream())
+
+        def operand(rows):
+            return [torch.randint(0, 256, (rows, nk // 2), **u8),
+                    torch.randint(0x30, 0x48, (rows, nk // 16), **u8)]
+
+        one = torch.ones(1, dtype=torch.float32, device="cuda")
+        a = operand(m)
+        ws = [operand(nk) for _ in range(1 if m == nk else 8)]
+        out = torch.empty((m, nk), dtype=torch.bfloat16, device="cuda")
+        launches = 4 if m == nk else 16
+        for i in range(launches):
+            w = ws[i % len(ws)]
+            rc = B.gemm_raw(*a, one, *w, one, m, nk, nk, B.OUT_BF16, out, torch.cuda.current_stream())
             if rc:
                 raise RuntimeError(f"nvfp4_46_gemm failed with status {rc}")
         torch.cuda.synchronize()
-        print("counter pass done: 4 products 8192 x 8192 x 8192")
+        print(f"counter pass done: {launches} products {m} x {nk} x {nk}")
         return
     if args.layer_pass:
         from paper_2512_02010_amd import linear
