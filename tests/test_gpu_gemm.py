@@ -67,7 +67,7 @@ def check_gemm(A, Bm, out_dtype, tag):
 
 
 SHAPES = [(32, 32, 32), (1, 1, 64), (100, 70, 160), (256, 256, 128), (257, 255, 384),
-          (300, 520, 1056), (512, 768, 2048),
+          (300, 520, 1056), (512, 768, 2048), (200, 300, 256),
           # few rows of A and K a multiple of 256: the kernel that streams B
           (1, 40, 256), (16, 32, 512), (33, 100, 1024), (64, 1000, 2304), (100, 96, 768),
           (128, 257, 512), (129, 64, 512)]
