@@ -251,7 +251,7 @@ def time_gemm(w_host, iters=20):
         "what": f"{m}x{n}x{k}: c3-like activations x c2 weights, both 4/6-quantized rowwise, "
                 "BF16 output",
         "us_avg": t_avg * 1e3, "us_median": t_med * 1e3,
-        "roofline": {"bound": "mfma", "kernel": "k_gemm (v_mfma_f32_32x32x16_f16)",
+        "roofline": {"bound": "mfma", "kernel": "k_gemm_dma (v_mfma_f32_32x32x16_f16)",
                      "achieved": flops / (t_avg * 1e-3) / 1e12, "peak": MFMA_F16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": flops / (t_avg * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS,
                      "traffic": GEMM_8192_TRAFFIC_BYTES if (m, n, k) == (8192, 8192, 8192) else None,
