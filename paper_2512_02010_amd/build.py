@@ -34,14 +34,31 @@ def hipcc() -> str:
 
 
 def build(out: Path | None = None, defines: dict | None = None, extra: list | None = None) -> Path:
+    """Compile every source to an object (side by side) and link the shared library."""
+    from concurrent.futures import ThreadPoolExecutor
     out = Path(out) if out else SO
     d = dict(DEFAULT_DEFINES)
     d.update(defines or {})
-    tmp = out.with_suffix(f".tmp{os.getpid()}.so")
-    cmd = [hipcc(), *HIPCC_FLAGS, *[f"-D{k}={v}" for k, v in d.items()], *(extra or []),
-           f"-I{ROOT / 'include'}", f"-I{PKG / 'csrc'}", *map(str, SRCS), "-o", str(tmp)]
-    subprocess.run(cmd, check=True)
-    os.replace(tmp, out)
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    common = [*flags, *[f"-D{k}={v}" for k, v in d.items()], *(extra or []),
+              f"-I{ROOT / 'include'}", f"-I{PKG / 'csrc'}"]
+    objdir = PKG / "_build" / f"{out.stem}.{os.getpid()}"
+    objdir.mkdir(parents=True, exist_ok=True)
+
+    def compile_one(src: Path) -> Path:
+        obj = objdir / (src.stem + ".o")
+        subprocess.run([hipcc(), *common, "-c", str(src), "-o", str(obj)], check=True)
+        return obj
+
+    try:
+        with ThreadPoolExecutor(len(SRCS)) as pool:
+            objs = list(pool.map(compile_one, SRCS))
+        tmp = out.with_suffix(f".tmp{os.getpid()}.so")
+        subprocess.run([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *map(str, objs),
+                        "-o", str(tmp)], check=True)
+        os.replace(tmp, out)
+    finally:
+        shutil.rmtree(objdir, ignore_errors=True)
     return out
 
 
