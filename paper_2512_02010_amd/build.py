@@ -8,7 +8,16 @@ from pathlib import Path
 
 PKG = Path(__file__).resolve().parent
 ROOT = PKG.parent
-SRCS = [PKG / "csrc" / "nvfp4_46.hip", PKG / "csrc" / "gemm.hip"]
+# (source, extra defines, object name).  Both sources are compiled in seven parts each, side
+# by side: part 0 holds the entry points, parts 1..6 one group of kernels each (see the
+# sources for the grouping).  The slowest parts come first so that they start first.
+UNITS = [(PKG / "csrc" / "gemm.hip", {"NVFP4_46_GEMM_PART": part}, f"gemm.part{part}")
+         for part in range(1, 5)]
+UNITS += [(PKG / "csrc" / "nvfp4_46.hip", {"NVFP4_46_PART": part}, f"nvfp4_46.part{part}")
+          for part in range(1, 7)]
+UNITS += [(PKG / "csrc" / "gemm.hip", {"NVFP4_46_GEMM_PART": part}, f"gemm.part{part}")
+          for part in (5, 6, 0)]
+UNITS.append((PKG / "csrc" / "nvfp4_46.hip", {"NVFP4_46_PART": 0}, "nvfp4_46.part0"))
 SO = PKG / "libnvfp4_46.so"
 
 # -ffp-contract=off: the method's arithmetic is one rounding per operation.
@@ -16,7 +25,7 @@ SO = PKG / "libnvfp4_46.so"
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wno-unused-function",
+    "-Wall", "-Wno-unused-function", "-Wno-unused-const-variable",
 ]
 
 # Which narrow-format conversions use the gfx950 instructions (see csrc/codec.hpp).  All
@@ -34,25 +43,26 @@ def hipcc() -> str:
 
 
 def build(out: Path | None = None, defines: dict | None = None, extra: list | None = None) -> Path:
-    """Compile every source to an object (side by side) and link the shared library."""
+    """Compile every unit to an object (side by side) and link the shared library."""
     from concurrent.futures import ThreadPoolExecutor
     out = Path(out) if out else SO
     d = dict(DEFAULT_DEFINES)
     d.update(defines or {})
     flags = [f for f in HIPCC_FLAGS if f != "-shared"]
-    common = [*flags, *[f"-D{k}={v}" for k, v in d.items()], *(extra or []),
-              f"-I{ROOT / 'include'}", f"-I{PKG / 'csrc'}"]
+    common = [*flags, *(extra or []), f"-I{ROOT / 'include'}", f"-I{PKG / 'csrc'}"]
     objdir = PKG / "_build" / f"{out.stem}.{os.getpid()}"
     objdir.mkdir(parents=True, exist_ok=True)
 
-    def compile_one(src: Path) -> Path:
-        obj = objdir / (src.stem + ".o")
-        subprocess.run([hipcc(), *common, "-c", str(src), "-o", str(obj)], check=True)
+    def compile_one(unit) -> Path:
+        src, unit_defines, name = unit
+        obj = objdir / (name + ".o")
+        macros = [f"-D{k}={v}" for k, v in {**unit_defines, **d}.items()]
+        subprocess.run([hipcc(), *common, *macros, "-c", str(src), "-o", str(obj)], check=True)
         return obj
 
     try:
-        with ThreadPoolExecutor(len(SRCS)) as pool:
-            objs = list(pool.map(compile_one, SRCS))
+        with ThreadPoolExecutor(min(len(UNITS), os.cpu_count() or 1)) as pool:
+            objs = list(pool.map(compile_one, UNITS))
         tmp = out.with_suffix(f".tmp{os.getpid()}.so")
         subprocess.run([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *map(str, objs),
                         "-o", str(tmp)], check=True)

@@ -302,12 +302,12 @@ constexpr size_t kGemmDmaLdsBytes = 4 * kDmaWave;   // 147456
 
 // M0 = LDS byte address of lane 0's piece; %1 = the lane's 32-bit byte offset (vector
 // register), %2 = the 64-bit base address (scalar register pair).
-#define NV_DMA16(lds_sgpr, imm, voff, gbase)                                                  \
+#define NV_DMA16(lds_sgpr, voff, gbase)                                                       \
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"                          \
-               :: "s"(lds_sgpr), "v"(voff), "s"(gbase) : "memory", "m0")
-#define NV_DMA4(lds_sgpr, imm, voff, gbase)                                                   \
+               :: "s"(lds_sgpr), "v"(voff), "s"(gbase) : "memory")
+#define NV_DMA4(lds_sgpr, voff, gbase)                                                        \
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2"                            \
-               :: "s"(lds_sgpr), "v"(voff), "s"(gbase) : "memory", "m0")
+               :: "s"(lds_sgpr), "v"(voff), "s"(gbase) : "memory")
 
 template <bool OUTF32>
 __global__ __launch_bounds__(kGemmThreads) void k_gemm_dma(
@@ -365,10 +365,10 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm_dma(
   // the 24 copy instructions of a chunk, numbered so that they can be issued one at a time
   auto copy_one = [&](int64_t c, uint32_t stage, int n) {
     const uint32_t lds = lds_wave + stage * kDmaStage;
-    if (n < 8) NV_DMA16(lds + n * 1024, 0, oca[n], gca + c * (GK / 2));
-    else if (n < 16) NV_DMA16(lds + 8192 + (n - 8) * 1024, 0, ocb[n - 8], gcb + c * (GK / 2));
-    else if (n < 20) NV_DMA4(lds + 16384 + (n - 16) * 256, 0, osa[n - 16], gsa + c * (GK / 16));
-    else NV_DMA4(lds + 17408 + (n - 20) * 256, 0, osb[n - 20], gsb + c * (GK / 16));
+    if (n < 8) NV_DMA16(lds + n * 1024, oca[n], gca + c * (GK / 2));
+    else if (n < 16) NV_DMA16(lds + 8192 + (n - 8) * 1024, ocb[n - 8], gcb + c * (GK / 2));
+    else if (n < 20) NV_DMA4(lds + 16384 + (n - 16) * 256, osa[n - 16], gsa + c * (GK / 16));
+    else NV_DMA4(lds + 17408 + (n - 20) * 256, osb[n - 20], gsb + c * (GK / 16));
   };
   auto copy_chunk = [&](int64_t c, uint32_t stage) {
 #pragma unroll
@@ -571,14 +571,14 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
     const uint8_t *pb = gcb + cc * (SK / 2), *pa = gca + cc * (SK / 2);
 #pragma unroll
     for (int q = 0; q < NC; ++q) {
-      if (q < 4) NV_DMA16(lds + q * 1024, 0, oc[q], pb);
-      else NV_DMA16(lds + q * 1024, 0, oc[q], pa);
+      if (q < 4) NV_DMA16(lds + q * 1024, oc[q], pb);
+      else NV_DMA16(lds + q * 1024, oc[q], pa);
     }
 #pragma unroll
     for (int j = 0; j < NS; ++j) {
       const uint8_t *src = ps[j] + cc * (SK / 16);
       asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
-                   :: "s"(lds + ROWS * 128 + j * 1024), "v"(src) : "memory", "m0");
+                   :: "s"(lds + ROWS * 128 + j * 1024), "v"(src) : "memory");
     }
   };
   constexpr int kCopies = NC + NS;
@@ -681,7 +681,98 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
 
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// The kernels compile side by side when this file is built in parts: NVFP4_46_GEMM_PART =
+// 1..4 hold one instantiation of the staged kernel each (by far the slowest to compile),
+// 5 the copy-based kernel, 6 the small-batch kernel, 0 the entry point; without the macro
+// the file is one self-contained translation unit.
+#ifndef NVFP4_46_GEMM_PART
+#define NVFP4_46_GEMM_PART (-1)
+#endif
+#define NVFP4_46_GEMM_HAS(part) (NVFP4_46_GEMM_PART < 0 || NVFP4_46_GEMM_PART == (part))
+
+struct GemmArgs {
+  const uint8_t *codes_a, *scales_a;
+  const float *alpha_a;
+  const uint8_t *codes_b, *scales_b;
+  const float *alpha_b;
+  void *out;
+  int64_t M, N, K;
+  uint32_t sha, shb;     // scale rows are shared by 2^sha rows of A, 2^shb rows of B
+  bool f32;              // C is fp32 instead of BF16
+  hipStream_t stream;
+};
+
+// Every run_* raises the kernel's dynamic LDS limit (all three need more than the 64 KiB a
+// kernel gets without asking), launches, and returns a status of the C ABI.
+template <bool KFULL, bool OUTF32>
+int run_gemm_staged(const GemmArgs &a);
+int run_gemm_dma(const GemmArgs &a);
+int run_gemm_skinny(const GemmArgs &a);
+
+template <typename Kernel, typename... Args>
+static int launch_with_lds(Kernel kernel, dim3 grid, dim3 block, size_t lds_bytes, hipStream_t s,
+                           Args... args) {
+  if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                          hipFuncAttributeMaxDynamicSharedMemorySize,
+                          (int)lds_bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    return NVFP4_ERR_HIP;
+  }
+  hipLaunchKernelGGL(kernel, grid, block, lds_bytes, s, args...);
+  return hipGetLastError() == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+}
+
+static dim3 tile_grid(const GemmArgs &a) {
+  const int64_t tiles_m = (a.M + GT - 1) / GT, tiles_n = (a.N + GT - 1) / GT;
+  return dim3((uint32_t)(tiles_m * tiles_n));
+}
+
+template <bool KFULL, bool OUTF32>
+int run_gemm_staged(const GemmArgs &a) {
+  return launch_with_lds(k_gemm<KFULL, OUTF32>, tile_grid(a), dim3(kGemmThreads), kGemmLdsBytes,
+                         a.stream, a.codes_a, a.scales_a, a.alpha_a, a.codes_b, a.scales_b,
+                         a.alpha_b, a.out, a.M, a.N, a.K, (uint32_t)((a.N + GT - 1) / GT), a.sha,
+                         a.shb);
+}
+#if NVFP4_46_GEMM_PART == 0
+extern template int run_gemm_staged<false, false>(const GemmArgs &);
+extern template int run_gemm_staged<false, true>(const GemmArgs &);
+extern template int run_gemm_staged<true, false>(const GemmArgs &);
+extern template int run_gemm_staged<true, true>(const GemmArgs &);
+#elif NVFP4_46_GEMM_PART >= 1 && NVFP4_46_GEMM_PART <= 4
+template int run_gemm_staged<((NVFP4_46_GEMM_PART - 1) / 2 != 0), ((NVFP4_46_GEMM_PART - 1) % 2 != 0)>(
+    const GemmArgs &);
+#endif
+
+#if NVFP4_46_GEMM_HAS(5)
+int run_gemm_dma(const GemmArgs &a) {
+  const uint32_t tiles_n = (uint32_t)((a.N + GT - 1) / GT);
+  auto go = [&](auto kernel) {
+    return launch_with_lds(kernel, tile_grid(a), dim3(kGemmThreads), kGemmDmaLdsBytes, a.stream,
+                           a.codes_a, a.scales_a, a.alpha_a, a.codes_b, a.scales_b, a.alpha_b,
+                           a.out, a.M, a.N, a.K, tiles_n, a.sha, a.shb);
+  };
+  return a.f32 ? go(k_gemm_dma<true>) : go(k_gemm_dma<false>);
+}
+#endif
+
+#if NVFP4_46_GEMM_HAS(6)
+// Few rows of A: one workgroup per 32 columns of C, bound by streaming B.
+int run_gemm_skinny(const GemmArgs &a) {
+  auto go = [&](auto kernel, int mt) {
+    return launch_with_lds(kernel, dim3((uint32_t)((a.N + 31) / 32)), dim3(64 * skinny_waves(mt)),
+                           skinny_lds_bytes(mt), a.stream, a.codes_a, a.scales_a, a.alpha_a,
+                           a.codes_b, a.scales_b, a.alpha_b, a.out, a.M, a.N, a.K, a.sha, a.shb);
+  };
+  if (a.M <= 32) return a.f32 ? go(k_gemm_skinny<1, true>, 1) : go(k_gemm_skinny<1, false>, 1);
+  if (a.M <= 64) return a.f32 ? go(k_gemm_skinny<2, true>, 2) : go(k_gemm_skinny<2, false>, 2);
+  return a.f32 ? go(k_gemm_skinny<4, true>, 4) : go(k_gemm_skinny<4, false>, 4);
+}
+#endif
+
 }  // namespace nvfp4_46
+
+#if NVFP4_46_GEMM_PART <= 0
 
 using namespace nvfp4_46;
 
@@ -700,68 +791,23 @@ extern "C" int nvfp4_46_gemm(const void *codes_a, const void *scales_a, const fl
   if (((flags & NVFP4_GEMM_A_TILE_SCALES) && (M % 16) != 0) ||
       ((flags & NVFP4_GEMM_B_TILE_SCALES) && (N % 16) != 0))
     return NVFP4_ERR_SHAPE;
-  const uint32_t sha = (flags & NVFP4_GEMM_A_TILE_SCALES) ? 4u : 0u;
-  const uint32_t shb = (flags & NVFP4_GEMM_B_TILE_SCALES) ? 4u : 0u;
   if (!aligned16(codes_a) || !aligned16(scales_a) || !aligned16(codes_b) || !aligned16(scales_b) ||
       !aligned16(out))
     return NVFP4_ERR_ALIGN;
   const int64_t tiles_m = (M + GT - 1) / GT, tiles_n = (N + GT - 1) / GT;
   if (tiles_m * tiles_n > (int64_t)1 << 30) return NVFP4_ERR_SHAPE;
-  const dim3 grid((uint32_t)(tiles_m * tiles_n)), block(kGemmThreads);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  // Both kernels need more LDS than the 64 KiB a kernel gets without asking.
-  bool attr_ok = true;
-  auto go = [&](auto kernel, size_t lds_bytes) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds_bytes) != hipSuccess) {
-      attr_ok = false;
-      return;
-    }
-    hipLaunchKernelGGL(kernel, grid, block, lds_bytes, s, static_cast<const uint8_t *>(codes_a),
-                       static_cast<const uint8_t *>(scales_a), alpha_a,
-                       static_cast<const uint8_t *>(codes_b), static_cast<const uint8_t *>(scales_b),
-                       alpha_b, out, M, N, K, (uint32_t)tiles_n, sha, shb);
-  };
-  const bool kfull = (K % GK) == 0, f32 = out_dtype == NVFP4_OUT_F32;
-  if (M <= 128 && (K % SK) == 0 && K <= ((int64_t)1 << 24)) {
-    // few rows of A: one workgroup per 32 columns of C, bound by streaming B
-    const dim3 sgrid((uint32_t)((N + 31) / 32));
-    bool ok = true;
-    auto sgo = [&](auto kernel, int mt) {
-      const size_t lds = skinny_lds_bytes(mt);
-      if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
-        ok = false;
-        return;
-      }
-      hipLaunchKernelGGL(kernel, sgrid, dim3(64 * skinny_waves(mt)), lds, s,
-                         static_cast<const uint8_t *>(codes_a), static_cast<const uint8_t *>(scales_a),
-                         alpha_a, static_cast<const uint8_t *>(codes_b),
-                         static_cast<const uint8_t *>(scales_b), alpha_b, out, M, N, K, sha, shb);
-    };
-    if (M <= 32) { if (f32) sgo(k_gemm_skinny<1, true>, 1); else sgo(k_gemm_skinny<1, false>, 1); }
-    else if (M <= 64) { if (f32) sgo(k_gemm_skinny<2, true>, 2); else sgo(k_gemm_skinny<2, false>, 2); }
-    else { if (f32) sgo(k_gemm_skinny<4, true>, 4); else sgo(k_gemm_skinny<4, false>, 4); }
-    if (!ok) {
-      (void)hipGetLastError();
-      return NVFP4_ERR_HIP;
-    }
-    return hipGetLastError() == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
-  }
-  if (NVFP4_46_GEMM_DMA && kfull && K <= ((int64_t)1 << 24)) {
-    if (f32) go(k_gemm_dma<true>, kGemmDmaLdsBytes);
-    else go(k_gemm_dma<false>, kGemmDmaLdsBytes);
-  } else if (kfull) {
-    if (f32) go(k_gemm<true, true>, kGemmLdsBytes);
-    else go(k_gemm<true, false>, kGemmLdsBytes);
-  } else {
-    if (f32) go(k_gemm<false, true>, kGemmLdsBytes);
-    else go(k_gemm<false, false>, kGemmLdsBytes);
-  }
-  if (!attr_ok) {
-    (void)hipGetLastError();
-    return NVFP4_ERR_HIP;
-  }
-  return hipGetLastError() == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+  const GemmArgs a{static_cast<const uint8_t *>(codes_a), static_cast<const uint8_t *>(scales_a),
+                   alpha_a, static_cast<const uint8_t *>(codes_b),
+                   static_cast<const uint8_t *>(scales_b), alpha_b, out, M, N, K,
+                   (flags & NVFP4_GEMM_A_TILE_SCALES) ? 4u : 0u,
+                   (flags & NVFP4_GEMM_B_TILE_SCALES) ? 4u : 0u, out_dtype == NVFP4_OUT_F32,
+                   static_cast<hipStream_t>(stream)};
+  const bool offsets_fit = K <= ((int64_t)1 << 24);     // 32-bit lane offsets of the copies
+  if (M <= 128 && (K % SK) == 0 && offsets_fit) return run_gemm_skinny(a);
+  if (NVFP4_46_GEMM_DMA && (K % GK) == 0 && offsets_fit) return run_gemm_dma(a);
+  if ((K % GK) == 0)
+    return a.f32 ? run_gemm_staged<true, true>(a) : run_gemm_staged<true, false>(a);
+  return a.f32 ? run_gemm_staged<false, true>(a) : run_gemm_staged<false, false>(a);
 }
+
+#endif

@@ -20,6 +20,17 @@
 #include "block.hpp"
 #include "nvfp4_46.h"
 
+// The quantizing kernels exist once per (input type, rounding mode, selection rule, ...):
+// several hundred instantiations.  To compile them side by side this file can be built in
+// parts: NVFP4_46_PART = 1..6 holds the kernels of one (input type, rounding mode) pair and
+// nothing else, NVFP4_46_PART = 0 holds everything else (the entry points included) and
+// refers to the six groups as explicit instantiations defined elsewhere.  Without the
+// macro the file is one self-contained translation unit.
+#ifndef NVFP4_46_PART
+#define NVFP4_46_PART (-1)
+#endif
+#define NVFP4_46_MAIN (NVFP4_46_PART <= 0)
+
 namespace nvfp4_46 {
 
 constexpr int kThreads = 256;
@@ -150,6 +161,7 @@ NV_DEV void publish_amax(float m, uint32_t *amax_bits) {
 
 // ------------------------------------------------------------ tensor scale
 
+#if NVFP4_46_MAIN
 __global__ void k_store_u32(uint32_t *p, uint32_t v) { *p = v; }
 
 // Eq. (1): alpha = amax / (6 * fp8_max); an all-zero tensor gets alpha = 1.
@@ -157,6 +169,7 @@ __global__ void k_finish_alpha(float *alpha, float fp8_max) {
   float amax = *alpha;
   *alpha = (amax == 0.0f) ? 1.0f : amax / (6.0f * fp8_max);
 }
+#endif
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 
@@ -316,6 +329,7 @@ __global__ __launch_bounds__(kThreads) void k_flat(
   if (OUT == kOutAmax) publish_amax(amax, amax_bits);
 }
 
+#if NVFP4_46_MAIN
 // One lane per 8 elements: 4 code bytes + the block's scale -> 8 BF16.
 __global__ __launch_bounds__(kThreads) void k_dequant_flat(const uint32_t *__restrict__ codes,
                                                            const uint8_t *__restrict__ scales,
@@ -331,6 +345,7 @@ __global__ __launch_bounds__(kThreads) void k_dequant_flat(const uint32_t *__res
                                           pack_bf16x2(D[4], D[5]), pack_bf16x2(D[6], D[7])));
   }
 }
+#endif
 
 // ------------------------------------------------ columnwise / both (tiled)
 
@@ -696,7 +711,7 @@ __global__ __launch_bounds__(kThreads) void k_block2d(
     // depend on the difference (as for 1x16 blocks; the same for all sixteen lanes of the tile)
     const float q6 = b * sc.rc6, q4 = b * sc.rc4;
     uint32_t S6 = e4m3_encode(q6), S4 = e4m3_encode(q4);
-    if (scale_byte_at_risk(q6) | scale_byte_at_risk(q4)) {
+    if ((int)scale_byte_at_risk(q6) | (int)scale_byte_at_risk(q4)) {
       S6 = e4m3_encode(b / sc.c6);
       S4 = e4m3_encode(b / sc.c4);
     }
@@ -786,6 +801,7 @@ __global__ __launch_bounds__(kThreads) void k_block2d(
   }
 }
 
+#if NVFP4_46_MAIN
 // 2D-block data -> BF16: one lane per 8 codes; the scale is the tile's.
 __global__ __launch_bounds__(kThreads) void k_dequant_2d(const uint32_t *__restrict__ codes,
                                                          const uint8_t *__restrict__ scales,
@@ -857,6 +873,8 @@ __global__ void k_dbg_philox(const uint32_t *ctr, uint32_t k0, uint32_t k1, int6
   }
 }
 
+#endif
+
 // ---------------------------------------------------------------- launchers
 
 static int grid_for(int64_t work_items, int per_cu) {
@@ -892,7 +910,7 @@ struct FlatArgs {
   hipStream_t stream;
 };
 
-template <int ROUNDING, int SELECT, bool RHT, int OUT>
+template <bool XF32, int ROUNDING, int SELECT, bool RHT, int OUT>
 static void launch_flat(const FlatArgs &a) {
   int grid = grid_for(a.nblocks, NVFP4_46_FLAT_WG_PER_CU);
   if (RHT) {
@@ -903,53 +921,30 @@ static void launch_flat(const FlatArgs &a) {
     const int period = (int)(a.nb_per_row / g);
     if (period <= grid / 2) grid -= grid % period;
   }
-  if (a.xf32)
-    hipLaunchKernelGGL((k_flat<true, ROUNDING, SELECT, RHT, OUT>), dim3(grid), dim3(kThreads), 0,
-                       a.stream, a.x, a.alpha, a.codes, a.scales, a.choice, a.out, a.amax,
-                       a.nblocks, a.nb_per_row, a.sr_seed, a.rht_seed);
-  else
-    hipLaunchKernelGGL((k_flat<false, ROUNDING, SELECT, RHT, OUT>), dim3(grid), dim3(kThreads), 0,
-                       a.stream, a.x, a.alpha, a.codes, a.scales, a.choice, a.out, a.amax,
-                       a.nblocks, a.nb_per_row, a.sr_seed, a.rht_seed);
+  hipLaunchKernelGGL((k_flat<XF32, ROUNDING, SELECT, RHT, OUT>), dim3(grid), dim3(kThreads), 0,
+                     a.stream, a.x, a.alpha, a.codes, a.scales, a.choice, a.out, a.amax,
+                     a.nblocks, a.nb_per_row, a.sr_seed, a.rht_seed);
 }
 
-template <int ROUNDING, int SELECT, bool RHT>
-static void launch_flat_out(const FlatArgs &a, int out) {
-  if (out == kOutCodes)
-    launch_flat<ROUNDING, SELECT, RHT, kOutCodes>(a);
-  else
-    launch_flat<ROUNDING, SELECT, RHT, kOutFake>(a);
+template <bool XF32, int ROUNDING, int SELECT>
+static void launch_flat_variant(const FlatArgs &a, bool rht, int out) {
+  if (out == kOutCodes) {
+    if (rht) launch_flat<XF32, ROUNDING, SELECT, true, kOutCodes>(a);
+    else launch_flat<XF32, ROUNDING, SELECT, false, kOutCodes>(a);
+  } else {
+    if (rht) launch_flat<XF32, ROUNDING, SELECT, true, kOutFake>(a);
+    else launch_flat<XF32, ROUNDING, SELECT, false, kOutFake>(a);
+  }
 }
 
-template <int ROUNDING, int SELECT>
-static void launch_flat_rht(const FlatArgs &a, bool rht, int out) {
-  if (rht)
-    launch_flat_out<ROUNDING, SELECT, true>(a, out);
-  else
-    launch_flat_out<ROUNDING, SELECT, false>(a, out);
-}
-
-template <int ROUNDING>
-static void launch_flat_sel(const FlatArgs &a, uint32_t select, bool rht, int out) {
-  if (select == NVFP4_SEL_46_MSE)
-    launch_flat_rht<ROUNDING, kSel46>(a, rht, out);
-  else if (select == NVFP4_SEL_FORCE6)
-    launch_flat_rht<ROUNDING, kSelForce6>(a, rht, out);
-  else if (select == NVFP4_SEL_FORCE4)
-    launch_flat_rht<ROUNDING, kSelForce4>(a, rht, out);
-  else if (select == NVFP4_SEL_46_MAE)
-    launch_flat_rht<ROUNDING, kSel46Mae>(a, rht, out);
-  else
-    launch_flat_rht<ROUNDING, kSel46AbsMax>(a, rht, out);
-}
-
-static void dispatch_flat(const FlatArgs &a, uint32_t rounding, uint32_t select, bool rht, int out) {
-  if (rounding == NVFP4_SR)
-    launch_flat_sel<kSR>(a, select, rht, out);
-  else if (rounding == NVFP4_SR_AFTER_RTN_SELECT)
-    launch_flat_sel<kSRAfterRtnSelect>(a, select, rht, out);
-  else
-    launch_flat_sel<kRTN>(a, select, rht, out);
+// All rowwise kernels of one (input type, rounding mode) pair.
+template <bool XF32, int ROUNDING>
+void run_flat(const FlatArgs &a, uint32_t select, bool rht, int out) {
+  if (select == NVFP4_SEL_46_MSE) launch_flat_variant<XF32, ROUNDING, kSel46>(a, rht, out);
+  else if (select == NVFP4_SEL_FORCE6) launch_flat_variant<XF32, ROUNDING, kSelForce6>(a, rht, out);
+  else if (select == NVFP4_SEL_FORCE4) launch_flat_variant<XF32, ROUNDING, kSelForce4>(a, rht, out);
+  else if (select == NVFP4_SEL_46_MAE) launch_flat_variant<XF32, ROUNDING, kSel46Mae>(a, rht, out);
+  else launch_flat_variant<XF32, ROUNDING, kSel46AbsMax>(a, rht, out);
 }
 
 struct TileArgs {
@@ -969,47 +964,35 @@ static int tile_grid(int64_t rows, int64_t cols) {
   return (int)(8 * ((nt_c + 7) / 8) * nt_r);
 }
 
-template <int ROUNDING, int SELECT, bool RHT, bool WANT_ROW, int OUT>
+template <bool XF32, int ROUNDING, int SELECT, bool RHT, bool WANT_ROW, int OUT>
 static void launch_tile(const TileArgs &a) {
-  const dim3 grid(tile_grid(a.rows, a.cols));
-  if (a.xf32)
-    hipLaunchKernelGGL((k_tile<true, ROUNDING, SELECT, RHT, WANT_ROW, OUT>), grid, dim3(kThreads), 0,
-                       a.stream, a.x, a.alpha, a.codes_row, a.scales_row, a.choice_row, a.codes_col,
-                       a.scales_col, a.choice_col, a.out, a.amax, a.rows, a.cols, a.sr_seed,
-                       a.rht_seed);
-  else
-    hipLaunchKernelGGL((k_tile<false, ROUNDING, SELECT, RHT, WANT_ROW, OUT>), grid, dim3(kThreads),
-                       0, a.stream, a.x, a.alpha, a.codes_row, a.scales_row, a.choice_row,
-                       a.codes_col, a.scales_col, a.choice_col, a.out, a.amax, a.rows, a.cols,
-                       a.sr_seed, a.rht_seed);
+  hipLaunchKernelGGL((k_tile<XF32, ROUNDING, SELECT, RHT, WANT_ROW, OUT>),
+                     dim3(tile_grid(a.rows, a.cols)), dim3(kThreads), 0, a.stream, a.x, a.alpha,
+                     a.codes_row, a.scales_row, a.choice_row, a.codes_col, a.scales_col,
+                     a.choice_col, a.out, a.amax, a.rows, a.cols, a.sr_seed, a.rht_seed);
 }
 
 // variant: 0 = columnwise codes, 1 = columnwise codes + rht, 2 = both orientations,
 //          3 = columnwise fake-quant, 4 = columnwise fake-quant + rht
-template <int ROUNDING, int SELECT>
+template <bool XF32, int ROUNDING, int SELECT>
 static void launch_tile_variant(const TileArgs &a, int variant) {
   switch (variant) {
-    case 0: launch_tile<ROUNDING, SELECT, false, false, kOutCodes>(a); break;
-    case 1: launch_tile<ROUNDING, SELECT, true, false, kOutCodes>(a); break;
-    case 2: launch_tile<ROUNDING, SELECT, false, true, kOutCodes>(a); break;
-    case 3: launch_tile<ROUNDING, SELECT, false, false, kOutFake>(a); break;
-    default: launch_tile<ROUNDING, SELECT, true, false, kOutFake>(a); break;
+    case 0: launch_tile<XF32, ROUNDING, SELECT, false, false, kOutCodes>(a); break;
+    case 1: launch_tile<XF32, ROUNDING, SELECT, true, false, kOutCodes>(a); break;
+    case 2: launch_tile<XF32, ROUNDING, SELECT, false, true, kOutCodes>(a); break;
+    case 3: launch_tile<XF32, ROUNDING, SELECT, false, false, kOutFake>(a); break;
+    default: launch_tile<XF32, ROUNDING, SELECT, true, false, kOutFake>(a); break;
   }
 }
 
-template <int ROUNDING>
-static void launch_tile_sel(const TileArgs &a, uint32_t select, int variant) {
-  if (select == NVFP4_SEL_46_MSE) launch_tile_variant<ROUNDING, kSel46>(a, variant);
-  else if (select == NVFP4_SEL_FORCE6) launch_tile_variant<ROUNDING, kSelForce6>(a, variant);
-  else if (select == NVFP4_SEL_FORCE4) launch_tile_variant<ROUNDING, kSelForce4>(a, variant);
-  else if (select == NVFP4_SEL_46_MAE) launch_tile_variant<ROUNDING, kSel46Mae>(a, variant);
-  else launch_tile_variant<ROUNDING, kSel46AbsMax>(a, variant);
-}
-
-static void dispatch_tile(const TileArgs &a, uint32_t rounding, uint32_t select, int variant) {
-  if (rounding == NVFP4_SR) launch_tile_sel<kSR>(a, select, variant);
-  else if (rounding == NVFP4_SR_AFTER_RTN_SELECT) launch_tile_sel<kSRAfterRtnSelect>(a, select, variant);
-  else launch_tile_sel<kRTN>(a, select, variant);
+// All tiled (columnwise / both) kernels of one (input type, rounding mode) pair.
+template <bool XF32, int ROUNDING>
+void run_tile(const TileArgs &a, uint32_t select, int variant) {
+  if (select == NVFP4_SEL_46_MSE) launch_tile_variant<XF32, ROUNDING, kSel46>(a, variant);
+  else if (select == NVFP4_SEL_FORCE6) launch_tile_variant<XF32, ROUNDING, kSelForce6>(a, variant);
+  else if (select == NVFP4_SEL_FORCE4) launch_tile_variant<XF32, ROUNDING, kSelForce4>(a, variant);
+  else if (select == NVFP4_SEL_46_MAE) launch_tile_variant<XF32, ROUNDING, kSel46Mae>(a, variant);
+  else launch_tile_variant<XF32, ROUNDING, kSel46AbsMax>(a, variant);
 }
 
 struct Block2dArgs {
@@ -1023,7 +1006,7 @@ struct Block2dArgs {
   hipStream_t stream;
 };
 
-template <int ROUNDING, int SELECT>
+template <bool XF32, int ROUNDING, int SELECT>
 static void launch_block2d(const Block2dArgs &a, int out) {
   const int64_t tiles = (a.rows / 16) * (a.cols / 16);
   const int grid = grid_for(tiles * 16, 16);
@@ -1032,28 +1015,65 @@ static void launch_block2d(const Block2dArgs &a, int out) {
                        a.scales, a.choice, a.codes_col, a.scales_col, a.choice_col, a.out, a.rows,
                        a.cols, a.sr_seed);
   };
-  if (out == kOutCodes) {
-    if (a.xf32) go(k_block2d<true, ROUNDING, SELECT, kOutCodes>);
-    else go(k_block2d<false, ROUNDING, SELECT, kOutCodes>);
-  } else {
-    if (a.xf32) go(k_block2d<true, ROUNDING, SELECT, kOutFake>);
-    else go(k_block2d<false, ROUNDING, SELECT, kOutFake>);
-  }
+  if (out == kOutCodes) go(k_block2d<XF32, ROUNDING, SELECT, kOutCodes>);
+  else go(k_block2d<XF32, ROUNDING, SELECT, kOutFake>);
 }
 
-template <int ROUNDING>
-static void launch_block2d_sel(const Block2dArgs &a, uint32_t select, int out) {
-  if (select == NVFP4_SEL_46_MSE) launch_block2d<ROUNDING, kSel46>(a, out);
-  else if (select == NVFP4_SEL_FORCE6) launch_block2d<ROUNDING, kSelForce6>(a, out);
-  else if (select == NVFP4_SEL_FORCE4) launch_block2d<ROUNDING, kSelForce4>(a, out);
-  else if (select == NVFP4_SEL_46_MAE) launch_block2d<ROUNDING, kSel46Mae>(a, out);
-  else launch_block2d<ROUNDING, kSel46AbsMax>(a, out);
+// All 16x16-tile kernels of one (input type, rounding mode) pair.
+template <bool XF32, int ROUNDING>
+void run_block2d(const Block2dArgs &a, uint32_t select, int out) {
+  if (select == NVFP4_SEL_46_MSE) launch_block2d<XF32, ROUNDING, kSel46>(a, out);
+  else if (select == NVFP4_SEL_FORCE6) launch_block2d<XF32, ROUNDING, kSelForce6>(a, out);
+  else if (select == NVFP4_SEL_FORCE4) launch_block2d<XF32, ROUNDING, kSelForce4>(a, out);
+  else if (select == NVFP4_SEL_46_MAE) launch_block2d<XF32, ROUNDING, kSel46Mae>(a, out);
+  else launch_block2d<XF32, ROUNDING, kSel46AbsMax>(a, out);
+}
+
+// One group of kernels = the three run_* templates for one (XF32, ROUNDING) pair.  A part
+// that holds a group defines it; the main part, when built apart, only declares them.
+#define NVFP4_46_GROUP(KEYWORD, XF32, ROUNDING)                                                 \
+  KEYWORD template void run_flat<XF32, ROUNDING>(const FlatArgs &, uint32_t, bool, int);        \
+  KEYWORD template void run_tile<XF32, ROUNDING>(const TileArgs &, uint32_t, int);              \
+  KEYWORD template void run_block2d<XF32, ROUNDING>(const Block2dArgs &, uint32_t, int);
+#if NVFP4_46_PART == 0
+NVFP4_46_GROUP(extern, false, kRTN)
+NVFP4_46_GROUP(extern, false, kSR)
+NVFP4_46_GROUP(extern, false, kSRAfterRtnSelect)
+NVFP4_46_GROUP(extern, true, kRTN)
+NVFP4_46_GROUP(extern, true, kSR)
+NVFP4_46_GROUP(extern, true, kSRAfterRtnSelect)
+#elif NVFP4_46_PART >= 1 && NVFP4_46_PART <= 6
+static_assert(kRTN == 0 && kSR == 1 && kSRAfterRtnSelect == 2, "parts are numbered by these");
+NVFP4_46_GROUP(, ((NVFP4_46_PART - 1) / 3 != 0), ((NVFP4_46_PART - 1) % 3))
+#endif
+
+#if NVFP4_46_MAIN
+static int rounding_index(uint32_t rounding) {
+  return rounding == NVFP4_SR ? kSR : rounding == NVFP4_SR_AFTER_RTN_SELECT ? kSRAfterRtnSelect : kRTN;
+}
+
+static void dispatch_flat(const FlatArgs &a, uint32_t rounding, uint32_t select, bool rht, int out) {
+  typedef void (*Fn)(const FlatArgs &, uint32_t, bool, int);
+  static const Fn table[2][3] = {
+      {run_flat<false, kRTN>, run_flat<false, kSR>, run_flat<false, kSRAfterRtnSelect>},
+      {run_flat<true, kRTN>, run_flat<true, kSR>, run_flat<true, kSRAfterRtnSelect>}};
+  table[a.xf32][rounding_index(rounding)](a, select, rht, out);
+}
+
+static void dispatch_tile(const TileArgs &a, uint32_t rounding, uint32_t select, int variant) {
+  typedef void (*Fn)(const TileArgs &, uint32_t, int);
+  static const Fn table[2][3] = {
+      {run_tile<false, kRTN>, run_tile<false, kSR>, run_tile<false, kSRAfterRtnSelect>},
+      {run_tile<true, kRTN>, run_tile<true, kSR>, run_tile<true, kSRAfterRtnSelect>}};
+  table[a.xf32][rounding_index(rounding)](a, select, variant);
 }
 
 static void dispatch_block2d(const Block2dArgs &a, uint32_t rounding, uint32_t select, int out) {
-  if (rounding == NVFP4_SR) launch_block2d_sel<kSR>(a, select, out);
-  else if (rounding == NVFP4_SR_AFTER_RTN_SELECT) launch_block2d_sel<kSRAfterRtnSelect>(a, select, out);
-  else launch_block2d_sel<kRTN>(a, select, out);
+  typedef void (*Fn)(const Block2dArgs &, uint32_t, int);
+  static const Fn table[2][3] = {
+      {run_block2d<false, kRTN>, run_block2d<false, kSR>, run_block2d<false, kSRAfterRtnSelect>},
+      {run_block2d<true, kRTN>, run_block2d<true, kSR>, run_block2d<true, kSRAfterRtnSelect>}};
+  table[a.xf32][rounding_index(rounding)](a, select, out);
 }
 
 // Checks shared by the entry points that take the parameter block.
@@ -1081,7 +1101,11 @@ static int check_params(const void *x, const nvfp4_46_params *p, bool one_layout
   return NVFP4_OK;
 }
 
+#endif  // NVFP4_46_MAIN
+
 }  // namespace nvfp4_46
+
+#if NVFP4_46_MAIN
 
 using namespace nvfp4_46;
 
@@ -1109,11 +1133,13 @@ int nvfp4_46_tensor_scale(const void *x, const nvfp4_46_params *p, float *alpha,
   } else if (p->layout == NVFP4_ROWWISE) {
     FlatArgs a{xf32, static_cast<const uint4 *>(x), nullptr, nullptr, nullptr, nullptr, nullptr, amax,
                n / 16, (uint32_t)(p->cols / 16), 0, p->rht_seed, s};
-    launch_flat<kRTN, kSel46, true, kOutAmax>(a);
+    if (xf32) launch_flat<true, kRTN, kSel46, true, kOutAmax>(a);
+    else launch_flat<false, kRTN, kSel46, true, kOutAmax>(a);
   } else {
     TileArgs a{xf32, x, nullptr, nullptr, nullptr, nullptr, nullptr,
                nullptr, nullptr, nullptr, amax, p->rows, p->cols, 0, p->rht_seed, s};
-    launch_tile<kRTN, kSel46, true, false, kOutAmax>(a);
+    if (xf32) launch_tile<true, kRTN, kSel46, true, false, kOutAmax>(a);
+    else launch_tile<false, kRTN, kSel46, true, false, kOutAmax>(a);
   }
   hipLaunchKernelGGL(k_finish_alpha, dim3(1), dim3(1), 0, s, alpha, p->fp8_max);
   return launch_status();
@@ -1287,3 +1313,5 @@ int nvfp4_46_debug_philox(const uint32_t *ctr, uint32_t key0, uint32_t key1, int
 }
 
 }  // extern "C"
+
+#endif  // NVFP4_46_MAIN
