@@ -30,11 +30,20 @@ from paper_2512_02010_amd import binding as B  # noqa: E402
 from paper_2512_02010_amd import workloads as wl  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
-# plain (unpacked) fp32 VALU issue rate: 256 CUs x 64 lanes x 2.4 GHz, in lane-operations/s
-VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
+# fp32 vector rate of the chip in lane-operations/s: 157.3 TFLOP/s counts a fused
+# multiply-add as two, i.e. 256 CUs x 128 lanes x 2.4 GHz.  `--valu-rates` measures that the
+# plain (unpacked) v_fma/v_mul/v_add and the two-operand logic operations do issue at about
+# this rate (a wave's instruction in two passes) while conversions, comparisons, selects,
+# min/max, integer multiplies and three-operand integer operations take four passes and the
+# FP4/FP8 packing conversions eight (profiles/valu_issue_rates.txt).
+VALU_PEAK_TOPS = 256 * 128 * 2.4e9 / 1e12
 # VALU wave-instructions per block of 16 elements in the rowwise 4/6 kernel, from
 # rocprofv3 --pmc SQ_INSTS_VALU (profiles/c2_step_counters.txt): 14,920,024 per 4,194,304/64 wave-blocks
 VALU_INSTS_PER_BLOCK_46 = 14920024.0 / (4194304.0 / 64.0)
+# the same for the kernels of c4 (both orientations, per 16 elements) and c5 (Hadamard +
+# stochastic rounding), profiles/c5_rowwise_rht_sr_counters.txt
+VALU_INSTS_PER_BLOCK_C4 = 30731260.0 / (4194304.0 / 64.0)
+VALU_INSTS_PER_BLOCK_C5 = 64939446.0 / (4194304.0 / 64.0)
 # HBM bytes per element of the same kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled
 # by a plain copy's readings (same file): (65612.8 * 2.000 + 36864.3 * 1.000) KiB per 67,108,864
 HBM_TRAFFIC_PER_ELEM_46 = (65612.8 * 2.0 + 36864.3) * 1024.0 / 67108864.0
@@ -67,6 +76,10 @@ def parse():
                          "codes, scale bytes 0x30..0x47; eight rotating weight operands) sixteen "
                          "times (four when M = 8192) and exit (for `rocprofv3 --pmc ... -- python3 "
                          "bench.py --counter-pass-gemm [M]`); prints no benchmark line")
+    ap.add_argument("--valu-rates", action="store_true",
+                    help="time the issue rate of each vector-ALU instruction class "
+                         "(nvfp4_46_debug_valu_rate) and print one line per class; prints no "
+                         "benchmark line")
     ap.add_argument("--layer-pass", action="store_true",
                     help="run five steps of the Fig. 3 linear layer (8192 tokens, 8192 -> 8192) and "
                          "exit (for `rocprofv3 --kernel-trace --stats -- python3 bench.py "
@@ -287,10 +300,17 @@ def time_other_workloads(iters=30):
             he.free(pair)
         return m
 
-    def entry(n, bpe, t_scale, t_main, what):
-        return {"what": what, "elements": n, "tensor_scale_us": t_scale, "main_us": t_main,
-                "main_g_elem_s": n / t_main / 1e3, "main_algorithmic_gb_s": n * bpe / t_main / 1e3,
-                "main_frac_of_8tbs": n * bpe / t_main / 1e3 / HBM_PEAK_GBS}
+    def entry(n, bpe, t_scale, t_main, what, valu_per_block=None):
+        e = {"what": what, "elements": n, "tensor_scale_us": t_scale, "main_us": t_main,
+             "main_g_elem_s": n / t_main / 1e3, "main_algorithmic_gb_s": n * bpe / t_main / 1e3,
+             "main_frac_of_8tbs": n * bpe / t_main / 1e3 / HBM_PEAK_GBS}
+        if valu_per_block is not None:
+            # the vector-ALU roof: lane-operations (rocprofv3 SQ_INSTS_VALU per block) / s
+            tops = valu_per_block * (n / 16.0) / (t_main * 1e-6) / 1e12
+            e["main_alu"] = {"bound": "alu", "achieved": tops, "peak": VALU_PEAK_TOPS,
+                             "unit": "T lane-op/s", "frac": tops / VALU_PEAK_TOPS,
+                             "valu_insts_per_16_elements": valu_per_block}
+        return e
 
     # variants of the rowwise quantizer on the c2 tensor: the other selection rules, the
     # stochastic-rounding modes, 16x16 tiles
@@ -424,7 +444,8 @@ def time_other_workloads(iters=30):
     t_m = med(lambda i: B.quantize_raw(xs[i % 2], p, alpha, os_[i % 2]["codes_row"],
                                        os_[i % 2]["scales_row"], os_[i % 2]["codes_col"],
                                        os_[i % 2]["scales_col"], None, None, st))
-    res["c4"] = entry(r * c, 3.125, t_s, t_m, "8192x8192 quantize, both orientations, RTN 4/6")
+    res["c4"] = entry(r * c, 3.125, t_s, t_m, "8192x8192 quantize, both orientations, RTN 4/6",
+                      VALU_INSTS_PER_BLOCK_C4)
     del xs, os_
     # c5: gradient tensor, Hadamard transform + stochastic rounding (arithmetic-bound)
     xs = [wl.make("c5").cuda() for _ in range(2)]
@@ -435,7 +456,8 @@ def time_other_workloads(iters=30):
     t_m = med(lambda i: B.quantize_raw(xs[i % 2], p, alpha, os_[i % 2]["codes_row"],
                                        os_[i % 2]["scales_row"], None, None, None, None, st))
     res["c5"] = entry(r * c, BYTES_PER_ELEM_QUANT, t_s, t_m,
-                      "32768x8192 quantize, rowwise, Hadamard + stochastic rounding, 4/6")
+                      "32768x8192 quantize, rowwise, Hadamard + stochastic rounding, 4/6",
+                      VALU_INSTS_PER_BLOCK_C5)
     return res
 
 
@@ -447,6 +469,31 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     B.lib()
+    if args.valu_rates:
+        out = torch.zeros(1, dtype=torch.float32, device="cuda")
+        st = torch.cuda.current_stream()
+        he = hip_events()
+        iters = 4096
+        wave_insts = B.VALU_RATE_WAVE_INSTS_PER_ITER * iters
+        print("wave-instructions per launch: %d (2048 workgroups x 4 waves x 32 x %d rounds); "
+              "best of 5 launches; passes = duration x 2.4 GHz x 1024 SIMDs / wave-instructions"
+              % (wave_insts, iters))
+        for kind, name in enumerate(B.VALU_RATE_KINDS):
+            B.nvfp4_46_debug_valu_rate(kind, 64, out, st)
+            torch.cuda.synchronize()
+            best = float("inf")
+            for _ in range(5):
+                a, b = he.new(), he.new()
+                he.record(a, st)
+                B.nvfp4_46_debug_valu_rate(kind, iters, out, st)
+                he.record(b, st)
+                torch.cuda.synchronize()
+                best = min(best, he.elapsed_ms(a, b))
+                he.free((a, b))
+            print("%-28s %7.3f ms  %6.2f T lane-op/s  %5.2f cycles per wave-instruction per "
+                  "SIMD at 2.4 GHz" % (name, best, wave_insts * 64 / (best * 1e-3) / 1e12,
+                                       best * 1e-3 * 2.4e9 * 1024 / wave_insts), flush=True)
+        return
     if args.counter_pass_gemm:
         g = torch.Generator(device="cuda")
         g.manual_seed(1)
@@ -507,6 +554,16 @@ def main():
                 B.quantize_raw(x4, p4, sets[0].alpha, o4["codes_row"], o4["scales_row"],
                                o4["codes_col"], o4["scales_col"], None, None, st)
                 B.fake_quant_raw(x4, sets[0].params, sets[0].alpha, sets[0].deq, st)
+            # the arithmetic-bound rowwise kernel: Hadamard transform + stochastic rounding
+            # on the c5 recipe (same per-block work as the full 32768x8192 tensor)
+            x5 = wl.make("c5", rows, cols).cuda()
+            p5 = B.make_params(rows, cols, rounding=B.SR, rht=1, sr_seed=wl.C5_SR_SEED,
+                               rht_seed=wl.C5_RHT_SEED)
+            a5 = torch.empty(1, dtype=torch.float32, device="cuda")
+            B.tensor_scale_raw(x5, p5, a5, st)
+            for i in range(4):
+                B.quantize_raw(x5, p5, a5, o4["codes_row"], o4["scales_row"], None, None, None,
+                               None, st)
         torch.cuda.synchronize()
         print("counter pass done: 3 copies of %d bytes, 6 steps" % (n * 2))
         return
@@ -600,9 +657,12 @@ def main():
         },
         "roofline_alu": {
             "bound": "alu",
-            "note": "the same kernel against plain fp32 VALU issue (packed fp32 is not used): "
-                    "lane-operations = wave-instructions per block (rocprofv3 SQ_INSTS_VALU) "
-                    "x blocks",
+            "note": "the same kernel against the chip's fp32 vector rate (157.3 TFLOP/s = 78.6 T "
+                    "fused multiply-adds/s; reached by plain instructions, packed fp32 is not "
+                    "used): lane-operations = wave-instructions per block (rocprofv3 "
+                    "SQ_INSTS_VALU) x blocks; half of this kernel's instructions are of classes "
+                    "that issue at half or a quarter of that rate "
+                    "(profiles/valu_issue_rates.txt)",
             "achieved": VALU_INSTS_PER_BLOCK_46 * (n / 16.0) / (t_quant * 1e-3) / 1e12,
             "peak": VALU_PEAK_TOPS,
             "unit": "T lane-op/s",

@@ -18,6 +18,7 @@ UNITS += [(PKG / "csrc" / "nvfp4_46.hip", {"NVFP4_46_PART": part}, f"nvfp4_46.pa
 UNITS += [(PKG / "csrc" / "gemm.hip", {"NVFP4_46_GEMM_PART": part}, f"gemm.part{part}")
           for part in (5, 6, 0)]
 UNITS.append((PKG / "csrc" / "nvfp4_46.hip", {"NVFP4_46_PART": 0}, "nvfp4_46.part0"))
+UNITS.append((PKG / "csrc" / "valu_rate.hip", {}, "valu_rate"))
 SO = PKG / "libnvfp4_46.so"
 
 # -ffp-contract=off: the method's arithmetic is one rounding per operation.
