@@ -523,6 +523,11 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
   constexpr int W = skinny_waves(MT), NST = skinny_stages(MT);
   constexpr uint32_t ROWS = skinny_rows(MT), STAGE = skinny_stage_bytes(MT);
   constexpr int NC = ROWS / 8, NS = skinny_scale_rows(MT) / 64;   // copy instructions per chunk
+#ifdef NVFP4_46_SKINNY_PROBE_NO_A
+  constexpr int NCI = 4;     // timing probe only: A's codes are never copied (wrong results)
+#else
+  constexpr int NCI = NC;
+#endif
   extern __shared__ __align__(16) uint8_t lds_raw[];
   const uint32_t t = threadIdx.x, lane = t & 63u;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -570,7 +575,7 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
     const uint32_t lds = lds_wave + stage * STAGE;
     const uint8_t *pb = gcb + cc * (SK / 2), *pa = gca + cc * (SK / 2);
 #pragma unroll
-    for (int q = 0; q < NC; ++q) {
+    for (int q = 0; q < NCI; ++q) {
       if (q < 4) NV_DMA16(lds + q * 1024, oc[q], pb);
       else NV_DMA16(lds + q * 1024, oc[q], pa);
     }
@@ -581,7 +586,7 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
                    :: "s"(lds + ROWS * 128 + j * 1024), "v"(src) : "memory");
     }
   };
-  constexpr int kCopies = NC + NS;
+  constexpr int kCopies = NCI + NS;
 
   // one chunk of one operand row as the lane holds it: 128 codes and their 8 scales, the
   // scales already as FP16 bit patterns (byte << 7), two per word
@@ -627,6 +632,9 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
   while (c < nchunks) {
     if (NST == 2) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(kCopies) : "memory");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#ifdef NVFP4_46_SKINNY_PROBE_NO_MATH
+    copy_chunk(c + W * NST, stage);       // timing probe only: the copies alone (wrong results)
+#else
     Raw rb, ra[MT];
     read_tile(stage, 0, rb);
 #pragma unroll
@@ -642,6 +650,7 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
         acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(expand(ra[i], s), fb, acc[i], 0, 0, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
+#endif
     c += W;
     if (NST == 2) stage ^= 1u;
   }
