@@ -499,10 +499,17 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm_dma(
 // arithmetic and the other waves' work.
 // MT = number of 32-row tiles of A (1, 2 or 4).  K must be a multiple of 256 and <= 2^24.
 constexpr int SK = 256;          // contraction indices per chunk
-// waves per workgroup: eight, or four with four tiles of A (whose registers need the larger
-// per-wave budget of a four-wave workgroup)
-constexpr int skinny_waves(int mt) { return mt <= 2 ? 8 : 4; }
-constexpr int skinny_stages(int mt) { return mt == 1 ? 2 : 1; }
+// Waves per workgroup and staging pieces per wave, for 1, 2 and 4 tiles of A.  Four waves were
+// fastest on every weight shape timed (8192 x 8192, 28672 x 8192, 8192 x 28672, 4096 x 4096;
+// 2 to 10 waves and 1 to 4 pieces were tried): with one tile of A the workgroup then needs
+// 72 KiB of LDS and two of them share a compute unit, so one's start and end overlap the
+// other's stream.
+#ifndef NVFP4_46_SKINNY_SHAPE
+#define NVFP4_46_SKINNY_SHAPE {4, 2}, {4, 1}, {4, 1}
+#endif
+constexpr int kSkinnyShape[3][2] = {NVFP4_46_SKINNY_SHAPE};
+constexpr int skinny_waves(int mt) { return kSkinnyShape[mt == 1 ? 0 : mt == 2 ? 1 : 2][0]; }
+constexpr int skinny_stages(int mt) { return kSkinnyShape[mt == 1 ? 0 : mt == 2 ? 1 : 2][1]; }
 constexpr uint32_t skinny_rows(int mt) { return 32u + 32u * mt; }        // B rows, then A rows
 constexpr uint32_t skinny_scale_rows(int mt) { return (skinny_rows(mt) + 63u) / 64u * 64u; }
 constexpr uint32_t skinny_stage_bytes(int mt) {
@@ -514,12 +521,16 @@ constexpr size_t skinny_lds_bytes(int mt) {
   return stages > partials ? stages : partials;
 }
 
+static_assert(skinny_lds_bytes(1) <= 160 * 1024 && skinny_lds_bytes(2) <= 160 * 1024 &&
+              skinny_lds_bytes(4) <= 160 * 1024, "the stages must fit the LDS");
+
 template <int MT, bool OUTF32>
 __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
     const uint8_t *__restrict__ codes_a, const uint8_t *__restrict__ scales_a,
     const float *__restrict__ alpha_a, const uint8_t *__restrict__ codes_b,
     const uint8_t *__restrict__ scales_b, const float *__restrict__ alpha_b,
-    void *__restrict__ out, int64_t M, int64_t N, int64_t K, uint32_t sha, uint32_t shb) {
+    void *__restrict__ out, int64_t M, int64_t N, int64_t K, uint32_t sha, uint32_t shb,
+    uint32_t slabs) {
   constexpr int W = skinny_waves(MT), NST = skinny_stages(MT);
   constexpr uint32_t ROWS = skinny_rows(MT), STAGE = skinny_stage_bytes(MT);
   constexpr int NC = ROWS / 8, NS = skinny_scale_rows(MT) / 64;   // copy instructions per chunk
@@ -532,8 +543,18 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
   const uint32_t t = threadIdx.x, lane = t & 63u;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const uint32_t r = lane & 31u, g = lane >> 5;
-  const int64_t n0 = (int64_t)blockIdx.x * 32;
+  // More than 32 MT rows of A are handled in slabs of 32 MT rows, each by a workgroup of its own.
+  // Workgroups go to the chip's eight dies in turn and each die has its own L2, so the slabs
+  // of one 32-column strip are consecutive workgroups of one die: B is fetched into one L2.
+  const uint32_t xcd = blockIdx.x & 7u, seq = blockIdx.x >> 3;
+  const uint32_t slab = seq % slabs, strip = (seq / slabs) * 8 + xcd;
+  const int64_t n0 = (int64_t)strip * 32;
+  if (n0 >= N) return;                                   // padding of the grid to whole turns
   const int64_t row_codes = K / 2, row_scales = K / 16;
+  const int64_t m0 = (int64_t)slab * (32 * MT);
+  codes_a += m0 * row_codes;
+  scales_a += (m0 >> sha) * row_scales;
+  M -= m0;                                               // rows left from this slab's first on
   const uint8_t *wl = lds_raw + wave * (NST * STAGE);
   const uint32_t lds_wave = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds_raw +
                             wave * (NST * STAGE);
@@ -630,8 +651,8 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
   for (int p = 0; p < NST; ++p) copy_chunk(c + W * p, p);
   uint32_t stage = 0;
   while (c < nchunks) {
-    if (NST == 2) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(kCopies) : "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // all but the copies of the NST - 1 younger stages must have landed
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"((NST - 1) * kCopies) : "memory");
 #ifdef NVFP4_46_SKINNY_PROBE_NO_MATH
     copy_chunk(c + W * NST, stage);       // timing probe only: the copies alone (wrong results)
 #else
@@ -652,7 +673,7 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
     __builtin_amdgcn_sched_barrier(0);
 #endif
     c += W;
-    if (NST == 2) stage ^= 1u;
+    stage = stage + 1 == (uint32_t)NST ? 0u : stage + 1;
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // nothing may still be writing LDS
   __syncthreads();                                       // ... of any wave: the stages are reused
@@ -677,6 +698,189 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
 #pragma unroll
         for (int w = 0; w < W - 1; ++w) sum += part[w][i][v][lane];
         const int64_t row = 32 * i + 8 * (v / 4) + 4 * g + (v % 4);
+        if (row < M && col < N) {
+          const float cval = sum * scale;
+          if (OUTF32)
+            static_cast<float *>(out)[(m0 + row) * N + col] = cval;
+          else
+            static_cast<uint16_t *>(out)[(m0 + row) * N + col] = (uint16_t)pack_bf16x2(cval, 0.0f);
+        }
+      }
+  }
+}
+
+// ----------------------------------------------------------------------------------------
+// At most 16 rows of A (a decoding batch): the same plan with the 16x16x32 matrix instruction.
+// A's tile is 16 rows, so half as much of A is copied, read back and expanded per workgroup,
+// and the two 16-column halves of the workgroup's 32 columns of C share each expanded
+// fragment of A; per 32 contraction indices a wave issues three expansions and two 4-pass
+// matrix instructions where the 32-row plan issues four and two 8-pass ones.
+//
+// Stage layout per wave: rows 0-31 B, rows 32-47 A (128 code bytes each, 16-byte units
+// swizzled as above), then 64 scale lines of 16 bytes (lines 48-63 repeat A's last row).
+// Lane l holds row l % 16 of a tile and the 64 codes 64 g .. 64 g + 63 of the chunk,
+// g = l / 16 (two 16-byte units); matrix step s (0..7) multiplies codes 64 g + 8 s .. + 7 of
+// every lane group, the same for A and B, so which contraction indices meet in one
+// instruction is again a permutation shared by both operands.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr uint32_t kSkinny16Rows = 48, kSkinny16Stage = kSkinny16Rows * 128 + 64 * 16;   // 7168
+#ifndef NVFP4_46_SKINNY16_WAVES
+#define NVFP4_46_SKINNY16_WAVES 4
+#endif
+#ifndef NVFP4_46_SKINNY16_STAGES
+#define NVFP4_46_SKINNY16_STAGES 2
+#endif
+constexpr int kSkinny16Waves = NVFP4_46_SKINNY16_WAVES, kSkinny16Stages = NVFP4_46_SKINNY16_STAGES;
+constexpr size_t kSkinny16LdsBytes = (size_t)kSkinny16Waves * kSkinny16Stages * kSkinny16Stage;
+static_assert(kSkinny16LdsBytes <= 160 * 1024 && kSkinny16Stages >= 1, "stages must fit the LDS");
+static_assert((size_t)(kSkinny16Waves - 1) * 2 * 4 * 64 * sizeof(float) <= kSkinny16LdsBytes,
+              "the partial sums reuse the stages");
+
+template <bool OUTF32>
+__global__ __launch_bounds__(64 * kSkinny16Waves) void k_gemm_skinny16(
+    const uint8_t *__restrict__ codes_a, const uint8_t *__restrict__ scales_a,
+    const float *__restrict__ alpha_a, const uint8_t *__restrict__ codes_b,
+    const uint8_t *__restrict__ scales_b, const float *__restrict__ alpha_b,
+    void *__restrict__ out, int64_t M, int64_t N, int64_t K, uint32_t sha, uint32_t shb) {
+  constexpr int W = kSkinny16Waves, NST = kSkinny16Stages;
+  constexpr uint32_t ROWS = kSkinny16Rows, STAGE = kSkinny16Stage;
+  constexpr int NC = ROWS / 8;                                     // code copies per chunk
+#ifdef NVFP4_46_SKINNY_PROBE_NO_A
+  constexpr int NCI = 4;     // timing probe only: A's codes are never copied (wrong results)
+#else
+  constexpr int NCI = NC;
+#endif
+  extern __shared__ __align__(16) uint8_t lds_raw[];
+  const uint32_t t = threadIdx.x, lane = t & 63u;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const uint32_t rr = lane & 15u, g = lane >> 4;
+  const int64_t n0 = (int64_t)blockIdx.x * 32;
+  const int64_t row_codes = K / 2, row_scales = K / 16;
+  const uint8_t *wl = lds_raw + wave * (NST * STAGE);
+  const uint32_t lds_wave = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds_raw +
+                            wave * (NST * STAGE);
+
+  auto uniform = [](const uint8_t *p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const uint8_t *>(((uint64_t)hi << 32) | lo);
+  };
+  const int64_t b_base = n0 < N ? n0 : N - 1;
+  const uint8_t *gcb = uniform(codes_b + b_base * row_codes), *gca = uniform(codes_a);
+  uint32_t oc[NC];
+#pragma unroll
+  for (int q = 0; q < NC; ++q) {
+    const uint32_t row = 8 * q + (lane >> 3), unit = (lane & 7u) ^ ((row >> 1) & 7u);
+    int64_t line;
+    if (q < 4) line = b_base + row < N ? row : N - 1 - b_base;       // relative to b_base
+    else line = (int64_t)(row - 32) < M ? row - 32 : M - 1;
+    oc[q] = (uint32_t)(line * row_codes) + unit * 16;
+  }
+  const uint8_t *ps;
+  if (lane < 32) {
+    const int64_t n = n0 + lane < N ? n0 + lane : N - 1;
+    ps = scales_b + (n >> shb) * row_scales;
+  } else {
+    const int64_t m = (int64_t)(lane - 32) < M ? lane - 32 : M - 1;
+    ps = scales_a + (m >> sha) * row_scales;
+  }
+  auto copy_chunk = [&](int64_t c, uint32_t stage) {
+    const int64_t cc = c < K / SK ? c : K / SK - 1;                  // past the end: a harmless re-read
+    const uint32_t lds = lds_wave + stage * STAGE;
+    const uint8_t *pb = gcb + cc * (SK / 2), *pa = gca + cc * (SK / 2);
+#pragma unroll
+    for (int q = 0; q < NCI; ++q) {
+      if (q < 4) NV_DMA16(lds + q * 1024, oc[q], pb);
+      else NV_DMA16(lds + q * 1024, oc[q], pa);
+    }
+    const uint8_t *src = ps + cc * (SK / 16);
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(lds + ROWS * 128), "v"(src) : "memory");
+  };
+  constexpr int kCopies = NCI + 1;
+
+  // a lane's share of one operand row for one chunk: 64 codes and the scales of their four
+  // blocks as FP16 bit patterns (byte << 7), two per word
+  struct Raw {
+    uint4 c[2];
+    uint32_t s[2];
+  };
+  auto read_tile = [&](uint32_t stage, uint32_t first_row, Raw &x) {
+    const uint8_t *st = wl + stage * STAGE;
+    const uint32_t row = first_row + rr, swz = (row >> 1) & 7u;
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+      x.c[q] = *reinterpret_cast<const uint4 *>(st + row * 128 + (((2 * g + q) ^ swz) * 16));
+    const uint32_t sc = *reinterpret_cast<const uint32_t *>(st + ROWS * 128 + row * 16 + 4 * g);
+    x.s[0] = __builtin_amdgcn_perm(0u, sc, 0x0c010c00u) << 7;
+    x.s[1] = __builtin_amdgcn_perm(0u, sc, 0x0c030c02u) << 7;
+  };
+  auto expand = [&](const Raw &x, int s) {                         // matrix step s = 0..7
+    const uint4 &q = x.c[s >> 2];
+    const uint32_t w = (s & 3) == 0 ? q.x : (s & 3) == 1 ? q.y : (s & 3) == 2 ? q.z : q.w;
+    const h2 pair = __builtin_bit_cast(h2, x.s[s >> 2]);            // blocks 4 g + 2 (s / 4), + 1
+    return expand8(w, (s & 2) ? pair.y : pair.x);                    // block 4 g + s / 2
+  };
+
+  f32x4 acc[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[j][v] = 0.0f;
+
+  const int64_t nchunks = K / SK;
+  int64_t c = wave;
+#pragma unroll
+  for (int p = 0; p < NST; ++p) copy_chunk(c + W * p, p);
+  uint32_t stage = 0;
+  while (c < nchunks) {
+    // all but the copies of the NST - 1 younger stages must have landed
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"((NST - 1) * kCopies) : "memory");
+#ifdef NVFP4_46_SKINNY_PROBE_NO_MATH
+    copy_chunk(c + NST * W, stage);       // timing probe only: the copies alone (wrong results)
+#else
+    Raw ra, rb[2];
+    read_tile(stage, 32, ra);
+    read_tile(stage, 0, rb[0]);
+    read_tile(stage, 16, rb[1]);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    copy_chunk(c + NST * W, stage);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const h8 fa = expand(ra, s);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa, expand(rb[j], s), acc[j], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#endif
+    c += W;
+    stage = stage + 1 == (uint32_t)NST ? 0u : stage + 1;
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // nothing may still be writing LDS
+  __syncthreads();                                       // ... of any wave: the stages are reused
+
+  // ---- add the waves' tiles in a fixed order (wave 0 collects), scale, store
+  float (*part)[2][4][64] = reinterpret_cast<float (*)[2][4][64]>(lds_raw);
+  if (wave > 0) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) part[wave - 1][j][v][lane] = acc[j][v];
+  }
+  __syncthreads();
+  if (wave == 0) {
+    const float scale = alpha_a[0] * alpha_b[0];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        float sum = acc[j][v];
+#pragma unroll
+        for (int w = 0; w < W - 1; ++w) sum += part[w][j][v][lane];
+        const int64_t row = 4 * g + v, col = n0 + 16 * j + rr;
         if (row < M && col < N) {
           const float cval = sum * scale;
           if (OUTF32)
@@ -769,10 +973,21 @@ int run_gemm_dma(const GemmArgs &a) {
 // Few rows of A: one workgroup per 32 columns of C, bound by streaming B.
 int run_gemm_skinny(const GemmArgs &a) {
   auto go = [&](auto kernel, int mt) {
-    return launch_with_lds(kernel, dim3((uint32_t)((a.N + 31) / 32)), dim3(64 * skinny_waves(mt)),
+    const int64_t slabs = (a.M + 32 * mt - 1) / (32 * mt), strips = (a.N + 31) / 32;
+    const int64_t grid = (strips + 7) / 8 * 8 * slabs;      // whole turns over the eight dies
+    return launch_with_lds(kernel, dim3((uint32_t)grid), dim3(64 * skinny_waves(mt)),
                            skinny_lds_bytes(mt), a.stream, a.codes_a, a.scales_a, a.alpha_a,
-                           a.codes_b, a.scales_b, a.alpha_b, a.out, a.M, a.N, a.K, a.sha, a.shb);
+                           a.codes_b, a.scales_b, a.alpha_b, a.out, a.M, a.N, a.K, a.sha, a.shb,
+                           (uint32_t)slabs);
   };
+  if (a.M <= 16) {
+    auto go16 = [&](auto kernel) {
+      return launch_with_lds(kernel, dim3((uint32_t)((a.N + 31) / 32)), dim3(64 * kSkinny16Waves),
+                             kSkinny16LdsBytes, a.stream, a.codes_a, a.scales_a, a.alpha_a,
+                             a.codes_b, a.scales_b, a.alpha_b, a.out, a.M, a.N, a.K, a.sha, a.shb);
+    };
+    return a.f32 ? go16(k_gemm_skinny16<true>) : go16(k_gemm_skinny16<false>);
+  }
   if (a.M <= 32) return a.f32 ? go(k_gemm_skinny<1, true>, 1) : go(k_gemm_skinny<1, false>, 1);
   if (a.M <= 64) return a.f32 ? go(k_gemm_skinny<2, true>, 2) : go(k_gemm_skinny<2, false>, 2);
   return a.f32 ? go(k_gemm_skinny<4, true>, 4) : go(k_gemm_skinny<4, false>, 4);
@@ -812,7 +1027,15 @@ extern "C" int nvfp4_46_gemm(const void *codes_a, const void *scales_a, const fl
                    (flags & NVFP4_GEMM_B_TILE_SCALES) ? 4u : 0u, out_dtype == NVFP4_OUT_F32,
                    static_cast<hipStream_t>(stream)};
   const bool offsets_fit = K <= ((int64_t)1 << 24);     // 32-bit lane offsets of the copies
-  if (M <= 128 && (K % SK) == 0 && offsets_fit) return run_gemm_skinny(a);
+  // The kernel that streams B takes up to 128 rows of A at its best and, in slabs of 128 rows,
+  // up to 512 as long as the 128 x 128 tiles of the other kernels would not even fill the
+  // chip's 256 compute units once (timed on 8192 x 8192, 28672 x 8192, 8192 x 28672 and
+  // 4096 x 4096 weights: with fewer tiles than that, those kernels wait on HBM chunk by chunk).
+#ifndef NVFP4_46_SKINNY_MAX_M
+#define NVFP4_46_SKINNY_MAX_M 512
+#endif
+  const bool few_rows = M <= 128 || (M <= NVFP4_46_SKINNY_MAX_M && tiles_m * tiles_n <= 256);
+  if (few_rows && (K % SK) == 0 && offsets_fit) return run_gemm_skinny(a);
   if (NVFP4_46_GEMM_DMA && (K % GK) == 0 && offsets_fit) return run_gemm_dma(a);
   if ((K % GK) == 0)
     return a.f32 ? run_gemm_staged<true, true>(a) : run_gemm_staged<true, false>(a);

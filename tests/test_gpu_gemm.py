@@ -70,7 +70,11 @@ SHAPES = [(32, 32, 32), (1, 1, 64), (100, 70, 160), (256, 256, 128), (257, 255, 
           (300, 520, 1056), (512, 768, 2048), (200, 300, 256),
           # few rows of A and K a multiple of 256: the kernel that streams B
           (1, 40, 256), (16, 32, 512), (33, 100, 1024), (64, 1000, 2304), (100, 96, 768),
-          (128, 257, 512), (129, 64, 512)]
+          (128, 257, 512), (129, 64, 512),
+          # at most 16 rows of A: the 16-row variant of that kernel
+          (7, 45, 256), (16, 64, 768), (9, 1000, 2304), (3, 17, 4096), (17, 33, 256),
+          # up to 512 rows of A in slabs of 128 rows through the same kernel
+          (257, 255, 768), (384, 300, 256), (511, 40, 1024), (513, 40, 512)]
 
 
 @pytest.mark.parametrize("out_dtype", [B.OUT_F32, B.OUT_BF16])
@@ -111,6 +115,41 @@ def test_gemm_is_exact_when_every_partial_sum_is_representable():
                             out_dtype=B.OUT_BF16)
     want16 = torch.from_numpy(c_ref.astype(np.float32)).to(torch.bfloat16)
     assert torch.equal(got16.cpu(), want16)
+
+
+@pytest.mark.parametrize("M", [1, 5, 16, 17, 30, 64, 128, 200, 512])
+def test_small_batch_gemm_is_exact_when_every_partial_sum_is_representable(M):
+    """The same argument for the kernels that take few rows of A (16-row, 32-row, 64-row and
+    128-row variants): scales 0.5 .. 4, so every sum is exact in fp32 in any order."""
+    rng = np.random.default_rng(4600 + M)
+    N, K = 77, 768
+    ca = rng.integers(0, 256, (M, K // 2), dtype=np.uint8)
+    cb = rng.integers(0, 256, (N, K // 2), dtype=np.uint8)
+    sa = rng.choice(np.array([0x30, 0x38, 0x40], np.uint8), (M, K // 16))
+    sb = rng.choice(np.array([0x38, 0x40, 0x48], np.uint8), (N, K // 16))
+    c_ref = ref.gemm(ca, sa, 1.0, cb, sb, 1.0)
+    assert np.array_equal(c_ref, c_ref.astype(np.float32).astype(np.float64))
+    got = B.nvfp4_46_gemm(_dev(ca), _dev(sa), _alpha(1.0), _dev(cb), _dev(sb), _alpha(1.0),
+                          out_dtype=B.OUT_F32)
+    assert np.array_equal(got.cpu().numpy().astype(np.float64), c_ref)
+
+
+def test_small_batch_gemm_with_tile_scaled_operands():
+    """Sixteen rows of A and a B operand, both quantized in 16x16 tiles (one scale line per
+    16 rows), through the 16-row kernel; and the same B against 32 rows of A."""
+    K, N = 512, 48
+    for M in (16, 32):
+        ops, ref_ops = [], []
+        for rows, name in ((M, "c3"), (N, "c2")):
+            bits = wl.bf16_bits(wl.make(name, rows, K, seed=7100 + rows))
+            a = ref.tensor_scale(bits)
+            c, s, _, _ = ref.quantize_2d(bits, a)
+            ref_ops += [c, s, a]
+            ops += [_dev(c), _dev(s), _alpha(a)]
+        flags = B.GEMM_A_TILE_SCALES | B.GEMM_B_TILE_SCALES
+        c_ref, c_abs = ref.gemm(*ref_ops, want_abs=True, tiles_a=True, tiles_b=True)
+        got = B.nvfp4_46_gemm(*ops, out_dtype=B.OUT_F32, flags=flags).double().cpu().numpy()
+        assert (np.abs(got - c_ref) <= _tolerance(c_ref, c_abs, K, B.OUT_F32)).all(), M
 
 
 def test_gemm_every_scale_byte_and_code():
