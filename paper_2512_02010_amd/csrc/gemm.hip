@@ -480,7 +480,8 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm_dma(
 }
 
 // ----------------------------------------------------------------------------------------
-// Few rows of A (M <= 128: a small batch of activations against a weight matrix).  The product
+// Few rows of A (a small batch of activations against a weight matrix; the entry point says
+// how few).  The product
 // is then bound by reading B once from HBM -- which is where four-bit operands pay on this
 // chip: 0.5625 bytes per weight instead of 2 -- so the plan changes: every workgroup owns 32
 // rows of B (32 columns of C) and all of A, and its waves split the contraction axis (wave w
