@@ -48,6 +48,9 @@ enum : int { kOutCodes = 0, kOutFake = 1, kOutAmax = 2 };
 #ifndef NVFP4_46_FLAT_WG_PER_CU
 #define NVFP4_46_FLAT_WG_PER_CU 32
 #endif
+#ifndef NVFP4_46_FLAT_AMAX_WG_PER_CU
+#define NVFP4_46_FLAT_AMAX_WG_PER_CU 2
+#endif
 
 // Streaming accesses: every input word is read once and every output byte written once,
 // so neither should displace anything in the caches (the `nt` forms of the memory
@@ -206,6 +209,70 @@ __global__ __launch_bounds__(kThreads) void k_amax_plain(const uint4 *__restrict
   for (; i < n16; i += stride) fold(load_stream(x + i));
   const uint32_t top = XF32 ? acc32 : (uint32_t)(acc.x > acc.y ? acc.x : acc.y) << 16;
   publish_amax(u2f(top), amax_bits);
+}
+
+// max|y| over the Hadamard-transformed column blocks (16 consecutive rows of one column),
+// without LDS: a lane loads one 16-byte piece from each of the 16 rows of a row block -- 8
+// BF16 or 4 fp32 columns, a wave's loads cover 1 KiB of each row -- and transforms every
+// column in registers.  The signs depend on the row only, so they are flipped in the packed
+// words; the factor 1/4 of the transform is applied once to the maximum (scaling by a power
+// of two is monotonic, so the maximum of the scaled values is the scaled maximum).
+#ifndef NVFP4_46_AMAX_RHT_COL_WG_PER_CU
+#define NVFP4_46_AMAX_RHT_COL_WG_PER_CU 8
+#endif
+template <bool XF32>
+__global__ __launch_bounds__(kThreads) void k_amax_rht_col(const uint4 *__restrict__ x,
+                                                           int64_t row_blocks, int64_t pieces_per_row,
+                                                           uint64_t rht_seed, uint32_t *amax_bits) {
+  const int64_t items = row_blocks * pieces_per_row;
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  float m = 0.0f;
+  for (int64_t item = (int64_t)blockIdx.x * kThreads + threadIdx.x; item < items; item += stride) {
+    const int64_t rb = item / pieces_per_row, piece = item - rb * pieces_per_row;
+    const uint4 *src = x + rb * 16 * pieces_per_row + piece;
+    uint4 w[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) w[j] = load_stream(src + j * pieces_per_row);
+    const uint32_t sw = rht_sign_word(rht_seed, (uint64_t)rb);
+    constexpr uint32_t kSignBits = XF32 ? 0x80000000u : 0x80008000u;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const uint32_t flip = (0u - ((sw >> j) & 1u)) & kSignBits;    // row j of the block
+      w[j].x ^= flip;
+      w[j].y ^= flip;
+      w[j].z ^= flip;
+      w[j].w ^= flip;
+    }
+#pragma unroll
+    for (int c = 0; c < (XF32 ? 4 : 8); ++c) {
+      float v[16];
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        if constexpr (XF32) {
+          v[j] = u2f(c == 0 ? w[j].x : c == 1 ? w[j].y : c == 2 ? w[j].z : w[j].w);
+        } else {
+          const uint32_t word = (c >> 1) == 0 ? w[j].x : (c >> 1) == 1 ? w[j].y
+                              : (c >> 1) == 2 ? w[j].z : w[j].w;
+          v[j] = u2f((c & 1) ? (word & 0xffff0000u) : (word << 16));
+        }
+      }
+      // the butterflies of rht16() (strides 1, 2, 4, 8), signs already applied, no scaling
+#pragma unroll
+      for (int h = 1; h < 16; h <<= 1) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          if ((i & h) == 0) {
+            const float a = v[i], b = v[i + h];
+            v[i] = a + b;
+            v[i + h] = a - b;
+          }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 16; j += 2) m = fmaxf(m, fmaxf(fabsf(v[j]), fabsf(v[j + 1])));
+    }
+  }
+  publish_amax(m * 0.25f, amax_bits);
 }
 
 // -------------------------------------------------------- rowwise (flat)
@@ -395,7 +462,7 @@ __global__ __launch_bounds__(kThreads) void k_tile(
     uint8_t *__restrict__ codes_row, uint8_t *__restrict__ scales_row,
     uint8_t *__restrict__ choice_row, uint8_t *__restrict__ codes_col,
     uint8_t *__restrict__ scales_col, uint8_t *__restrict__ choice_col,
-    uint16_t *__restrict__ out_bf16, uint32_t *amax_bits, int64_t rows, int64_t cols,
+    uint16_t *__restrict__ out_bf16, int64_t rows, int64_t cols,
     uint64_t sr_seed, uint64_t rht_seed) {
   __shared__ ScaleTable tab;
   // the tile, row-major: one 32-bit word (two BF16) or two (two fp32) per pair of columns
@@ -438,9 +505,7 @@ __global__ __launch_bounds__(kThreads) void k_tile(
       for (int q = 0; q < Raw::kPieces; ++q) dst[q] = w[j].w[q];
     }
   }
-  ScaleConsts sc{};
-  if (OUT != kOutAmax) sc = build_scale_table(tab, *alpha_p);   // ends with a barrier
-  else __syncthreads();
+  const ScaleConsts sc = build_scale_table(tab, *alpha_p);     // ends with a barrier
 
   if (WANT_ROW) {
     // the lane's own row blocks, taken back from LDS one at a time (keeps the register
@@ -474,7 +539,6 @@ __global__ __launch_bounds__(kThreads) void k_tile(
   // ---- phase 2: every lane takes two adjacent columns x 16 rows.  A (column pair, row
   // block) unit is read and, for the fake-quant output, rewritten in place by its owner
   // lane only, so no barrier is needed inside this phase.
-  float amax = 0.0f;
 #pragma unroll 1
   for (int j = 0; j < kPairUnitsPerLane; ++j) {
     const int pu = t + j * kThreads;
@@ -499,11 +563,6 @@ __global__ __launch_bounds__(kThreads) void k_tile(
       const uint32_t sw = rht_sign_word(rht_seed, (uint64_t)(gr >> 4));
       rht16(va, sw);
       rht16(vb, sw);
-    }
-    if (OUT == kOutAmax) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fmaxf(fabsf(va[i]), fabsf(vb[i])));
-      continue;
     }
     if (ROUNDING != kRTN) {
       // element (row, col) has flat index g = row*cols + col; the pair (gc, gc+1) shares a
@@ -549,10 +608,6 @@ __global__ __launch_bounds__(kThreads) void k_tile(
       for (int i = 0; i < 16; ++i)
         tile[((rb * 16 + i) * kColPairs + cp) * kXW] = pack_bf16x2(Da[i], Db[i]);
     }
-  }
-  if (OUT == kOutAmax) {
-    publish_amax(amax, amax_bits);
-    return;
   }
   __syncthreads();
 
@@ -912,7 +967,9 @@ struct FlatArgs {
 
 template <bool XF32, int ROUNDING, int SELECT, bool RHT, int OUT>
 static void launch_flat(const FlatArgs &a) {
-  int grid = grid_for(a.nblocks, NVFP4_46_FLAT_WG_PER_CU);
+  // the amax pass ends with one access per workgroup to the one result word: fewer, longer-lived
+  // workgroups than the passes that write their own outputs
+  int grid = grid_for(a.nblocks, OUT == kOutAmax ? NVFP4_46_FLAT_AMAX_WG_PER_CU : NVFP4_46_FLAT_WG_PER_CU);
   if (RHT) {
     // round r of a workgroup starts at block 256*r; if 256*grid is a multiple of the
     // blocks per row, every lane sees one position along the row in all its rounds
@@ -953,7 +1010,6 @@ struct TileArgs {
   const float *alpha;
   uint8_t *codes_row, *scales_row, *choice_row, *codes_col, *scales_col, *choice_col;
   uint16_t *out;
-  uint32_t *amax;
   int64_t rows, cols;
   uint64_t sr_seed, rht_seed;
   hipStream_t stream;
@@ -969,7 +1025,7 @@ static void launch_tile(const TileArgs &a) {
   hipLaunchKernelGGL((k_tile<XF32, ROUNDING, SELECT, RHT, WANT_ROW, OUT>),
                      dim3(tile_grid(a.rows, a.cols)), dim3(kThreads), 0, a.stream, a.x, a.alpha,
                      a.codes_row, a.scales_row, a.choice_row, a.codes_col, a.scales_col,
-                     a.choice_col, a.out, a.amax, a.rows, a.cols, a.sr_seed, a.rht_seed);
+                     a.choice_col, a.out, a.rows, a.cols, a.sr_seed, a.rht_seed);
 }
 
 // variant: 0 = columnwise codes, 1 = columnwise codes + rht, 2 = both orientations,
@@ -1136,10 +1192,15 @@ int nvfp4_46_tensor_scale(const void *x, const nvfp4_46_params *p, float *alpha,
     if (xf32) launch_flat<true, kRTN, kSel46, true, kOutAmax>(a);
     else launch_flat<false, kRTN, kSel46, true, kOutAmax>(a);
   } else {
-    TileArgs a{xf32, x, nullptr, nullptr, nullptr, nullptr, nullptr,
-               nullptr, nullptr, nullptr, amax, p->rows, p->cols, 0, p->rht_seed, s};
-    if (xf32) launch_tile<true, kRTN, kSel46, true, false, kOutAmax>(a);
-    else launch_tile<false, kRTN, kSel46, true, false, kOutAmax>(a);
+    // columnwise blocks (rows % 16 == 0, cols % 8 == 0): 16-byte pieces of 8 BF16 / 4 fp32 columns
+    const int64_t row_blocks = p->rows / 16, pieces = xf32 ? p->cols / 4 : p->cols / 8;
+    const dim3 grid(grid_for(row_blocks * pieces, NVFP4_46_AMAX_RHT_COL_WG_PER_CU));
+    if (xf32)
+      hipLaunchKernelGGL(k_amax_rht_col<true>, grid, dim3(kThreads), 0, s,
+                         static_cast<const uint4 *>(x), row_blocks, pieces, p->rht_seed, amax);
+    else
+      hipLaunchKernelGGL(k_amax_rht_col<false>, grid, dim3(kThreads), 0, s,
+                         static_cast<const uint4 *>(x), row_blocks, pieces, p->rht_seed, amax);
   }
   hipLaunchKernelGGL(k_finish_alpha, dim3(1), dim3(1), 0, s, alpha, p->fp8_max);
   return launch_status();
@@ -1178,7 +1239,7 @@ int nvfp4_46_quantize(const void *x, const nvfp4_46_params *p, const float *alph
     TileArgs a{xf32, x, alpha, static_cast<uint8_t *>(codes_row),
                static_cast<uint8_t *>(scales_row), static_cast<uint8_t *>(choice_row),
                static_cast<uint8_t *>(codes_col), static_cast<uint8_t *>(scales_col),
-               static_cast<uint8_t *>(choice_col), nullptr, nullptr, p->rows, p->cols, p->sr_seed,
+               static_cast<uint8_t *>(choice_col), nullptr, p->rows, p->cols, p->sr_seed,
                p->rht_seed, s};
     dispatch_tile(a, p->rounding, p->select, want_row ? 2 : (p->rht ? 1 : 0));
   }
@@ -1242,7 +1303,7 @@ int nvfp4_46_fake_quant(const void *x, const nvfp4_46_params *p, const float *al
     dispatch_flat(a, p->rounding, p->select, p->rht != 0, kOutFake);
   } else {
     TileArgs a{xf32, x, alpha, nullptr, nullptr, nullptr, nullptr,
-               nullptr, nullptr, static_cast<uint16_t *>(out_bf16), nullptr, p->rows, p->cols,
+               nullptr, nullptr, static_cast<uint16_t *>(out_bf16), p->rows, p->cols,
                p->sr_seed, p->rht_seed, s};
     dispatch_tile(a, p->rounding, p->select, p->rht ? 4 : 3);
   }
