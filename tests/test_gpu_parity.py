@@ -446,6 +446,21 @@ def test_workload_c5_full_rht_sr():
     check_case(wl.make("c5"), rounding=B.SR, rht=1, tag="c5-full")
 
 
+@pytest.mark.parametrize("dtype,rows,cols", [(torch.bfloat16, 8192, 8192), (torch.float32, 4096, 6152),
+                                             (torch.bfloat16, 16, 8), (torch.float32, 48, 8)])
+def test_tensor_scale_of_hadamard_transformed_columns_at_size(dtype, rows, cols):
+    """The columnwise maximum after the transform (many rounds of the grid, a ragged last
+    round, and the smallest legal tensors) equals the oracle's, bit for bit."""
+    x = wl.make("c5", rows, cols, dtype=dtype)
+    a_ref = ref.tensor_scale(wl.host_array(x), layout=ref.COLWISE, rht=1, rht_seed=RHT_SEED)
+    a_gpu = B.nvfp4_46_tensor_scale(x.cuda(), layout=B.COLWISE, rht=1, rht_seed=RHT_SEED)
+    assert _alpha_bits(a_gpu.item()) == _alpha_bits(a_ref)
+    if cols % 16 == 0:          # the rowwise pass over the same tensor
+        a_ref = ref.tensor_scale(wl.host_array(x), rht=1, rht_seed=RHT_SEED)
+        a_gpu = B.nvfp4_46_tensor_scale(x.cuda(), rht=1, rht_seed=RHT_SEED)
+        assert _alpha_bits(a_gpu.item()) == _alpha_bits(a_ref)
+
+
 # ------------------------------------------------------------------ seeded sweep over shapes and options
 
 def _sweep_cases(n, seed):
