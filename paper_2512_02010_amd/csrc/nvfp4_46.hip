@@ -479,9 +479,16 @@ __global__ __launch_bounds__(kThreads) void k_tile(
   const int64_t r0 = tcd.r0, c0 = tcd.c0;
   const int t = threadIdx.x;
 
+  // Only columnwise codes wanted: nothing needs the tile in LDS -- a lane reads its two columns
+  // straight from memory, a row at a time (a wave's load covers 256 contiguous bytes of a row).
+#ifndef NVFP4_46_TILE_DIRECT
+#define NVFP4_46_TILE_DIRECT 1
+#endif
+  constexpr bool kDirect = NVFP4_46_TILE_DIRECT && !WANT_ROW && OUT == kOutCodes;
+
   // ---- phase 1: global -> LDS (and the rowwise outputs on the way); the loads go out
   // before the scale table is built
-  {
+  if (!kDirect) {
     constexpr int kElemsPerPiece = XF32 ? 4 : 8;
     Raw w[kRowBlocksPerLane];
 #pragma unroll
@@ -550,11 +557,14 @@ __global__ __launch_bounds__(kThreads) void k_tile(
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       if constexpr (XF32) {
-        const uint2 pair = reinterpret_cast<const uint2 *>(tile)[(rb * 16 + i) * kColPairs + cp];
+        const uint2 pair = kDirect
+            ? static_cast<const uint2 *>(x_any)[((gr + i) * cols + gc) >> 1]
+            : reinterpret_cast<const uint2 *>(tile)[(rb * 16 + i) * kColPairs + cp];
         va[i] = u2f(pair.x);
         vb[i] = u2f(pair.y);
       } else {
-        const uint32_t pair = tile[(rb * 16 + i) * kColPairs + cp];
+        const uint32_t pair = kDirect ? static_cast<const uint32_t *>(x_any)[((gr + i) * cols + gc) >> 1]
+                                      : tile[(rb * 16 + i) * kColPairs + cp];
         va[i] = bf16_lo(pair);
         vb[i] = bf16_hi(pair);
       }
