@@ -118,3 +118,14 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     with pytest.raises(FileNotFoundError):
         B.lib()
+
+
+def test_every_hip_source_is_part_of_the_build():
+    from pathlib import Path
+    from paper_2512_02010_amd import build
+    sources = {p.name for p in (Path(build.PKG) / "csrc").glob("*.hip")}
+    assert sources == {Path(u[0]).name for u in build.UNITS}
+    # each part number of a source compiled in parts appears exactly once
+    for name in ("nvfp4_46.hip", "gemm.hip"):
+        parts = sorted(list(u[1].values())[0] for u in build.UNITS if Path(u[0]).name == name)
+        assert parts == list(range(7)), (name, parts)
