@@ -76,10 +76,6 @@ def parse():
                          "codes, scale bytes 0x30..0x47; eight rotating weight operands) sixteen "
                          "times (four when M = 8192) and exit (for `rocprofv3 --pmc ... -- python3 "
                          "bench.py --counter-pass-gemm [M]`); prints no benchmark line")
-    ap.add_argument("--valu-rates", action="store_true",
-                    help="time the issue rate of each vector-ALU instruction class "
-                         "(nvfp4_46_debug_valu_rate) and print one line per class; prints no "
-                         "benchmark line")
     ap.add_argument("--layer-pass", action="store_true",
                     help="run five steps of the Fig. 3 linear layer (8192 tokens, 8192 -> 8192) and "
                          "exit (for `rocprofv3 --kernel-trace --stats -- python3 bench.py "
@@ -469,31 +465,6 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     B.lib()
-    if args.valu_rates:
-        out = torch.zeros(1, dtype=torch.float32, device="cuda")
-        st = torch.cuda.current_stream()
-        he = hip_events()
-        iters = 4096
-        wave_insts = B.VALU_RATE_WAVE_INSTS_PER_ITER * iters
-        print("wave-instructions per launch: %d (2048 workgroups x 4 waves x 32 x %d rounds); "
-              "best of 5 launches; passes = duration x 2.4 GHz x 1024 SIMDs / wave-instructions"
-              % (wave_insts, iters))
-        for kind, name in enumerate(B.VALU_RATE_KINDS):
-            B.nvfp4_46_debug_valu_rate(kind, 64, out, st)
-            torch.cuda.synchronize()
-            best = float("inf")
-            for _ in range(5):
-                a, b = he.new(), he.new()
-                he.record(a, st)
-                B.nvfp4_46_debug_valu_rate(kind, iters, out, st)
-                he.record(b, st)
-                torch.cuda.synchronize()
-                best = min(best, he.elapsed_ms(a, b))
-                he.free((a, b))
-            print("%-28s %7.3f ms  %6.2f T lane-op/s  %5.2f cycles per wave-instruction per "
-                  "SIMD at 2.4 GHz" % (name, best, wave_insts * 64 / (best * 1e-3) / 1e12,
-                                       best * 1e-3 * 2.4e9 * 1024 / wave_insts), flush=True)
-        return
     if args.counter_pass_gemm:
         g = torch.Generator(device="cuda")
         g.manual_seed(1)

@@ -216,21 +216,6 @@ int nvfp4_46_debug_e2m1_sr(const float *y, const float *u, int64_t n, void *out_
 int nvfp4_46_debug_philox(const uint32_t *ctr, uint32_t key0, uint32_t key1, int64_t n,
                           uint32_t *out, void *stream);
 
-/* ---- measurement aid ----------------------------------------------------------------
- * Launches one kernel (2048 workgroups of 256 lanes, no memory traffic) in which every wave
- * executes 32 * iters instructions of one class on eight independent registers, so that
- * the caller can time how fast that class issues; the quantizers' arithmetic bound is
- * priced with these rates.  kind: 0 v_fma_f32, 1 v_mul_f32, 2 v_add_f32, 3 v_max_f32,
- * 4 v_max3_f32, 5 v_xor_b32, 6 v_lshrrev_b32, 7 v_lshlrev_b32, 8 v_add_u32, 9 v_max_u32,
- * 10 v_mad_u64_u32, 11 v_mul_lo_u32, 12 v_cvt_f32_u32, 13 v_floor_f32, 14 v_rcp_f32,
- * 15 v_cndmask_b32, 16 v_cmp_lt_f32, 17 v_bitop3_b32, 18 v_and_or_b32, 19 v_perm_b32,
- * 20 v_cvt_scalef32_pk_fp4_f32, 21 v_cvt_scalef32_pk_f32_fp4, 22 v_cvt_pk_fp8_f32,
- * 23 v_cvt_pk_bf16_f32.  out_f32: at least 4 bytes (device), practically never written.
- * Wave-instructions per launch = 2048 * 4 * 32 * iters.  Errors: out_f32 NULL -> ERR_NULL;
- * kind > 23, iters < 1 or iters > 2^20 -> ERR_PARAM. */
-#define NVFP4_46_VALU_RATE_KINDS 24
-int nvfp4_46_debug_valu_rate(uint32_t kind, int32_t iters, void *out_f32, void *stream);
-
 #ifdef __cplusplus
 }
 #endif

@@ -30,7 +30,7 @@ EXPORTS = (
     "nvfp4_46_tensor_scale", "nvfp4_46_quantize", "nvfp4_46_dequantize", "nvfp4_46_fake_quant",
     "nvfp4_46_gemm", "nvfp4_46_status_string", "nvfp4_46_debug_e2m1_rtn_range", "nvfp4_46_debug_e4m3_range",
     "nvfp4_46_debug_decode_tables", "nvfp4_46_debug_bf16_range", "nvfp4_46_debug_e2m1_sr",
-    "nvfp4_46_debug_philox", "nvfp4_46_debug_valu_rate",
+    "nvfp4_46_debug_philox",
 )
 
 
@@ -91,8 +91,6 @@ def lib() -> C.CDLL:
         L.nvfp4_46_debug_e2m1_sr.argtypes = [vp, vp, i64, vp, vp]
         L.nvfp4_46_debug_philox.restype = C.c_int
         L.nvfp4_46_debug_philox.argtypes = [vp, u32, u32, i64, vp, vp]
-        L.nvfp4_46_debug_valu_rate.restype = C.c_int
-        L.nvfp4_46_debug_valu_rate.argtypes = [u32, C.c_int32, vp, vp]
         _lib = L
     return _lib
 
@@ -306,20 +304,3 @@ def nvfp4_46_debug_philox(ctr: torch.Tensor, key0: int, key1: int) -> torch.Tens
     _check(lib().nvfp4_46_debug_philox(_ptr(ctr), key0, key1, ctr.shape[0], _ptr(out),
                                        _stream(None)), "nvfp4_46_debug_philox")
     return out
-
-
-# instruction class of each ``kind`` of nvfp4_46_debug_valu_rate (same order as the header)
-VALU_RATE_KINDS = (
-    "v_fma_f32", "v_mul_f32", "v_add_f32", "v_max_f32", "v_max3_f32", "v_xor_b32",
-    "v_lshrrev_b32", "v_lshlrev_b32", "v_add_u32", "v_max_u32", "v_mad_u64_u32", "v_mul_lo_u32",
-    "v_cvt_f32_u32", "v_floor_f32", "v_rcp_f32", "v_cndmask_b32", "v_cmp_lt_f32", "v_bitop3_b32",
-    "v_and_or_b32", "v_perm_b32", "v_cvt_scalef32_pk_fp4_f32", "v_cvt_scalef32_pk_f32_fp4",
-    "v_cvt_pk_fp8_f32", "v_cvt_pk_bf16_f32",
-)
-VALU_RATE_WAVE_INSTS_PER_ITER = 2048 * 4 * 32
-
-
-def nvfp4_46_debug_valu_rate(kind: int, iters: int, out: torch.Tensor, stream=None) -> None:
-    """Launch the issue-rate kernel of instruction class ``kind`` (the caller times it)."""
-    _check(lib().nvfp4_46_debug_valu_rate(kind, iters, _ptr(out), _stream(stream)),
-           "nvfp4_46_debug_valu_rate")

@@ -18,7 +18,6 @@ UNITS += [(PKG / "csrc" / "nvfp4_46.hip", {"NVFP4_46_PART": part}, f"nvfp4_46.pa
 UNITS += [(PKG / "csrc" / "gemm.hip", {"NVFP4_46_GEMM_PART": part}, f"gemm.part{part}")
           for part in (5, 6, 0)]
 UNITS.append((PKG / "csrc" / "nvfp4_46.hip", {"NVFP4_46_PART": 0}, "nvfp4_46.part0"))
-UNITS.append((PKG / "csrc" / "valu_rate.hip", {}, "valu_rate"))
 SO = PKG / "libnvfp4_46.so"
 
 # -ffp-contract=off: the method's arithmetic is one rounding per operation.
@@ -27,13 +26,11 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function", "-Wno-unused-const-variable",
+    # the copy instructions' inline assembly names m0 as clobbered; the compiler remarks that
+    # m0 is a reserved register
+    "-Wno-inline-asm",
 ]
 
-# Which narrow-format conversions use the gfx950 instructions (see csrc/codec.hpp).  All
-# three were compared with the CPU oracle over their whole input range on an MI355X
-# (tests/test_gpu_codecs.py) and round identically, so they are on; 0 selects the
-# integer implementation of the same rounding.
-DEFAULT_DEFINES = {"NVFP4_46_HW_FP4": 1, "NVFP4_46_HW_FP8": 1, "NVFP4_46_HW_BF16": 1}
 
 
 def hipcc() -> str:
@@ -47,8 +44,7 @@ def build(out: Path | None = None, defines: dict | None = None, extra: list | No
     """Compile every unit to an object (side by side) and link the shared library."""
     from concurrent.futures import ThreadPoolExecutor
     out = Path(out) if out else SO
-    d = dict(DEFAULT_DEFINES)
-    d.update(defines or {})
+    d = dict(defines or {})
     flags = [f for f in HIPCC_FLAGS if f != "-shared"]
     common = [*flags, *(extra or []), f"-I{ROOT / 'include'}", f"-I{PKG / 'csrc'}"]
     objdir = PKG / "_build" / f"{out.stem}.{os.getpid()}"

@@ -35,7 +35,7 @@ NV_DEV ScaleConsts build_scale_table(ScaleTable &tab, float alpha) {
   k.c4 = alpha * 4.0f;
   for (uint32_t s = threadIdx.x; s < 128u; s += blockDim.x) {
     if (s < 127u) {
-      float dec = e4m3_decode_sw(s) * alpha;
+      float dec = e4m3_decode(s) * alpha;
       float enc = (dec == 0.0f) ? 0.0f : 1.0f / dec;
       tab.e[s] = make_float2(dec, enc);
     } else {
@@ -96,14 +96,9 @@ NV_DEV float error_tree(const float (&e)[16]) {
 NV_DEV void grid8(uint32_t codes, float (&g)[8]) {
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-#if NVFP4_46_HW_FP4
     f32x2 p = hw_pk_f32_fp4_sel(codes, j);
     g[2 * j] = p.x;
     g[2 * j + 1] = p.y;
-#else
-    g[2 * j] = e2m1_decode_sw((codes >> (8 * j)) & 15u);
-    g[2 * j + 1] = e2m1_decode_sw((codes >> (8 * j + 4)) & 15u);
-#endif
   }
 }
 
@@ -120,7 +115,6 @@ NV_DEV float candidate(const float (&v)[16], const float (&u)[16], float dec, fl
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     float g[8];
-#if NVFP4_46_HW_FP4
     if (ROUNDING == kRTN) {
       // v_cvt_scalef32_pk_fp4_f32 fills byte j of the word (first source in the low
       // nibble); the word is complete before v_cvt_scalef32_pk_f32_fp4 reads the bytes
@@ -131,7 +125,7 @@ NV_DEV float candidate(const float (&v)[16], const float (&u)[16], float dec, fl
         w = hw_pk_fp4_sel(w, v[8 * h + 2 * j] * enc, v[8 * h + 2 * j + 1] * enc, j);
       if (ERR != kErrNone) grid8(w, g);
       c[h] = w;
-    } else if (ROUNDING == kSR) {
+    } else {
       // the rounded values are on the grid, so the conversion that packs them is exact
 #pragma unroll
       for (int j = 0; j < 8; ++j) g[j] = e2m1_sr_value(v[8 * h + j] * enc, u[8 * h + j]);
@@ -139,23 +133,6 @@ NV_DEV float candidate(const float (&v)[16], const float (&u)[16], float dec, fl
 #pragma unroll
       for (int j = 0; j < 4; ++j) w = hw_pk_fp4_sel(w, g[2 * j], g[2 * j + 1], j);
       c[h] = w;
-    } else
-#endif
-    {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const float y = v[8 * h + j] * enc;
-        uint32_t k;
-        if (ROUNDING == kSR) {
-          g[j] = e2m1_sr_value(y, u[8 * h + j]);
-          k = e2m1_code_of_grid_value(g[j]);
-        } else {
-          float r;
-          k = e2m1_rtn_mag_sw(fminf(fabsf(y), 6.0f), r) | ((f2u(y) >> 28) & 8u);
-          g[j] = u2f(f2u(r) | (f2u(y) & 0x80000000u));
-        }
-        c[h] |= k << (4 * j);
-      }
     }
     if (ERR == kErrMseEstimate) {
 #pragma unroll

@@ -4,28 +4,14 @@
 // memory.  Arithmetic on values is IEEE binary32 with one rounding per
 // operation (the translation unit is compiled with -ffp-contract=off).
 //
-// Two implementations exist for the three narrow-format conversions:
-//   *_sw  -- integer / magic-number code whose rounding can be read off the
-//            source (round to nearest, ties to even, saturating);
-//   *_hw  -- the gfx950 conversion instructions (v_cvt_scalef32_pk_fp4_f32,
-//            v_cvt_pk_fp8_f32, v_cvt_pk_bf16_f32).
-// NVFP4_46_HW_FP4 / _FP8 / _BF16 (0 or 1) pick which one the kernels use.  A
-// hardware conversion is switched on only after the GPU tests have compared
-// it with the CPU oracle over its whole input range.
+// The three narrow-format roundings (fp32 -> E2M1, fp32 -> E4M3, fp32 -> BF16) are the
+// gfx950 conversion instructions v_cvt_scalef32_pk_fp4_f32, v_cvt_pk_fp8_f32 and
+// v_cvt_pk_bf16_f32: the GPU tests compare each with the CPU oracle over its whole
+// input range (round to nearest, ties to even, saturating).
 #pragma once
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-
-#ifndef NVFP4_46_HW_FP4
-#define NVFP4_46_HW_FP4 0
-#endif
-#ifndef NVFP4_46_HW_FP8
-#define NVFP4_46_HW_FP8 0
-#endif
-#ifndef NVFP4_46_HW_BF16
-#define NVFP4_46_HW_BF16 0
-#endif
 
 #define NV_DEV __device__ __forceinline__
 
@@ -43,59 +29,17 @@ NV_DEV float u2f(uint32_t u) { return __uint_as_float(u); }
 NV_DEV float bf16_lo(uint32_t w) { return u2f(w << 16); }
 NV_DEV float bf16_hi(uint32_t w) { return u2f(w & 0xffff0000u); }
 
-// fp32 -> BF16 bits, round to nearest even (finite inputs; overflow -> inf).
-NV_DEV uint32_t bf16_rne_sw(float f) {
-  uint32_t u = f2u(f);
-  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
-
-// Two fp32 -> one word of two BF16 (a in the low half).
+// Two fp32 -> one word of two BF16 (a in the low half), round to nearest even, overflow
+// to infinity (v_cvt_pk_bf16_f32).
 NV_DEV uint32_t pack_bf16x2(float a, float b) {
-#if NVFP4_46_HW_BF16
   f32x2 v = {a, b};
   bf16x2 h = __builtin_convertvector(v, bf16x2);
   return *reinterpret_cast<uint32_t *>(&h);
-#else
-  return bf16_rne_sw(a) | (bf16_rne_sw(b) << 16);
-#endif
 }
 
 // ------------------------------------------------------------------ E2M1
 
-// Value of a 4-bit code: sign<<3 | index into {0,.5,1,1.5,2,3,4,6} (Section 1).
-NV_DEV float e2m1_decode_sw(uint32_t code) {
-  uint32_t k = code & 7u;
-  // index k >= 2 is a normal number 2^(k/2 - 1) * (1 + (k&1)/2); 0 and 1 are 0 and 0.5
-  uint32_t bits = (k >= 2u) ? (((k >> 1) + 126u) << 23) | ((k & 1u) << 22)
-                            : (k ? 0x3f000000u : 0u);
-  return u2f(bits | ((code & 8u) << 28));
-}
-
-// Round |y| (clamped to 6) to the nearest E2M1 magnitude, ties to the even
-// index (Eq. 3 with half-even rounding).  Returns the 3-bit index and writes
-// the rounded magnitude.
-NV_DEV uint32_t e2m1_rtn_mag_sw(float a, float &r) {
-  // below 2 the grid step is 0.5: adding 2^22 (whose ulp is 0.5) rounds to a
-  // multiple of 0.5 half-even, and the low mantissa bits are then the index
-  if (a < 2.0f) {
-    float t = a + 4194304.0f;
-    r = t - 4194304.0f;
-    return f2u(t) & 7u;
-  }
-  // from 2 up the grid is "one mantissa bit": round the fp32 mantissa to its
-  // top bit half-even; a carry moves into the exponent as it should
-  uint32_t u = f2u(a);
-  u = (u + 0x1fffffu + ((u >> 22) & 1u)) >> 22;   // (exponent << 1) | mantissa bit
-  r = u2f(u << 22);
-  return u - 252u;                                 // exponent 128 -> index 4
-}
-
-// Code of y under round-to-nearest-even, saturating at +-6.
-NV_DEV uint32_t e2m1_rtn_sw(float y) {
-  float r;
-  uint32_t k = e2m1_rtn_mag_sw(fminf(fabsf(y), 6.0f), r);
-  return k | ((f2u(y) >> 28) & 8u);
-}
+// A 4-bit code is sign<<3 | index into {0,.5,1,1.5,2,3,4,6} (Section 1).
 
 // Stochastic rounding of y with uniform u in [0,1): lo <= |y| < hi neighbours on the
 // grid, up iff u < (|y|-lo)/(hi-lo).  The grid step around a = min(|y|, 6) is a power of
@@ -126,31 +70,16 @@ NV_DEV uint32_t e2m1_code_of_grid_value(float r) {
 // ------------------------------------------------------------------ E4M3
 
 // Value of an E4M3 byte 0x00..0x7E (bias 7, subnormals m * 2^-9).
-NV_DEV float e4m3_decode_sw(uint32_t b) {
+NV_DEV float e4m3_decode(uint32_t b) {
   uint32_t e = (b >> 3) & 15u, m = b & 7u;
   return e ? u2f(((e + 120u) << 23) | (m << 20)) : (float)m * 0x1p-9f;
 }
 
-// Non-negative fp32 -> E4M3 byte, round to nearest even, saturating at 448.
-NV_DEV uint32_t e4m3_encode_sw(float x) {
-  x = fminf(x, 448.0f);
-  if (x < 0x1p-6f) {
-    // subnormal range: multiples of 2^-9; the scaling is exact and rint is
-    // half-even; a result of 8 is the byte of 2^-6, the first normal value
-    return (uint32_t)__builtin_rintf(x * 512.0f);
-  }
-  uint32_t u = f2u(x);
-  u = (u + 0x7ffffu + ((u >> 20) & 1u)) >> 20;       // (exponent << 3) | 3 mantissa bits
-  return u - (120u << 3);
-}
-
+// Non-negative fp32 -> E4M3 byte, round to nearest even, saturating at 448 (the clamp
+// comes first: the conversion instruction alone turns values past 448 into NaN).
 NV_DEV uint32_t e4m3_encode(float x) {
-#if NVFP4_46_HW_FP8
   x = fminf(x, 448.0f);
   return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(x, x, 0, false) & 0xffu;
-#else
-  return e4m3_encode_sw(x);
-#endif
 }
 
 // --------------------------------------------------------------- Philox

@@ -26,6 +26,7 @@
 #include <hip/hip_runtime.h>
 
 #include "codec.hpp"
+#include "launch.hpp"
 #include "nvfp4_46.h"
 
 namespace nvfp4_46 {
@@ -33,12 +34,6 @@ namespace nvfp4_46 {
 typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-// 1: products with K a multiple of 128 use the variant with asynchronous global -> LDS copies
-// (k_gemm_dma); 0: every product uses the variant that stages through registers (k_gemm)
-#ifndef NVFP4_46_GEMM_DMA
-#define NVFP4_46_GEMM_DMA 1
-#endif
 
 constexpr int kGemmThreads = 256;
 constexpr int GT = 256;                  // rows of A (and of B) per workgroup tile
@@ -304,10 +299,10 @@ constexpr size_t kGemmDmaLdsBytes = 4 * kDmaWave;   // 147456
 // register), %2 = the 64-bit base address (scalar register pair).
 #define NV_DMA16(lds_sgpr, voff, gbase)                                                       \
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"                          \
-               :: "s"(lds_sgpr), "v"(voff), "s"(gbase) : "memory")
+               :: "s"(lds_sgpr), "v"(voff), "s"(gbase) : "memory", "m0")
 #define NV_DMA4(lds_sgpr, voff, gbase)                                                        \
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2"                            \
-               :: "s"(lds_sgpr), "v"(voff), "s"(gbase) : "memory")
+               :: "s"(lds_sgpr), "v"(voff), "s"(gbase) : "memory", "m0")
 
 template <bool OUTF32>
 __global__ __launch_bounds__(kGemmThreads) void k_gemm_dma(
@@ -505,10 +500,7 @@ constexpr int SK = 256;          // contraction indices per chunk
 // 2 to 10 waves and 1 to 4 pieces were tried): with one tile of A the workgroup then needs
 // 72 KiB of LDS and two of them share a compute unit, so one's start and end overlap the
 // other's stream.
-#ifndef NVFP4_46_SKINNY_SHAPE
-#define NVFP4_46_SKINNY_SHAPE {4, 2}, {4, 1}, {4, 1}
-#endif
-constexpr int kSkinnyShape[3][2] = {NVFP4_46_SKINNY_SHAPE};
+constexpr int kSkinnyShape[3][2] = {{4, 2}, {4, 1}, {4, 1}};
 constexpr int skinny_waves(int mt) { return kSkinnyShape[mt == 1 ? 0 : mt == 2 ? 1 : 2][0]; }
 constexpr int skinny_stages(int mt) { return kSkinnyShape[mt == 1 ? 0 : mt == 2 ? 1 : 2][1]; }
 constexpr uint32_t skinny_rows(int mt) { return 32u + 32u * mt; }        // B rows, then A rows
@@ -535,11 +527,6 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
   constexpr int W = skinny_waves(MT), NST = skinny_stages(MT);
   constexpr uint32_t ROWS = skinny_rows(MT), STAGE = skinny_stage_bytes(MT);
   constexpr int NC = ROWS / 8, NS = skinny_scale_rows(MT) / 64;   // copy instructions per chunk
-#ifdef NVFP4_46_SKINNY_PROBE_NO_A
-  constexpr int NCI = 4;     // timing probe only: A's codes are never copied (wrong results)
-#else
-  constexpr int NCI = NC;
-#endif
   extern __shared__ __align__(16) uint8_t lds_raw[];
   const uint32_t t = threadIdx.x, lane = t & 63u;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -597,7 +584,7 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
     const uint32_t lds = lds_wave + stage * STAGE;
     const uint8_t *pb = gcb + cc * (SK / 2), *pa = gca + cc * (SK / 2);
 #pragma unroll
-    for (int q = 0; q < NCI; ++q) {
+    for (int q = 0; q < NC; ++q) {
       if (q < 4) NV_DMA16(lds + q * 1024, oc[q], pb);
       else NV_DMA16(lds + q * 1024, oc[q], pa);
     }
@@ -605,10 +592,10 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
     for (int j = 0; j < NS; ++j) {
       const uint8_t *src = ps[j] + cc * (SK / 16);
       asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
-                   :: "s"(lds + ROWS * 128 + j * 1024), "v"(src) : "memory");
+                   :: "s"(lds + ROWS * 128 + j * 1024), "v"(src) : "memory", "m0");
     }
   };
-  constexpr int kCopies = NCI + NS;
+  constexpr int kCopies = NC + NS;
 
   // one chunk of one operand row as the lane holds it: 128 codes and their 8 scales, the
   // scales already as FP16 bit patterns (byte << 7), two per word
@@ -654,9 +641,6 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
   while (c < nchunks) {
     // all but the copies of the NST - 1 younger stages must have landed
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"((NST - 1) * kCopies) : "memory");
-#ifdef NVFP4_46_SKINNY_PROBE_NO_MATH
-    copy_chunk(c + W * NST, stage);       // timing probe only: the copies alone (wrong results)
-#else
     Raw rb, ra[MT];
     read_tile(stage, 0, rb);
 #pragma unroll
@@ -672,7 +656,6 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
         acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(expand(ra[i], s), fb, acc[i], 0, 0, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
-#endif
     c += W;
     stage = stage + 1 == (uint32_t)NST ? 0u : stage + 1;
   }
@@ -725,13 +708,7 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void k_gemm_skinny(
 // instruction is again a permutation shared by both operands.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr uint32_t kSkinny16Rows = 48, kSkinny16Stage = kSkinny16Rows * 128 + 64 * 16;   // 7168
-#ifndef NVFP4_46_SKINNY16_WAVES
-#define NVFP4_46_SKINNY16_WAVES 4
-#endif
-#ifndef NVFP4_46_SKINNY16_STAGES
-#define NVFP4_46_SKINNY16_STAGES 2
-#endif
-constexpr int kSkinny16Waves = NVFP4_46_SKINNY16_WAVES, kSkinny16Stages = NVFP4_46_SKINNY16_STAGES;
+constexpr int kSkinny16Waves = 4, kSkinny16Stages = 2;
 constexpr size_t kSkinny16LdsBytes = (size_t)kSkinny16Waves * kSkinny16Stages * kSkinny16Stage;
 static_assert(kSkinny16LdsBytes <= 160 * 1024 && kSkinny16Stages >= 1, "stages must fit the LDS");
 static_assert((size_t)(kSkinny16Waves - 1) * 2 * 4 * 64 * sizeof(float) <= kSkinny16LdsBytes,
@@ -746,11 +723,6 @@ __global__ __launch_bounds__(64 * kSkinny16Waves) void k_gemm_skinny16(
   constexpr int W = kSkinny16Waves, NST = kSkinny16Stages;
   constexpr uint32_t ROWS = kSkinny16Rows, STAGE = kSkinny16Stage;
   constexpr int NC = ROWS / 8;                                     // code copies per chunk
-#ifdef NVFP4_46_SKINNY_PROBE_NO_A
-  constexpr int NCI = 4;     // timing probe only: A's codes are never copied (wrong results)
-#else
-  constexpr int NCI = NC;
-#endif
   extern __shared__ __align__(16) uint8_t lds_raw[];
   const uint32_t t = threadIdx.x, lane = t & 63u;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -791,15 +763,15 @@ __global__ __launch_bounds__(64 * kSkinny16Waves) void k_gemm_skinny16(
     const uint32_t lds = lds_wave + stage * STAGE;
     const uint8_t *pb = gcb + cc * (SK / 2), *pa = gca + cc * (SK / 2);
 #pragma unroll
-    for (int q = 0; q < NCI; ++q) {
+    for (int q = 0; q < NC; ++q) {
       if (q < 4) NV_DMA16(lds + q * 1024, oc[q], pb);
       else NV_DMA16(lds + q * 1024, oc[q], pa);
     }
     const uint8_t *src = ps + cc * (SK / 16);
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :: "s"(lds + ROWS * 128), "v"(src) : "memory");
+                 :: "s"(lds + ROWS * 128), "v"(src) : "memory", "m0");
   };
-  constexpr int kCopies = NCI + 1;
+  constexpr int kCopies = NC + 1;
 
   // a lane's share of one operand row for one chunk: 64 codes and the scales of their four
   // blocks as FP16 bit patterns (byte << 7), two per word
@@ -838,9 +810,6 @@ __global__ __launch_bounds__(64 * kSkinny16Waves) void k_gemm_skinny16(
   while (c < nchunks) {
     // all but the copies of the NST - 1 younger stages must have landed
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"((NST - 1) * kCopies) : "memory");
-#ifdef NVFP4_46_SKINNY_PROBE_NO_MATH
-    copy_chunk(c + NST * W, stage);       // timing probe only: the copies alone (wrong results)
-#else
     Raw ra, rb[2];
     read_tile(stage, 32, ra);
     read_tile(stage, 0, rb[0]);
@@ -856,7 +825,6 @@ __global__ __launch_bounds__(64 * kSkinny16Waves) void k_gemm_skinny16(
         acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa, expand(rb[j], s), acc[j], 0, 0, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
-#endif
     c += W;
     stage = stage + 1 == (uint32_t)NST ? 0u : stage + 1;
   }
@@ -929,11 +897,9 @@ static int launch_with_lds(Kernel kernel, dim3 grid, dim3 block, size_t lds_byte
   if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                           hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)lds_bytes) != hipSuccess) {
-    (void)hipGetLastError();
     return NVFP4_ERR_HIP;
   }
-  hipLaunchKernelGGL(kernel, grid, block, lds_bytes, s, args...);
-  return hipGetLastError() == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+  return launch(kernel, grid, block, lds_bytes, s, args...);
 }
 
 static dim3 tile_grid(const GemmArgs &a) {
@@ -1032,12 +998,10 @@ extern "C" int nvfp4_46_gemm(const void *codes_a, const void *scales_a, const fl
   // up to 512 as long as the 128 x 128 tiles of the other kernels would not even fill the
   // chip's 256 compute units once (timed on 8192 x 8192, 28672 x 8192, 8192 x 28672 and
   // 4096 x 4096 weights: with fewer tiles than that, those kernels wait on HBM chunk by chunk).
-#ifndef NVFP4_46_SKINNY_MAX_M
-#define NVFP4_46_SKINNY_MAX_M 512
-#endif
-  const bool few_rows = M <= 128 || (M <= NVFP4_46_SKINNY_MAX_M && tiles_m * tiles_n <= 256);
+  const bool few_rows = M <= 128 || (M <= 512 && tiles_m * tiles_n <= 256);
   if (few_rows && (K % SK) == 0 && offsets_fit) return run_gemm_skinny(a);
-  if (NVFP4_46_GEMM_DMA && (K % GK) == 0 && offsets_fit) return run_gemm_dma(a);
+  // K a multiple of 128: the variant with asynchronous global -> LDS copies
+  if ((K % GK) == 0 && offsets_fit) return run_gemm_dma(a);
   if ((K % GK) == 0)
     return a.f32 ? run_gemm_staged<true, true>(a) : run_gemm_staged<true, false>(a);
   return a.f32 ? run_gemm_staged<false, true>(a) : run_gemm_staged<false, false>(a);

@@ -18,6 +18,7 @@
 #include <hip/hip_runtime.h>
 
 #include "block.hpp"
+#include "launch.hpp"
 #include "nvfp4_46.h"
 
 // The quantizing kernels exist once per (input type, rounding mode, selection rule, ...):
@@ -36,47 +37,27 @@ namespace nvfp4_46 {
 constexpr int kThreads = 256;
 enum : int { kOutCodes = 0, kOutFake = 1, kOutAmax = 2 };
 
-// workgroups per compute unit launched by the rowwise kernel (it strides over the tensor)
-// the plain absolute-maximum pass: few, long-lived workgroups (each ends with a
-// serialising access to the one result word) with many loads in flight per lane
-#ifndef NVFP4_46_AMAX_UNROLL
-#define NVFP4_46_AMAX_UNROLL 8
-#endif
-#ifndef NVFP4_46_AMAX_WG_PER_CU
-#define NVFP4_46_AMAX_WG_PER_CU 1
-#endif
-#ifndef NVFP4_46_FLAT_WG_PER_CU
-#define NVFP4_46_FLAT_WG_PER_CU 32
-#endif
-#ifndef NVFP4_46_FLAT_AMAX_WG_PER_CU
-#define NVFP4_46_FLAT_AMAX_WG_PER_CU 2
-#endif
+// Launch shapes (workgroups per compute unit; every kernel strides over its input).  Each
+// value is the fastest of a timed sweep on 8192 x 8192 tensors.
+constexpr int kAmaxUnroll = 8;          // independent 128-bit loads per lane in k_amax_plain
+constexpr int kAmaxWgPerCu = 1;         // k_amax_plain: few, long-lived workgroups, each ends
+                                        // with a serialising access to the one result word
+constexpr int kFlatWgPerCu = 32;        // k_flat with outputs (4 ... 64 were within 1 us)
+constexpr int kFlatAmaxWgPerCu = 2;     // k_flat as the amax pass of the Hadamard transform
+constexpr int kAmaxRhtColWgPerCu = 8;   // k_amax_rht_col
 
-// Streaming accesses: every input word is read once and every output byte written once,
-// so neither should displace anything in the caches (the `nt` forms of the memory
-// instructions); the knobs exist to measure that choice.
-#ifndef NVFP4_46_NT_LOAD
-#define NVFP4_46_NT_LOAD 0
-#endif
-#ifndef NVFP4_46_NT_STORE_CODES
-#define NVFP4_46_NT_STORE_CODES 0
-#endif
-#ifndef NVFP4_46_NT_STORE_BF16
-#define NVFP4_46_NT_STORE_BF16 1
-#endif
-constexpr bool kNtCodes = NVFP4_46_NT_STORE_CODES != 0;   // codes / scales / choice bytes
-constexpr bool kNtBf16 = NVFP4_46_NT_STORE_BF16 != 0;     // dequantized BF16 tensors
+// Streaming accesses.  Dequantized BF16 tensors are write-once streams and leave with
+// nontemporal stores (dequantize 45 -> 28 us per 8192 x 8192, and their write-back no
+// longer competes with the next kernel).  Codes, scales and choice bytes use ordinary
+// stores so that the consumer finds them in L2 / the memory-side cache (nontemporal
+// stores gain 1.5 us here and cost the following dequantize 4-5 us).  Loads are ordinary
+// (nontemporal loads are slower when x is cache-resident and neutral otherwise).
+constexpr bool kNtCodes = false;   // codes / scales / choice bytes
+constexpr bool kNtBf16 = true;     // dequantized BF16 tensors
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-NV_DEV uint4 load_stream(const uint4 *p) {
-#if NVFP4_46_NT_LOAD
-  u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
-  return make_uint4(v.x, v.y, v.z, v.w);
-#else
-  return *p;
-#endif
-}
+NV_DEV uint4 load_stream(const uint4 *p) { return *p; }
 template <bool NT>
 NV_DEV void store_as(uint4 *p, const uint4 &v) {
   if (NT) {
@@ -196,7 +177,7 @@ __global__ __launch_bounds__(kThreads) void k_amax_plain(const uint4 *__restrict
       }
     }
   };
-  constexpr int U = NVFP4_46_AMAX_UNROLL;
+  constexpr int U = kAmaxUnroll;
   const int64_t stride = (int64_t)gridDim.x * kThreads;
   int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   for (; i + (U - 1) * stride < n16; i += U * stride) {
@@ -217,9 +198,6 @@ __global__ __launch_bounds__(kThreads) void k_amax_plain(const uint4 *__restrict
 // column in registers.  The signs depend on the row only, so they are flipped in the packed
 // words; the factor 1/4 of the transform is applied once to the maximum (scaling by a power
 // of two is monotonic, so the maximum of the scaled values is the scaled maximum).
-#ifndef NVFP4_46_AMAX_RHT_COL_WG_PER_CU
-#define NVFP4_46_AMAX_RHT_COL_WG_PER_CU 8
-#endif
 template <bool XF32>
 __global__ __launch_bounds__(kThreads) void k_amax_rht_col(const uint4 *__restrict__ x,
                                                            int64_t row_blocks, int64_t pieces_per_row,
@@ -405,7 +383,7 @@ __global__ __launch_bounds__(kThreads) void k_dequant_flat(const uint32_t *__res
   const float alpha = *alpha_p;
   const int64_t stride = (int64_t)gridDim.x * kThreads;
   for (int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x; t < n8; t += stride) {
-    float dec = e4m3_decode_sw(scales[t >> 1]) * alpha;
+    float dec = e4m3_decode(scales[t >> 1]) * alpha;
     float D[8];
     dequant8(codes[t], dec, D);
     store_as<kNtBf16>(out + t, make_uint4(pack_bf16x2(D[0], D[1]), pack_bf16x2(D[2], D[3]),
@@ -416,14 +394,8 @@ __global__ __launch_bounds__(kThreads) void k_dequant_flat(const uint32_t *__res
 
 // ------------------------------------------------ columnwise / both (tiled)
 
-#ifndef NVFP4_46_TILE_ROWS
-#define NVFP4_46_TILE_ROWS 64
-#endif
-#ifndef NVFP4_46_TILE_COLS
-#define NVFP4_46_TILE_COLS 128
-#endif
-constexpr int TR = NVFP4_46_TILE_ROWS;   // tile rows    (multiple of 16)
-constexpr int TC = NVFP4_46_TILE_COLS;   // tile columns (multiple of 16)
+constexpr int TR = 64;    // tile rows    (multiple of 16)
+constexpr int TC = 128;   // tile columns (multiple of 16)
 constexpr int kRowBlocksPerTileRow = TC / 16;          // 16-element row blocks across a tile row
 constexpr int kRowBlocksPerTile = TR * TC / 16;
 constexpr int kRowBlocksPerLane = kRowBlocksPerTile / kThreads;
@@ -481,10 +453,7 @@ __global__ __launch_bounds__(kThreads) void k_tile(
 
   // Only columnwise codes wanted: nothing needs the tile in LDS -- a lane reads its two columns
   // straight from memory, a row at a time (a wave's load covers 256 contiguous bytes of a row).
-#ifndef NVFP4_46_TILE_DIRECT
-#define NVFP4_46_TILE_DIRECT 1
-#endif
-  constexpr bool kDirect = NVFP4_46_TILE_DIRECT && !WANT_ROW && OUT == kOutCodes;
+  constexpr bool kDirect = !WANT_ROW && OUT == kOutCodes;
 
   // ---- phase 1: global -> LDS (and the rowwise outputs on the way); the loads go out
   // before the scale table is built
@@ -675,7 +644,7 @@ __global__ __launch_bounds__(kThreads) void k_dequant_col(const uint8_t *__restr
     if (gc < cols && gr < rows) {
       const uint2 c = *reinterpret_cast<const uint2 *>(codes + gc * col_codes + (gr >> 1));
       const float dec =
-          e4m3_decode_sw(scales[(TILE2D ? (gc >> 4) : gc) * col_scales + (gr >> 4)]) * alpha;
+          e4m3_decode(scales[(TILE2D ? (gc >> 4) : gc) * col_scales + (gr >> 4)]) * alpha;
       float D[8];
       dequant8(c.x, dec, D);
 #pragma unroll
@@ -878,7 +847,7 @@ __global__ __launch_bounds__(kThreads) void k_dequant_2d(const uint32_t *__restr
   const int64_t stride = (int64_t)gridDim.x * kThreads;
   for (int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x; t < n8; t += stride) {
     const int64_t row = t / per_row, c8 = t - row * per_row;
-    const float dec = e4m3_decode_sw(scales[(row >> 4) * ncb + (c8 >> 1)]) * alpha;
+    const float dec = e4m3_decode(scales[(row >> 4) * ncb + (c8 >> 1)]) * alpha;
     float D[8];
     dequant8(codes[t], dec, D);
     store_as<kNtBf16>(out + t, make_uint4(pack_bf16x2(D[0], D[1]), pack_bf16x2(D[2], D[3]),
@@ -892,11 +861,7 @@ __global__ void k_dbg_e2m1_rtn(uint32_t first, int64_t n, uint8_t *out) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
     float y = u2f(first + (uint32_t)i);
-#if NVFP4_46_HW_FP4
     out[i] = (uint8_t)(hw_pk_fp4<0>(0u, y, 0.0f) & 15u);
-#else
-    out[i] = (uint8_t)e2m1_rtn_sw(y);
-#endif
   }
 }
 
@@ -913,7 +878,7 @@ __global__ void k_dbg_tables(float *out) {
     dequant8((uint32_t)t, 1.0f, D);     // code t in nibble 0
     out[t] = D[0];
   }
-  if (t < 256) out[16 + t] = e4m3_decode_sw((uint32_t)t & 0x7fu);
+  if (t < 256) out[16 + t] = e4m3_decode((uint32_t)t & 0x7fu);
 }
 
 __global__ void k_dbg_bf16(uint32_t first, uint32_t stride_bits, int64_t n, uint16_t *out) {
@@ -942,22 +907,28 @@ __global__ void k_dbg_philox(const uint32_t *ctr, uint32_t k0, uint32_t k1, int6
 
 // ---------------------------------------------------------------- launchers
 
+// Compute units of the device that is current for the calling thread, asked for on every
+// call (the library keeps no state, and two devices of one process may differ).
+static int compute_units() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+    cus = 256;
+  return cus;
+}
+
 static int grid_for(int64_t work_items, int per_cu) {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-      cus = prop.multiProcessorCount;
-    if (cus <= 0) cus = 256;
-  }
   int64_t need = (work_items + kThreads - 1) / kThreads;
-  int64_t cap = (int64_t)cus * per_cu;
+  int64_t cap = (int64_t)compute_units() * per_cu;
   if (need < 1) need = 1;
   return (int)(need < cap ? need : cap);
 }
 
-static int launch_status() { return hipGetLastError() == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP; }
+// every kernel of this file uses static LDS only
+template <typename Kernel, typename... Args>
+static int launch(Kernel kernel, dim3 grid, dim3 block, hipStream_t stream, Args... args) {
+  return launch(kernel, grid, block, (size_t)0, stream, args...);
+}
 
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -976,10 +947,10 @@ struct FlatArgs {
 };
 
 template <bool XF32, int ROUNDING, int SELECT, bool RHT, int OUT>
-static void launch_flat(const FlatArgs &a) {
+static int launch_flat(const FlatArgs &a) {
   // the amax pass ends with one access per workgroup to the one result word: fewer, longer-lived
   // workgroups than the passes that write their own outputs
-  int grid = grid_for(a.nblocks, OUT == kOutAmax ? NVFP4_46_FLAT_AMAX_WG_PER_CU : NVFP4_46_FLAT_WG_PER_CU);
+  int grid = grid_for(a.nblocks, OUT == kOutAmax ? kFlatAmaxWgPerCu : kFlatWgPerCu);
   if (RHT) {
     // round r of a workgroup starts at block 256*r; if 256*grid is a multiple of the
     // blocks per row, every lane sees one position along the row in all its rounds
@@ -988,30 +959,29 @@ static void launch_flat(const FlatArgs &a) {
     const int period = (int)(a.nb_per_row / g);
     if (period <= grid / 2) grid -= grid % period;
   }
-  hipLaunchKernelGGL((k_flat<XF32, ROUNDING, SELECT, RHT, OUT>), dim3(grid), dim3(kThreads), 0,
-                     a.stream, a.x, a.alpha, a.codes, a.scales, a.choice, a.out, a.amax,
-                     a.nblocks, a.nb_per_row, a.sr_seed, a.rht_seed);
+  return launch(k_flat<XF32, ROUNDING, SELECT, RHT, OUT>, dim3(grid), dim3(kThreads), a.stream, a.x,
+                a.alpha, a.codes, a.scales, a.choice, a.out, a.amax, a.nblocks, a.nb_per_row,
+                a.sr_seed, a.rht_seed);
 }
 
 template <bool XF32, int ROUNDING, int SELECT>
-static void launch_flat_variant(const FlatArgs &a, bool rht, int out) {
+static int launch_flat_variant(const FlatArgs &a, bool rht, int out) {
   if (out == kOutCodes) {
-    if (rht) launch_flat<XF32, ROUNDING, SELECT, true, kOutCodes>(a);
-    else launch_flat<XF32, ROUNDING, SELECT, false, kOutCodes>(a);
-  } else {
-    if (rht) launch_flat<XF32, ROUNDING, SELECT, true, kOutFake>(a);
-    else launch_flat<XF32, ROUNDING, SELECT, false, kOutFake>(a);
+    if (rht) return launch_flat<XF32, ROUNDING, SELECT, true, kOutCodes>(a);
+    return launch_flat<XF32, ROUNDING, SELECT, false, kOutCodes>(a);
   }
+  if (rht) return launch_flat<XF32, ROUNDING, SELECT, true, kOutFake>(a);
+  return launch_flat<XF32, ROUNDING, SELECT, false, kOutFake>(a);
 }
 
 // All rowwise kernels of one (input type, rounding mode) pair.
 template <bool XF32, int ROUNDING>
-void run_flat(const FlatArgs &a, uint32_t select, bool rht, int out) {
-  if (select == NVFP4_SEL_46_MSE) launch_flat_variant<XF32, ROUNDING, kSel46>(a, rht, out);
-  else if (select == NVFP4_SEL_FORCE6) launch_flat_variant<XF32, ROUNDING, kSelForce6>(a, rht, out);
-  else if (select == NVFP4_SEL_FORCE4) launch_flat_variant<XF32, ROUNDING, kSelForce4>(a, rht, out);
-  else if (select == NVFP4_SEL_46_MAE) launch_flat_variant<XF32, ROUNDING, kSel46Mae>(a, rht, out);
-  else launch_flat_variant<XF32, ROUNDING, kSel46AbsMax>(a, rht, out);
+int run_flat(const FlatArgs &a, uint32_t select, bool rht, int out) {
+  if (select == NVFP4_SEL_46_MSE) return launch_flat_variant<XF32, ROUNDING, kSel46>(a, rht, out);
+  if (select == NVFP4_SEL_FORCE6) return launch_flat_variant<XF32, ROUNDING, kSelForce6>(a, rht, out);
+  if (select == NVFP4_SEL_FORCE4) return launch_flat_variant<XF32, ROUNDING, kSelForce4>(a, rht, out);
+  if (select == NVFP4_SEL_46_MAE) return launch_flat_variant<XF32, ROUNDING, kSel46Mae>(a, rht, out);
+  return launch_flat_variant<XF32, ROUNDING, kSel46AbsMax>(a, rht, out);
 }
 
 struct TileArgs {
@@ -1031,34 +1001,34 @@ static int tile_grid(int64_t rows, int64_t cols) {
 }
 
 template <bool XF32, int ROUNDING, int SELECT, bool RHT, bool WANT_ROW, int OUT>
-static void launch_tile(const TileArgs &a) {
-  hipLaunchKernelGGL((k_tile<XF32, ROUNDING, SELECT, RHT, WANT_ROW, OUT>),
-                     dim3(tile_grid(a.rows, a.cols)), dim3(kThreads), 0, a.stream, a.x, a.alpha,
-                     a.codes_row, a.scales_row, a.choice_row, a.codes_col, a.scales_col,
-                     a.choice_col, a.out, a.rows, a.cols, a.sr_seed, a.rht_seed);
+static int launch_tile(const TileArgs &a) {
+  return launch(k_tile<XF32, ROUNDING, SELECT, RHT, WANT_ROW, OUT>, dim3(tile_grid(a.rows, a.cols)),
+                dim3(kThreads), a.stream, a.x, a.alpha, a.codes_row, a.scales_row, a.choice_row,
+                a.codes_col, a.scales_col, a.choice_col, a.out, a.rows, a.cols, a.sr_seed,
+                a.rht_seed);
 }
 
 // variant: 0 = columnwise codes, 1 = columnwise codes + rht, 2 = both orientations,
 //          3 = columnwise fake-quant, 4 = columnwise fake-quant + rht
 template <bool XF32, int ROUNDING, int SELECT>
-static void launch_tile_variant(const TileArgs &a, int variant) {
+static int launch_tile_variant(const TileArgs &a, int variant) {
   switch (variant) {
-    case 0: launch_tile<XF32, ROUNDING, SELECT, false, false, kOutCodes>(a); break;
-    case 1: launch_tile<XF32, ROUNDING, SELECT, true, false, kOutCodes>(a); break;
-    case 2: launch_tile<XF32, ROUNDING, SELECT, false, true, kOutCodes>(a); break;
-    case 3: launch_tile<XF32, ROUNDING, SELECT, false, false, kOutFake>(a); break;
-    default: launch_tile<XF32, ROUNDING, SELECT, true, false, kOutFake>(a); break;
+    case 0: return launch_tile<XF32, ROUNDING, SELECT, false, false, kOutCodes>(a);
+    case 1: return launch_tile<XF32, ROUNDING, SELECT, true, false, kOutCodes>(a);
+    case 2: return launch_tile<XF32, ROUNDING, SELECT, false, true, kOutCodes>(a);
+    case 3: return launch_tile<XF32, ROUNDING, SELECT, false, false, kOutFake>(a);
+    default: return launch_tile<XF32, ROUNDING, SELECT, true, false, kOutFake>(a);
   }
 }
 
 // All tiled (columnwise / both) kernels of one (input type, rounding mode) pair.
 template <bool XF32, int ROUNDING>
-void run_tile(const TileArgs &a, uint32_t select, int variant) {
-  if (select == NVFP4_SEL_46_MSE) launch_tile_variant<XF32, ROUNDING, kSel46>(a, variant);
-  else if (select == NVFP4_SEL_FORCE6) launch_tile_variant<XF32, ROUNDING, kSelForce6>(a, variant);
-  else if (select == NVFP4_SEL_FORCE4) launch_tile_variant<XF32, ROUNDING, kSelForce4>(a, variant);
-  else if (select == NVFP4_SEL_46_MAE) launch_tile_variant<XF32, ROUNDING, kSel46Mae>(a, variant);
-  else launch_tile_variant<XF32, ROUNDING, kSel46AbsMax>(a, variant);
+int run_tile(const TileArgs &a, uint32_t select, int variant) {
+  if (select == NVFP4_SEL_46_MSE) return launch_tile_variant<XF32, ROUNDING, kSel46>(a, variant);
+  if (select == NVFP4_SEL_FORCE6) return launch_tile_variant<XF32, ROUNDING, kSelForce6>(a, variant);
+  if (select == NVFP4_SEL_FORCE4) return launch_tile_variant<XF32, ROUNDING, kSelForce4>(a, variant);
+  if (select == NVFP4_SEL_46_MAE) return launch_tile_variant<XF32, ROUNDING, kSel46Mae>(a, variant);
+  return launch_tile_variant<XF32, ROUNDING, kSel46AbsMax>(a, variant);
 }
 
 struct Block2dArgs {
@@ -1073,34 +1043,34 @@ struct Block2dArgs {
 };
 
 template <bool XF32, int ROUNDING, int SELECT>
-static void launch_block2d(const Block2dArgs &a, int out) {
+static int launch_block2d(const Block2dArgs &a, int out) {
   const int64_t tiles = (a.rows / 16) * (a.cols / 16);
   const int grid = grid_for(tiles * 16, 16);
   auto go = [&](auto kernel) {
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), 0, a.stream, a.x, a.alpha, a.codes,
-                       a.scales, a.choice, a.codes_col, a.scales_col, a.choice_col, a.out, a.rows,
-                       a.cols, a.sr_seed);
+    return launch(kernel, dim3(grid), dim3(kThreads), a.stream, a.x, a.alpha, a.codes, a.scales,
+                  a.choice, a.codes_col, a.scales_col, a.choice_col, a.out, a.rows, a.cols,
+                  a.sr_seed);
   };
-  if (out == kOutCodes) go(k_block2d<XF32, ROUNDING, SELECT, kOutCodes>);
-  else go(k_block2d<XF32, ROUNDING, SELECT, kOutFake>);
+  if (out == kOutCodes) return go(k_block2d<XF32, ROUNDING, SELECT, kOutCodes>);
+  return go(k_block2d<XF32, ROUNDING, SELECT, kOutFake>);
 }
 
 // All 16x16-tile kernels of one (input type, rounding mode) pair.
 template <bool XF32, int ROUNDING>
-void run_block2d(const Block2dArgs &a, uint32_t select, int out) {
-  if (select == NVFP4_SEL_46_MSE) launch_block2d<XF32, ROUNDING, kSel46>(a, out);
-  else if (select == NVFP4_SEL_FORCE6) launch_block2d<XF32, ROUNDING, kSelForce6>(a, out);
-  else if (select == NVFP4_SEL_FORCE4) launch_block2d<XF32, ROUNDING, kSelForce4>(a, out);
-  else if (select == NVFP4_SEL_46_MAE) launch_block2d<XF32, ROUNDING, kSel46Mae>(a, out);
-  else launch_block2d<XF32, ROUNDING, kSel46AbsMax>(a, out);
+int run_block2d(const Block2dArgs &a, uint32_t select, int out) {
+  if (select == NVFP4_SEL_46_MSE) return launch_block2d<XF32, ROUNDING, kSel46>(a, out);
+  if (select == NVFP4_SEL_FORCE6) return launch_block2d<XF32, ROUNDING, kSelForce6>(a, out);
+  if (select == NVFP4_SEL_FORCE4) return launch_block2d<XF32, ROUNDING, kSelForce4>(a, out);
+  if (select == NVFP4_SEL_46_MAE) return launch_block2d<XF32, ROUNDING, kSel46Mae>(a, out);
+  return launch_block2d<XF32, ROUNDING, kSel46AbsMax>(a, out);
 }
 
 // One group of kernels = the three run_* templates for one (XF32, ROUNDING) pair.  A part
 // that holds a group defines it; the main part, when built apart, only declares them.
 #define NVFP4_46_GROUP(KEYWORD, XF32, ROUNDING)                                                 \
-  KEYWORD template void run_flat<XF32, ROUNDING>(const FlatArgs &, uint32_t, bool, int);        \
-  KEYWORD template void run_tile<XF32, ROUNDING>(const TileArgs &, uint32_t, int);              \
-  KEYWORD template void run_block2d<XF32, ROUNDING>(const Block2dArgs &, uint32_t, int);
+  KEYWORD template int run_flat<XF32, ROUNDING>(const FlatArgs &, uint32_t, bool, int);         \
+  KEYWORD template int run_tile<XF32, ROUNDING>(const TileArgs &, uint32_t, int);               \
+  KEYWORD template int run_block2d<XF32, ROUNDING>(const Block2dArgs &, uint32_t, int);
 #if NVFP4_46_PART == 0
 NVFP4_46_GROUP(extern, false, kRTN)
 NVFP4_46_GROUP(extern, false, kSR)
@@ -1118,28 +1088,28 @@ static int rounding_index(uint32_t rounding) {
   return rounding == NVFP4_SR ? kSR : rounding == NVFP4_SR_AFTER_RTN_SELECT ? kSRAfterRtnSelect : kRTN;
 }
 
-static void dispatch_flat(const FlatArgs &a, uint32_t rounding, uint32_t select, bool rht, int out) {
-  typedef void (*Fn)(const FlatArgs &, uint32_t, bool, int);
+static int dispatch_flat(const FlatArgs &a, uint32_t rounding, uint32_t select, bool rht, int out) {
+  typedef int (*Fn)(const FlatArgs &, uint32_t, bool, int);
   static const Fn table[2][3] = {
       {run_flat<false, kRTN>, run_flat<false, kSR>, run_flat<false, kSRAfterRtnSelect>},
       {run_flat<true, kRTN>, run_flat<true, kSR>, run_flat<true, kSRAfterRtnSelect>}};
-  table[a.xf32][rounding_index(rounding)](a, select, rht, out);
+  return table[a.xf32][rounding_index(rounding)](a, select, rht, out);
 }
 
-static void dispatch_tile(const TileArgs &a, uint32_t rounding, uint32_t select, int variant) {
-  typedef void (*Fn)(const TileArgs &, uint32_t, int);
+static int dispatch_tile(const TileArgs &a, uint32_t rounding, uint32_t select, int variant) {
+  typedef int (*Fn)(const TileArgs &, uint32_t, int);
   static const Fn table[2][3] = {
       {run_tile<false, kRTN>, run_tile<false, kSR>, run_tile<false, kSRAfterRtnSelect>},
       {run_tile<true, kRTN>, run_tile<true, kSR>, run_tile<true, kSRAfterRtnSelect>}};
-  table[a.xf32][rounding_index(rounding)](a, select, variant);
+  return table[a.xf32][rounding_index(rounding)](a, select, variant);
 }
 
-static void dispatch_block2d(const Block2dArgs &a, uint32_t rounding, uint32_t select, int out) {
-  typedef void (*Fn)(const Block2dArgs &, uint32_t, int);
+static int dispatch_block2d(const Block2dArgs &a, uint32_t rounding, uint32_t select, int out) {
+  typedef int (*Fn)(const Block2dArgs &, uint32_t, int);
   static const Fn table[2][3] = {
       {run_block2d<false, kRTN>, run_block2d<false, kSR>, run_block2d<false, kSRAfterRtnSelect>},
       {run_block2d<true, kRTN>, run_block2d<true, kSR>, run_block2d<true, kSRAfterRtnSelect>}};
-  table[a.xf32][rounding_index(rounding)](a, select, out);
+  return table[a.xf32][rounding_index(rounding)](a, select, out);
 }
 
 // Checks shared by the entry points that take the parameter block.
@@ -1183,37 +1153,33 @@ int nvfp4_46_tensor_scale(const void *x, const nvfp4_46_params *p, float *alpha,
   if (rc != NVFP4_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   uint32_t *amax = reinterpret_cast<uint32_t *>(alpha);
-  hipLaunchKernelGGL(k_store_u32, dim3(1), dim3(1), 0, s, amax, 0u);
+  rc = launch(k_store_u32, dim3(1), dim3(1), s, amax, 0u);
+  if (rc != NVFP4_OK) return rc;
   const int64_t n = p->rows * p->cols;
   const bool xf32 = p->x_dtype == NVFP4_X_F32;
+  const uint4 *x4 = static_cast<const uint4 *>(x);
   if (!p->rht) {
     // 128-bit pieces (n is a multiple of 8 by the shape checks)
     const int64_t n16 = xf32 ? n / 4 : n / 8;
-    const dim3 grid(grid_for(n16, NVFP4_46_AMAX_WG_PER_CU));
-    if (xf32)
-      hipLaunchKernelGGL(k_amax_plain<true>, grid, dim3(kThreads), 0, s,
-                         static_cast<const uint4 *>(x), n16, amax);
-    else
-      hipLaunchKernelGGL(k_amax_plain<false>, grid, dim3(kThreads), 0, s,
-                         static_cast<const uint4 *>(x), n16, amax);
+    const dim3 grid(grid_for(n16, kAmaxWgPerCu));
+    rc = xf32 ? launch(k_amax_plain<true>, grid, dim3(kThreads), s, x4, n16, amax)
+              : launch(k_amax_plain<false>, grid, dim3(kThreads), s, x4, n16, amax);
   } else if (p->layout == NVFP4_ROWWISE) {
-    FlatArgs a{xf32, static_cast<const uint4 *>(x), nullptr, nullptr, nullptr, nullptr, nullptr, amax,
+    FlatArgs a{xf32, x4, nullptr, nullptr, nullptr, nullptr, nullptr, amax,
                n / 16, (uint32_t)(p->cols / 16), 0, p->rht_seed, s};
-    if (xf32) launch_flat<true, kRTN, kSel46, true, kOutAmax>(a);
-    else launch_flat<false, kRTN, kSel46, true, kOutAmax>(a);
+    rc = xf32 ? launch_flat<true, kRTN, kSel46, true, kOutAmax>(a)
+              : launch_flat<false, kRTN, kSel46, true, kOutAmax>(a);
   } else {
     // columnwise blocks (rows % 16 == 0, cols % 8 == 0): 16-byte pieces of 8 BF16 / 4 fp32 columns
     const int64_t row_blocks = p->rows / 16, pieces = xf32 ? p->cols / 4 : p->cols / 8;
-    const dim3 grid(grid_for(row_blocks * pieces, NVFP4_46_AMAX_RHT_COL_WG_PER_CU));
-    if (xf32)
-      hipLaunchKernelGGL(k_amax_rht_col<true>, grid, dim3(kThreads), 0, s,
-                         static_cast<const uint4 *>(x), row_blocks, pieces, p->rht_seed, amax);
-    else
-      hipLaunchKernelGGL(k_amax_rht_col<false>, grid, dim3(kThreads), 0, s,
-                         static_cast<const uint4 *>(x), row_blocks, pieces, p->rht_seed, amax);
+    const dim3 grid(grid_for(row_blocks * pieces, kAmaxRhtColWgPerCu));
+    rc = xf32 ? launch(k_amax_rht_col<true>, grid, dim3(kThreads), s, x4, row_blocks, pieces,
+                       p->rht_seed, amax)
+              : launch(k_amax_rht_col<false>, grid, dim3(kThreads), s, x4, row_blocks, pieces,
+                       p->rht_seed, amax);
   }
-  hipLaunchKernelGGL(k_finish_alpha, dim3(1), dim3(1), 0, s, alpha, p->fp8_max);
-  return launch_status();
+  if (rc != NVFP4_OK) return rc;
+  return launch(k_finish_alpha, dim3(1), dim3(1), s, alpha, p->fp8_max);
 }
 
 int nvfp4_46_quantize(const void *x, const nvfp4_46_params *p, const float *alpha,
@@ -1237,23 +1203,20 @@ int nvfp4_46_quantize(const void *x, const nvfp4_46_params *p, const float *alph
                   static_cast<uint8_t *>(scales_row), static_cast<uint8_t *>(choice_row),
                   static_cast<uint8_t *>(codes_col), static_cast<uint8_t *>(scales_col),
                   static_cast<uint8_t *>(choice_col), nullptr, p->rows, p->cols, p->sr_seed, s};
-    dispatch_block2d(a, p->rounding, p->select, kOutCodes);
-    return launch_status();
+    return dispatch_block2d(a, p->rounding, p->select, kOutCodes);
   }
   if (!want_col) {
     FlatArgs a{xf32, static_cast<const uint4 *>(x), alpha, static_cast<uint2 *>(codes_row),
                static_cast<uint8_t *>(scales_row), static_cast<uint8_t *>(choice_row), nullptr,
                nullptr, p->rows * p->cols / 16, (uint32_t)(p->cols / 16), p->sr_seed, p->rht_seed, s};
-    dispatch_flat(a, p->rounding, p->select, p->rht != 0, kOutCodes);
-  } else {
-    TileArgs a{xf32, x, alpha, static_cast<uint8_t *>(codes_row),
-               static_cast<uint8_t *>(scales_row), static_cast<uint8_t *>(choice_row),
-               static_cast<uint8_t *>(codes_col), static_cast<uint8_t *>(scales_col),
-               static_cast<uint8_t *>(choice_col), nullptr, p->rows, p->cols, p->sr_seed,
-               p->rht_seed, s};
-    dispatch_tile(a, p->rounding, p->select, want_row ? 2 : (p->rht ? 1 : 0));
+    return dispatch_flat(a, p->rounding, p->select, p->rht != 0, kOutCodes);
   }
-  return launch_status();
+  TileArgs a{xf32, x, alpha, static_cast<uint8_t *>(codes_row),
+             static_cast<uint8_t *>(scales_row), static_cast<uint8_t *>(choice_row),
+             static_cast<uint8_t *>(codes_col), static_cast<uint8_t *>(scales_col),
+             static_cast<uint8_t *>(choice_col), nullptr, p->rows, p->cols, p->sr_seed,
+             p->rht_seed, s};
+  return dispatch_tile(a, p->rounding, p->select, want_row ? 2 : (p->rht ? 1 : 0));
 }
 
 int nvfp4_46_dequantize(const void *codes, const void *scales, const float *alpha, int64_t rows,
@@ -1270,26 +1233,21 @@ int nvfp4_46_dequantize(const void *codes, const void *scales, const float *alph
     return NVFP4_ERR_SHAPE;
   if (!aligned16(codes) || !aligned16(scales) || !aligned16(out_bf16)) return NVFP4_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (layout == NVFP4_BLOCK2D) {
-    const int64_t n8 = rows * cols / 8;
-    hipLaunchKernelGGL(k_dequant_2d, dim3(grid_for(n8, 16)), dim3(kThreads), 0, s,
-                       static_cast<const uint32_t *>(codes), static_cast<const uint8_t *>(scales),
-                       alpha, static_cast<uint4 *>(out_bf16), n8, cols);
-  } else if (layout == NVFP4_ROWWISE) {
-    const int64_t n8 = rows * cols / 8;
-    hipLaunchKernelGGL(k_dequant_flat, dim3(grid_for(n8, 16)), dim3(kThreads), 0, s,
-                       static_cast<const uint32_t *>(codes), static_cast<const uint8_t *>(scales),
-                       alpha, static_cast<uint4 *>(out_bf16), n8);
-  } else if (layout == NVFP4_COLWISE) {
-    hipLaunchKernelGGL(k_dequant_col<false>, dim3(tile_grid(rows, cols)), dim3(kThreads), 0, s,
-                       static_cast<const uint8_t *>(codes), static_cast<const uint8_t *>(scales),
-                       alpha, static_cast<uint16_t *>(out_bf16), rows, cols);
-  } else {
-    hipLaunchKernelGGL(k_dequant_col<true>, dim3(tile_grid(rows, cols)), dim3(kThreads), 0, s,
-                       static_cast<const uint8_t *>(codes), static_cast<const uint8_t *>(scales),
-                       alpha, static_cast<uint16_t *>(out_bf16), rows, cols);
-  }
-  return launch_status();
+  const uint8_t *c8 = static_cast<const uint8_t *>(codes), *s8 = static_cast<const uint8_t *>(scales);
+  const int64_t n8 = rows * cols / 8;
+  if (layout == NVFP4_BLOCK2D)
+    return launch(k_dequant_2d, dim3(grid_for(n8, 16)), dim3(kThreads), s,
+                  static_cast<const uint32_t *>(codes), s8, alpha, static_cast<uint4 *>(out_bf16),
+                  n8, cols);
+  if (layout == NVFP4_ROWWISE)
+    return launch(k_dequant_flat, dim3(grid_for(n8, 16)), dim3(kThreads), s,
+                  static_cast<const uint32_t *>(codes), s8, alpha, static_cast<uint4 *>(out_bf16),
+                  n8);
+  if (layout == NVFP4_COLWISE)
+    return launch(k_dequant_col<false>, dim3(tile_grid(rows, cols)), dim3(kThreads), s, c8, s8,
+                  alpha, static_cast<uint16_t *>(out_bf16), rows, cols);
+  return launch(k_dequant_col<true>, dim3(tile_grid(rows, cols)), dim3(kThreads), s, c8, s8, alpha,
+                static_cast<uint16_t *>(out_bf16), rows, cols);
 }
 
 int nvfp4_46_fake_quant(const void *x, const nvfp4_46_params *p, const float *alpha,
@@ -1303,21 +1261,18 @@ int nvfp4_46_fake_quant(const void *x, const nvfp4_46_params *p, const float *al
   if (p->block2d) {
     Block2dArgs a{xf32, x, alpha, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
                   static_cast<uint16_t *>(out_bf16), p->rows, p->cols, p->sr_seed, s};
-    dispatch_block2d(a, p->rounding, p->select, kOutFake);
-    return launch_status();
+    return dispatch_block2d(a, p->rounding, p->select, kOutFake);
   }
   if (p->layout == NVFP4_ROWWISE) {
     FlatArgs a{xf32, static_cast<const uint4 *>(x), alpha, nullptr, nullptr, nullptr,
                static_cast<uint4 *>(out_bf16), nullptr, p->rows * p->cols / 16,
                (uint32_t)(p->cols / 16), p->sr_seed, p->rht_seed, s};
-    dispatch_flat(a, p->rounding, p->select, p->rht != 0, kOutFake);
-  } else {
-    TileArgs a{xf32, x, alpha, nullptr, nullptr, nullptr, nullptr,
-               nullptr, nullptr, static_cast<uint16_t *>(out_bf16), p->rows, p->cols,
-               p->sr_seed, p->rht_seed, s};
-    dispatch_tile(a, p->rounding, p->select, p->rht ? 4 : 3);
+    return dispatch_flat(a, p->rounding, p->select, p->rht != 0, kOutFake);
   }
-  return launch_status();
+  TileArgs a{xf32, x, alpha, nullptr, nullptr, nullptr, nullptr,
+             nullptr, nullptr, static_cast<uint16_t *>(out_bf16), p->rows, p->cols,
+             p->sr_seed, p->rht_seed, s};
+  return dispatch_tile(a, p->rounding, p->select, p->rht ? 4 : 3);
 }
 
 const char *nvfp4_46_status_string(int status) {
@@ -1336,51 +1291,45 @@ const char *nvfp4_46_status_string(int status) {
 int nvfp4_46_debug_e2m1_rtn_range(uint32_t first_bits, int64_t n, void *out_u8, void *stream) {
   if (!out_u8) return NVFP4_ERR_NULL;
   if (n <= 0) return NVFP4_ERR_SHAPE;
-  hipLaunchKernelGGL(k_dbg_e2m1_rtn, dim3(grid_for(n, 8)), dim3(kThreads), 0,
-                     static_cast<hipStream_t>(stream), first_bits, n, static_cast<uint8_t *>(out_u8));
-  return launch_status();
+  return launch(k_dbg_e2m1_rtn, dim3(grid_for(n, 8)), dim3(kThreads),
+                static_cast<hipStream_t>(stream), first_bits, n, static_cast<uint8_t *>(out_u8));
 }
 
 int nvfp4_46_debug_e4m3_range(uint32_t first_bits, int64_t n, void *out_u8, void *stream) {
   if (!out_u8) return NVFP4_ERR_NULL;
   if (n <= 0) return NVFP4_ERR_SHAPE;
-  hipLaunchKernelGGL(k_dbg_e4m3, dim3(grid_for(n, 8)), dim3(kThreads), 0,
-                     static_cast<hipStream_t>(stream), first_bits, n, static_cast<uint8_t *>(out_u8));
-  return launch_status();
+  return launch(k_dbg_e4m3, dim3(grid_for(n, 8)), dim3(kThreads),
+                static_cast<hipStream_t>(stream), first_bits, n, static_cast<uint8_t *>(out_u8));
 }
 
 int nvfp4_46_debug_decode_tables(void *out_f32, void *stream) {
   if (!out_f32) return NVFP4_ERR_NULL;
-  hipLaunchKernelGGL(k_dbg_tables, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream),
-                     static_cast<float *>(out_f32));
-  return launch_status();
+  return launch(k_dbg_tables, dim3(1), dim3(256), static_cast<hipStream_t>(stream),
+                static_cast<float *>(out_f32));
 }
 
 int nvfp4_46_debug_bf16_range(uint32_t first_bits, uint32_t stride, int64_t n, void *out_u16,
                               void *stream) {
   if (!out_u16) return NVFP4_ERR_NULL;
   if (n <= 0) return NVFP4_ERR_SHAPE;
-  hipLaunchKernelGGL(k_dbg_bf16, dim3(grid_for(n, 8)), dim3(kThreads), 0,
-                     static_cast<hipStream_t>(stream), first_bits, stride, n,
-                     static_cast<uint16_t *>(out_u16));
-  return launch_status();
+  return launch(k_dbg_bf16, dim3(grid_for(n, 8)), dim3(kThreads),
+                static_cast<hipStream_t>(stream), first_bits, stride, n,
+                static_cast<uint16_t *>(out_u16));
 }
 
 int nvfp4_46_debug_e2m1_sr(const float *y, const float *u, int64_t n, void *out_u8, void *stream) {
   if (!y || !u || !out_u8) return NVFP4_ERR_NULL;
   if (n <= 0) return NVFP4_ERR_SHAPE;
-  hipLaunchKernelGGL(k_dbg_e2m1_sr, dim3(grid_for(n, 8)), dim3(kThreads), 0,
-                     static_cast<hipStream_t>(stream), y, u, n, static_cast<uint8_t *>(out_u8));
-  return launch_status();
+  return launch(k_dbg_e2m1_sr, dim3(grid_for(n, 8)), dim3(kThreads),
+                static_cast<hipStream_t>(stream), y, u, n, static_cast<uint8_t *>(out_u8));
 }
 
 int nvfp4_46_debug_philox(const uint32_t *ctr, uint32_t key0, uint32_t key1, int64_t n,
                           uint32_t *out, void *stream) {
   if (!ctr || !out) return NVFP4_ERR_NULL;
   if (n <= 0) return NVFP4_ERR_SHAPE;
-  hipLaunchKernelGGL(k_dbg_philox, dim3(grid_for(n, 8)), dim3(kThreads), 0,
-                     static_cast<hipStream_t>(stream), ctr, key0, key1, n, out);
-  return launch_status();
+  return launch(k_dbg_philox, dim3(grid_for(n, 8)), dim3(kThreads),
+                static_cast<hipStream_t>(stream), ctr, key0, key1, n, out);
 }
 
 }  // extern "C"

@@ -21,7 +21,7 @@ def _declared():
 def test_library_exports_every_declared_symbol():
     L = B.lib()
     names = _declared()
-    assert len(names) == 13
+    assert len(names) == 12
     assert sorted(B.EXPORTS) == names
     for n in names:
         assert hasattr(L, n), n
@@ -108,9 +108,6 @@ def test_other_entry_points_validation_codes():
     L = B.lib()
     assert L.nvfp4_46_debug_e2m1_rtn_range(0, 16, None, None) == 1
     assert L.nvfp4_46_debug_e4m3_range(0, 0, C.c_void_p(P), None) == 2
-    assert L.nvfp4_46_debug_valu_rate(0, 1, None, None) == 1
-    assert L.nvfp4_46_debug_valu_rate(len(B.VALU_RATE_KINDS), 1, C.c_void_p(P), None) == 4
-    assert L.nvfp4_46_debug_valu_rate(0, 0, C.c_void_p(P), None) == 4
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
