@@ -187,17 +187,38 @@ NV_DEV float exact_error(const float (&v)[16], uint32_t lo, uint32_t hi, float d
 // the defined one.
 //
 // Bound used (u = 2^-24, S = sum of the exact real squares t_i^2, t_i = g_i*dec - v_i,
-// |g_i| <= 6, m = max(dec^2, S)):
+// |g_i| <= 6, m = max(dec^2, S)), first for operations that do not underflow:
 //   defined value E:  D_i carries a relative error u, d_i another, so d_i = t_i + eps_i
 //     with |eps_i| <= u(6 dec + |t_i|)(1+u); squaring and summing 16 terms through a
 //     4-level tree (and sum|t_i| <= 4 sqrt(S), dec sqrt(S) <= m) gives
 //     |E - S| <= 48.1 u m + 7.1 u S;
 //   estimate E':  one rounding in d', at most 9 more per term in the accumulation:
 //     |E' - S| <= 18.1 u S.
-// Hence |E - E'| <= 48.1 u m + 25.2 u S < tol := 64 u (max(dec^2, E') + E').  If
-// |E4' - E6'| > tol4 + tol6 the order of E4 and E6 is the order of the estimates.
+// Hence |E - E'| <= 48.1 u m + 25.2 u S < 64 u (max(dec^2, E') + E').
+// Underflow adds absolute errors that no relative bound covers: the contract keeps
+// dec >= 2^-109, so products g*dec and the differences are never inexact for being small,
+// but each of the 16 squares of the defined value and each of the 16 accumulation steps of
+// the estimate may round in the subnormal range, by at most 2^-150 each: 2^-145 per
+// candidate.  The tolerance therefore carries the absolute term 2^-126 (which also covers
+// dec*dec or the tolerance's own products flushing towards zero):
+//   tol := 64 u (max(dec6^2, E6') + E6' + max(dec4^2, E4') + E4') + 2^-126.
+// If |E4' - E6'| > tol the order of E4 and E6 is the order of the estimates; tensors so
+// small that all squared errors lie below 2^-126 always take the defined path.
 // Overflowed (infinite / NaN) estimates fail the test and take the exact path.
-//
+NV_DEV float decision_tolerance(float m6, float E6p, float m4, float E4p) {
+  return __builtin_fmaf(0x1p-18f, (fmaxf(m6, E6p) + E6p) + (fmaxf(m4, E4p) + E4p), 0x1p-126f);
+}
+
+// The same for a 16x16 tile whose error is the sum of its sixteen row errors (each row an
+// estimate as above, E6t and E4t their sums in the fixed order): each row estimate is within
+// 2^-18 (max(dec^2, E'r) + E'r) + 2^-145 of the row's defined error, so the tile sums differ
+// from the defined tile errors by less than 2^-18 (16 dec^2 + 2 E't) + 2^-141 plus the
+// rounding of two 16-term trees (< 2^-20 E't).
+NV_DEV float tile_decision_tolerance(float dec6, float E6t, float dec4, float E4t) {
+  return __builtin_fmaf(0x1p-18f, (16.0f * dec6 * dec6 + 3.0f * E6t) + (16.0f * dec4 * dec4 + 3.0f * E4t),
+                        0x1p-126f);
+}
+
 // Exact ties are common and must not pay for the exact path: a block whose maximum is an
 // outlier quantizes every other element to zero under both scalings, and then the two
 // candidates dequantize to the very same values.  same_dequantized() recognises the two
@@ -220,7 +241,7 @@ NV_DEV bool same_dequantized(uint32_t lo6, uint32_t hi6, uint32_t lo4, uint32_t 
 
 NV_DEV bool decide_four(const float (&v)[16], float E6p, float E4p, float dec6, float dec4,
                         uint32_t lo6, uint32_t hi6, uint32_t lo4, uint32_t hi4) {
-  const float tol = 0x1p-18f * ((fmaxf(dec6 * dec6, E6p) + E6p) + (fmaxf(dec4 * dec4, E4p) + E4p));
+  const float tol = decision_tolerance(dec6 * dec6, E6p, dec4 * dec4, E4p);
   const float diff = E4p - E6p;
   bool four = diff < 0.0f;
   if (!(fabsf(diff) > tol)) {

@@ -783,14 +783,12 @@ __global__ __launch_bounds__(kThreads) void k_block2d(
       over_tile(E6, E4);      // evaluated as defined
       four = E4 < E6;
     } else if (SELECT == kSel46) {
-      // E6, E4 are row estimates (see decide_four): each within 2^-18 (max(dec^2, E') + E') of
-      // the row's defined error, so the tile sums differ from the defined tile errors by less
-      // than 2^-18 (16 dec^2 + 2 E't) plus the rounding of two 16-term trees (< 2^-20 E't).
-      // Outside that margin the estimates order the defined errors; inside it the defined
-      // errors are evaluated.  All sixteen lanes hold the same sums and take the same path.
+      // E6, E4 are row estimates (see decide_four).  Outside the margin of
+      // tile_decision_tolerance() the summed estimates order the defined errors; inside it
+      // the defined errors are evaluated.  All sixteen lanes hold the same sums and take the
+      // same path.
       over_tile(E6, E4);
-      const float tol = 0x1p-18f * ((16.0f * r6.dec * r6.dec + 3.0f * E6) +
-                                    (16.0f * r4.dec * r4.dec + 3.0f * E4));
+      const float tol = tile_decision_tolerance(r6.dec, E6, r4.dec, E4);
       const float diff = E4 - E6;
       four = diff < 0.0f;
       if (!(fabsf(diff) > tol)) {

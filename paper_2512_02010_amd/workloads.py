@@ -214,6 +214,14 @@ def adversarial(kind: str, rows: int = 32, cols: int = 64,
         x = torch.where((pat == 4).unsqueeze(-1), torch.ones(16) * 0.75, x)
         x = torch.where((pat == 5).unsqueeze(-1), 0.3 * noise, x)
         x = (x * mag.unsqueeze(-1)).reshape(rows, cols)
+    elif kind == "sq_underflow_stress":
+        # the near-tie patterns of "decision_stress" at those magnitudes
+        return (adversarial("decision_stress", rows, cols, torch.float32) * 2.0 ** -62).to(dtype).contiguous()
+    elif kind.startswith("sq_underflow_"):
+        # magnitudes at which the squared errors of a block fall into the fp32 subnormal
+        # range (max|x| around 2^-58 ... 2^-72) without all of them underflowing to zero
+        e = int(kind.rsplit("_", 1)[1])
+        x = _normal((rows, cols), g) * 2.0 ** -e
     elif kind == "bf16_small":
         x = _normal((rows, cols), g) * 1.0e-24
     elif kind == "bf16_large":
@@ -225,4 +233,6 @@ def adversarial(kind: str, rows: int = 32, cols: int = 64,
 
 ADVERSARIAL_KINDS = ("zeros", "neg_zeros", "constant", "neg_constant", "one_hot",
                      "one_hot_per_block", "tiny", "wide_range", "grid_exact", "ties",
-                     "bf16_small", "bf16_large")
+                     "bf16_small", "bf16_large", "sq_underflow_60", "sq_underflow_66",
+                     "sq_underflow_70", "sq_underflow_72", "sq_underflow_74",
+                     "sq_underflow_stress")

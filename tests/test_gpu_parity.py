@@ -112,6 +112,25 @@ def test_option_matrix(layout, select, rounding, rht):
                tag="c5-matrix")
 
 
+UNDERFLOW_KINDS = [k for k in wl.ADVERSARIAL_KINDS if k.startswith("sq_underflow")]
+
+
+@pytest.mark.parametrize("kind", UNDERFLOW_KINDS)
+@pytest.mark.parametrize("rounding,rht", [(B.RTN, 0), (B.SR, 0), (B.SR_AFTER_RTN_SELECT, 0),
+                                          (B.RTN, 1), (B.SR, 1)])
+def test_option_matrix_where_squared_errors_are_subnormal(kind, rounding, rht):
+    """max|x| around 2^-58 ... 2^-72: the squared errors of Table 3 lines 6 / 12 are fp32
+    subnormals (not all zero), so the 4-vs-6 decision rests on subnormal arithmetic and the
+    kernel's error estimates are worthless there -- it has to evaluate the defined errors."""
+    for dt in (torch.bfloat16, torch.float32):
+        x = wl.adversarial(kind, 64, 256, dtype=dt)
+        for layout in (B.ROWWISE, B.COLWISE):
+            out = check_case(x, layout=layout, rounding=rounding, rht=rht, tag=f"{kind}-{dt}")
+        if kind in ("sq_underflow_60", "sq_underflow_66", "sq_underflow_70", "sq_underflow_72"):
+            sfx = "row" if layout == B.ROWWISE else "col"
+            assert 0.05 < float(_np(out[f"choice_{sfx}"]).mean()) < 0.95
+
+
 @pytest.mark.parametrize("rounding", [B.RTN, B.SR])
 def test_both_layouts_with_sr(rounding):
     check_case(wl.make("c3", 144, 272), layout=B.BOTH, rounding=rounding, tag="c3-both")
@@ -173,10 +192,14 @@ def test_sr_after_rtn_selection(name, layout):
 @pytest.mark.parametrize("rounding", [B.RTN, B.SR, B.SR_AFTER_RTN_SELECT])
 def test_block2d_matches_oracle(select, rounding):
     """One scale per 16x16 tile (the weight quantization named in Section 4.1)."""
-    for name, shape in (("c2", (272, 400)), ("c4", (1024, 1024))):
-        x = wl.make(name, *shape)
-        rows, cols = shape
-        xb, xd = wl.bf16_bits(x), x.cuda()
+    cases = [(wl.make("c2", 272, 400), "c2"), (wl.make("c4", 1024, 1024), "c4")]
+    # tiles whose squared errors are fp32 subnormals, BF16 and FP32 input
+    cases += [(wl.adversarial(k, 64, 256, dtype=dt), k) for k in UNDERFLOW_KINDS
+              for dt in (torch.bfloat16, torch.float32)]
+    for x, name in cases:
+        _log(f"block2d case {name} {tuple(x.shape)} {x.dtype} select={select} rounding={rounding}")
+        rows, cols = x.shape
+        xb, xd = wl.host_array(x), x.cuda()
         alpha = B.nvfp4_46_tensor_scale(xd)
         a = float(alpha.item())
         kw = dict(rounding=rounding, select=select, sr_seed=SR_SEED)
@@ -261,7 +284,7 @@ def test_fp32_input_option_matrix(layout, select, rounding, rht):
 
 
 @pytest.mark.parametrize("kind", ["zeros", "neg_zeros", "one_hot", "tiny", "wide_range", "ties",
-                                  "bf16_small", "bf16_large"])
+                                  "bf16_small", "bf16_large"] + UNDERFLOW_KINDS)
 def test_fp32_input_adversarial(kind):
     check_case(wl.adversarial(kind, dtype=torch.float32), layout=B.BOTH, tag=f"adv-f32-{kind}")
 

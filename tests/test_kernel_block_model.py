@@ -1,0 +1,176 @@
+"""CPU: the kernels' per-block code, compiled for the host, against the oracle.
+
+`tests/host_model/` compiles csrc/block.hpp and csrc/codec.hpp -- block scales by
+multiplication with an exactness guard, both candidates, the 4-vs-6 decision from error
+estimates with a fallback to the defined errors (Table 3 lines 1-14), stochastic rounding,
+Philox, the Hadamard butterflies -- with the host compiler.  These tests need no GPU and
+reach input ranges where a shortcut of the kernel could silently differ from the definition:
+the fp32-subnormal range of the squared errors (Table 3 lines 6 / 12), the rounding
+boundaries of the E4M3 block scale (Eq. (2)), exact ties (Table 3 line 13).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2512_02010_amd import workloads as wl
+from tests import _host_model as hm
+
+SR_SEED, RHT_SEED = wl.C5_SR_SEED, wl.C5_RHT_SEED
+
+
+def _blocks(x: torch.Tensor) -> np.ndarray:
+    return x.float().numpy().reshape(-1, 16)
+
+
+def _uniforms(rows, cols, seed=SR_SEED) -> np.ndarray:
+    """The oracle's uniform of every element (Philox keyed by the flat element index)."""
+    u = np.array([ref.sr_uniform(seed, g) for g in range(rows * cols)], np.float32)
+    return u.reshape(-1, 16)
+
+
+def _compare(x: torch.Tensor, rounding=ref.RTN, select=ref.SEL_46_MSE, tag=""):
+    xb = wl.host_array(x)
+    rows, cols = x.shape
+    alpha = ref.tensor_scale(xb)
+    c, s, f = ref.quantize(xb, alpha, rounding=rounding, select=select, sr_seed=SR_SEED)
+    u = _uniforms(rows, cols) if rounding != ref.RTN else None
+    mc, ms, mf = hm.quantize_blocks(_blocks(x), alpha, rounding, select, u)
+    bad_s = int((ms.reshape(s.shape) != s).sum())
+    bad_f = int((mf.reshape(f.shape) != f).sum())
+    bad_c = int((mc.reshape(c.shape) != c).any(axis=1).sum())
+    assert (bad_s, bad_f, bad_c) == (0, 0, 0), (tag, rounding, select, bad_s, bad_f, bad_c)
+    return f
+
+
+@pytest.mark.parametrize("rounding", [ref.RTN, ref.SR, ref.SR_AFTER_RTN_SELECT])
+@pytest.mark.parametrize("select", [ref.SEL_46_MSE, ref.SEL_FORCE6, ref.SEL_FORCE4, ref.SEL_46_MAE,
+                                    ref.SEL_46_ABSMAX])
+def test_block_code_matches_oracle_on_the_workloads(rounding, select):
+    for name in ("c1", "c2", "c3", "c5"):
+        _compare(wl.make(name, 48, 256), rounding, select, name)
+
+
+@pytest.mark.parametrize("kind", wl.ADVERSARIAL_KINDS + ("decision_stress",))
+def test_block_code_matches_oracle_on_adversarial_tensors(kind):
+    for dt in (torch.bfloat16, torch.float32):
+        x = wl.adversarial(kind, 32, 128, dtype=dt)
+        _compare(x, ref.RTN, tag=kind)
+        _compare(x, ref.SR, tag=kind)
+
+
+@pytest.mark.parametrize("rounding", [ref.RTN, ref.SR])
+def test_decision_where_squared_errors_are_subnormal(rounding):
+    """N(0,1) * 2^e for e = -40 ... -90: from about 2^-58 down the squared errors are fp32
+    subnormals, where the relative-error bound behind the kernel's estimate-based decision
+    does not hold (an estimate may be off by a whole subnormal step while the tolerance has
+    underflowed to zero); the decision must still be the defined one, ties going to 6."""
+    g = torch.Generator().manual_seed(5)
+    base = torch.randn((64, 256), generator=g)
+    seen_four = 0
+    for e in range(-40, -92, -2):
+        x = (base * 2.0 ** e).to(torch.bfloat16)
+        assert float(x.abs().max()) >= 2.0 ** -89          # the contract of the tensor scale
+        f = _compare(x, rounding, tag=f"2^{e}")
+        seen_four += int(f.sum())
+        _compare((base * 2.0 ** e).contiguous(), rounding, tag=f"fp32 2^{e}")
+    assert seen_four > 1000
+
+
+def test_subnormal_range_inputs_really_reach_near_ties():
+    # the sweep above is only worth something if the two errors there are close or equal for
+    # many blocks while not all being zero
+    x = wl.adversarial("sq_underflow_72", 64, 256)
+    xb = wl.bf16_bits(x)
+    alpha = ref.tensor_scale(xb)
+    E6, E4 = ref.block_errors(xb, alpha)
+    tiny = np.float32(2.0 ** -126)
+    assert (E6 < tiny).all() and (E4 < tiny).all()           # all subnormal ...
+    assert (E6 > 0).mean() > 0.8 and (E4 > 0).mean() > 0.8   # ... and most of them not zero
+    assert (E6 == E4).sum() > 50                             # exact ties occur
+    near = (E6 != E4) & (np.abs(E6 - E4) <= np.float32(4 * 2.0 ** -149))
+    assert near.sum() > 100                                  # and differences of a few steps
+    f = ref.quantize(xb, alpha)[2]
+    assert 0.05 < f.mean() < 0.95
+
+
+@pytest.mark.parametrize("rounding", [ref.RTN, ref.SR])
+def test_tile_decision_matches_oracle(rounding):
+    """The 16x16-tile decision (sum of sixteen row estimates, fallback to the defined errors)
+    on ordinary tensors, on near-tie patterns and where the squared errors are subnormal."""
+    cases = [wl.make("c2", 64, 128), wl.make("c4", 64, 128),
+             wl.adversarial("decision_stress", 64, 128)]
+    cases += [wl.adversarial(k, 64, 128, dtype=dt) for k in wl.ADVERSARIAL_KINDS
+              if k.startswith("sq_underflow") for dt in (torch.bfloat16, torch.float32)]
+    defined_path = 0
+    for x in cases:
+        xb = wl.host_array(x)
+        rows, cols = x.shape
+        alpha = ref.tensor_scale(xb)
+        _, s_ref, f_ref, _ = ref.quantize_2d(xb, alpha, rounding=rounding, sr_seed=SR_SEED)
+        xf = x.float().numpy()
+        u = _uniforms(rows, cols).reshape(rows, cols) if rounding == ref.SR else None
+        for tr in range(rows // 16):
+            for tc in range(cols // 16):
+                sl = (slice(16 * tr, 16 * tr + 16), slice(16 * tc, 16 * tc + 16))
+                four, s6, s4, path = hm.tile_decision(xf[sl], alpha, rounding,
+                                                      None if u is None else u[sl])
+                defined_path += path
+                assert four == f_ref[tr, tc], (tr, tc, four, path)
+                assert (s4 if four else s6) == s_ref[tr, tc]
+    assert defined_path > 0
+
+
+def test_block_scale_shortcut_is_exact_around_every_rounding_boundary():
+    """Eq. (2): the kernel takes the E4M3 byte of b * fl(1/(alpha*M)) unless that product is
+    close to a rounding boundary, where it divides.  Probe both sides of every boundary of the
+    E4M3 cast, for several alpha whose reciprocals round in different directions."""
+    rng = np.random.default_rng(11)
+    alphas = [1.0, 1.0 / 3.0, 0.7, 1000.0 / 1536.0, 2.0 ** -40 * 1.37, 3.1e7]
+    n = 0
+    for alpha in alphas:
+        a32 = float(np.float32(alpha))
+        for M in (6, 4):
+            c = float(np.float32(np.float32(a32) * np.float32(M)))
+            for byte in range(0, 0x7E):
+                lo, hi = ref.e4m3_decode(byte), ref.e4m3_decode(byte + 1)
+                mid = 0.5 * (lo + hi)                      # exact in double
+                b0 = np.float32(mid * c)
+                for step in range(-6, 7):                  # fp32 neighbours of the boundary's pre-image
+                    b = b0
+                    for _ in range(abs(step)):
+                        b = np.nextafter(b, np.float32(np.inf if step > 0 else 0), dtype=np.float32)
+                    if not (b > 0):
+                        continue
+                    assert hm.block_scale(float(b), a32, M) == ref.block_scale(float(b), a32, float(M))
+                    n += 1
+            for b in rng.lognormal(0.0, 3.0, 300).astype(np.float32):
+                assert hm.block_scale(float(b * c), a32, M) == ref.block_scale(float(b * c), a32, float(M))
+    assert n > 15000
+
+
+def test_stochastic_rounding_rule_matches_oracle():
+    rng = np.random.default_rng(3)
+    y = np.concatenate([rng.uniform(-7, 7, 20000), rng.normal(0, 0.3, 20000),
+                        np.array([0.0, -0.0, 0.25, 0.5, 5.999, 6.0, 6.5, 1e-30, -1e30])]).astype(np.float32)
+    u = rng.integers(0, 1 << 24, y.size).astype(np.float32) * np.float32(2.0 ** -24)
+    # thresholds hit exactly: u == (|y| - lo) / (hi - lo) must round down, one step below up
+    yy = np.array([0.125, 0.625, 1.75, 2.25, 3.5, 5.0, -0.375, -4.5], np.float32)
+    pp = np.array([0.25, 0.25, 0.5, 0.25, 0.5, 0.5, 0.75, 0.25], np.float32)
+    y = np.concatenate([y, yy, yy, yy])
+    u = np.concatenate([u, pp, pp - np.float32(2.0 ** -24), np.zeros_like(pp)])
+    got = hm.e2m1_sr(y, u)
+    want = np.array([ref.e2m1_sr(float(a), float(b)) for a, b in zip(y, u)], np.uint8)
+    assert np.array_equal(got, want)
+
+
+def test_philox_and_hadamard_match_oracle():
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        ctr = [int(v) for v in rng.integers(0, 1 << 32, 4)]
+        key = [int(v) for v in rng.integers(0, 1 << 32, 2)]
+        assert hm.philox(ctr, key) == ref.philox4x32_10(ctr, key)
+    for _ in range(200):
+        v = (rng.normal(0, 1, 16) * 2.0 ** rng.integers(-30, 30)).astype(np.float32)
+        sw = int(rng.integers(0, 1 << 32))
+        assert np.array_equal(hm.rht16(v, sw).view(np.uint32), ref.rht16(v, sw).view(np.uint32))
