@@ -106,7 +106,7 @@ NV_DEV void grid8(uint32_t codes, float (&g)[8]) {
 // i < 8, of hi for i >= 8).  Also returns a cheap estimate E' of the block's squared
 // error: d' = fma(g, dec, -v) and a running fma(d', d', E'), i.e. two instructions per
 // element where the defining sequence (product, difference, square, tree sum, each
-// rounded) takes four.  E' is only ever used through decide_four() below.
+// rounded) takes four.  E' is only ever used through decide_from_estimates() below.
 template <int ROUNDING, int ERR>
 NV_DEV float candidate(const float (&v)[16], const float (&u)[16], float dec, float enc,
                        uint32_t &lo, uint32_t &hi) {
@@ -239,17 +239,18 @@ NV_DEV bool same_dequantized(uint32_t lo6, uint32_t hi6, uint32_t lo4, uint32_t 
   return identical | (scaled & lo_ok & hi_ok);
 }
 
-NV_DEV bool decide_four(const float (&v)[16], float E6p, float E4p, float dec6, float dec4,
-                        uint32_t lo6, uint32_t hi6, uint32_t lo4, uint32_t hi4) {
+// Outcome of comparing the two estimates.
+enum : int { kKeepSix = 0, kKeepFour = 1, kUndecided = 2 };
+
+// kKeepFour / kKeepSix when the estimates (or the codes, for exact ties) settle Table 3
+// line 13, kUndecided when only the defined errors can.
+NV_DEV int decide_from_estimates(float E6p, float E4p, float dec6, float dec4, uint32_t lo6,
+                                 uint32_t hi6, uint32_t lo4, uint32_t hi4) {
   const float tol = decision_tolerance(dec6 * dec6, E6p, dec4 * dec4, E4p);
   const float diff = E4p - E6p;
-  bool four = diff < 0.0f;
-  if (!(fabsf(diff) > tol)) {
-    four = false;   // identical dequantized values: equal errors, and ties keep 6
-    if (!same_dequantized(lo6, hi6, lo4, hi4, dec6, dec4))
-      four = exact_error(v, lo4, hi4, dec4) < exact_error(v, lo6, hi6, dec6);
-  }
-  return four;
+  if (fabsf(diff) > tol) return diff < 0.0f ? kKeepFour : kKeepSix;
+  // identical dequantized values: equal errors, and ties keep 6
+  return same_dequantized(lo6, hi6, lo4, hi4, dec6, dec4) ? kKeepSix : kUndecided;
 }
 
 struct BlockResult {
@@ -275,10 +276,14 @@ NV_DEV bool scale_byte_at_risk(float q) {
   return near_midpoint | subnormal_range;
 }
 
-// The whole per-block procedure (Table 3 lines 1-14).
-template <int ROUNDING, int SELECT>
-NV_DEV BlockResult quantize_block(const float (&v)[16], const float (&u)[16],
-                                  const ScaleConsts &k, const ScaleTable &tab) {
+// The per-block procedure (Table 3 lines 1-14) in one pass.  DEFINED_ERRORS = false: the
+// squared-error rule compares the cheap estimates and reports through `undecided` when they
+// cannot tell (the result is then provisional).  DEFINED_ERRORS = true: the errors are
+// evaluated exactly as defined.  The other rules are always evaluated as defined.
+template <int ROUNDING, int SELECT, bool DEFINED_ERRORS>
+NV_DEV BlockResult quantize_block_pass(const float (&v)[16], const float (&u)[16],
+                                       const ScaleConsts &k, const ScaleTable &tab,
+                                       bool &undecided) {
   float b = 0.0f;
 #pragma unroll
   for (int i = 0; i < 16; i += 2) b = fmaxf(fmaxf(b, fabsf(v[i])), fabsf(v[i + 1]));
@@ -302,7 +307,7 @@ NV_DEV BlockResult quantize_block(const float (&v)[16], const float (&u)[16],
     if (SELECT != kSelForce6) S4 = e4m3_encode(b / k.c4);
   }
 
-  constexpr int kErr = SELECT == kSel46 ? kErrMseEstimate
+  constexpr int kErr = SELECT == kSel46 ? (DEFINED_ERRORS ? kErrNone : kErrMseEstimate)
                        : SELECT == kSel46Mae ? kErrMae
                        : SELECT == kSel46AbsMax ? kErrAbsMax : kErrNone;
   // Appendix A.3's second alternative compares round-to-nearest candidates and rounds
@@ -329,13 +334,40 @@ NV_DEV BlockResult quantize_block(const float (&v)[16], const float (&u)[16],
       E4p = candidate<kCandRounding, kErr>(v, u, t.x, t.y, r4.lo, r4.hi);
   }
   bool four;
-  if (SELECT == kSelForce6) four = false;
-  else if (SELECT == kSelForce4) four = true;
-  else if (SELECT == kSel46Mae || SELECT == kSel46AbsMax) four = E4p < E6p;   // as defined
-  else four = decide_four(v, E6p, E4p, r6.dec, r4.dec, r6.lo, r6.hi, r4.lo, r4.hi);
+  if (SELECT == kSelForce6) {
+    four = false;
+  } else if (SELECT == kSelForce4) {
+    four = true;
+  } else if (SELECT == kSel46Mae || SELECT == kSel46AbsMax) {
+    four = E4p < E6p;   // as defined
+  } else if (DEFINED_ERRORS) {
+    four = exact_error(v, r4.lo, r4.hi, r4.dec) < exact_error(v, r6.lo, r6.hi, r6.dec);
+  } else {
+    const int d = decide_from_estimates(E6p, E4p, r6.dec, r4.dec, r6.lo, r6.hi, r4.lo, r4.hi);
+    four = d == kKeepFour;
+    undecided = d == kUndecided;
+  }
   BlockResult r = four ? r4 : r6;
   if (ROUNDING == kSRAfterRtnSelect)
     (void)candidate<kSR, kErrNone>(v, u, r.dec, four ? enc4 : enc6, r.lo, r.hi);
+  return r;
+}
+
+// The whole per-block procedure.  `again(w, uu)` must produce the block's values (and its
+// stochastic-rounding uniforms) once more: the rare block that the estimates cannot decide
+// is redone from those with the defined errors, so that nothing of the first pass has to
+// stay in registers for it -- keeping the sixteen values and both candidates alive across
+// the common path cost the rowwise kernel three of its eight waves per SIMD.
+template <int ROUNDING, int SELECT, typename Again>
+NV_DEV BlockResult quantize_block(const float (&v)[16], const float (&u)[16],
+                                  const ScaleConsts &k, const ScaleTable &tab, Again &&again) {
+  bool undecided = false;
+  BlockResult r = quantize_block_pass<ROUNDING, SELECT, false>(v, u, k, tab, undecided);
+  if (SELECT == kSel46 && undecided) {
+    float w[16], uu[16];
+    again(w, uu);
+    r = quantize_block_pass<ROUNDING, SELECT, true>(w, uu, k, tab, undecided);
+  }
   return r;
 }
 

@@ -42,7 +42,9 @@ enum : int { kOutCodes = 0, kOutFake = 1, kOutAmax = 2 };
 constexpr int kAmaxUnroll = 8;          // independent 128-bit loads per lane in k_amax_plain
 constexpr int kAmaxWgPerCu = 1;         // k_amax_plain: few, long-lived workgroups, each ends
                                         // with a serialising access to the one result word
-constexpr int kFlatWgPerCu = 32;        // k_flat with outputs (4 ... 64 were within 1 us)
+constexpr int kFlatLongWgPerCu = 6;     // k_flat with outputs: long-lived workgroups (5 ... 8
+                                        // timed; 8 leaves no slot for the short ones)
+constexpr int kFlatShortRoundsPerCu = 16;  // ... and rounds left to one-round workgroups
 constexpr int kFlatAmaxWgPerCu = 2;     // k_flat as the amax pass of the Hadamard transform
 constexpr int kAmaxRhtColWgPerCu = 8;   // k_amax_rht_col
 
@@ -260,16 +262,21 @@ __global__ __launch_bounds__(kThreads) void k_flat(
     const uint4 *__restrict__ x, const float *__restrict__ alpha_p, uint2 *__restrict__ codes,
     uint8_t *__restrict__ scales, uint8_t *__restrict__ choice, uint4 *__restrict__ out_bf16,
     uint32_t *amax_bits, int64_t nblocks, uint32_t nb_per_row, uint64_t sr_seed,
-    uint64_t rht_seed) {
+    uint64_t rht_seed, uint32_t n_long, uint32_t rounds_long) {
   __shared__ ScaleTable tab;
   // fake-quant only: a wave's 2 KiB of output is turned round in LDS so that each of its
   // two store instructions writes 1 KiB of whole cache lines (streaming stores of half
   // lines are slow), instead of every lane writing its own 32 bytes
   __shared__ uint4 xpose[OUT == kOutFake ? 2 * kThreads : 1];
-  // The tensor is cut into rounds of 256 consecutive blocks; workgroup w takes rounds
-  // w, w + gridDim, ...  Everything that depends on the round only (base pointers, the
-  // number of live lanes) is wave-uniform and stays on the scalar unit; a lane adds its
-  // own constant offset.
+  // The tensor is cut into rounds of 256 consecutive blocks, dealt to two classes of
+  // workgroups: the first n_long workgroups take rounds_long rounds each (w, w + n_long, ...,
+  // all below n_long * rounds_long), the others share the remaining rounds (one each, when
+  // the launcher sizes the grid for it; in general w', w' + n_short, ...).  A workgroup pays
+  // a full memory latency before its first round, with its wave slots idle: the long ones,
+  // few enough to be resident all at once, pay it once for most of the tensor, and the short
+  // ones, launched as slots fall free, even out the end.  Everything that depends on the
+  // round only (base pointers, the number of live lanes) is wave-uniform and stays on the
+  // scalar unit; a lane adds its own constant offset.
   const uint32_t tid = threadIdx.x;
   const uint32_t rounds = (uint32_t)((nblocks + kThreads - 1) / kThreads);
   const uint32_t tail = (uint32_t)(nblocks - (int64_t)(rounds - 1) * kThreads);  // 1..256
@@ -303,12 +310,22 @@ __global__ __launch_bounds__(kThreads) void k_flat(
       for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(v[i]));
       return;
     }
-    if (ROUNDING != kRTN) {
+    auto uniforms = [&](float (&uu)[16]) {
       const uint64_t q0 = ((uint64_t)base + tid) * 4u;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) sr_uniforms4(sr_seed, q0 + j, &u[4 * j]);
-    }
-    const BlockResult res = quantize_block<ROUNDING, SELECT>(v, u, sc, tab);
+      for (int j = 0; j < 4; ++j) sr_uniforms4(sr_seed, q0 + j, &uu[4 * j]);
+    };
+    if (ROUNDING != kRTN) uniforms(u);
+    // the block once more, from memory (a lane without a block of its own holds a copy of
+    // the round's last block, as fetch() gave it)
+    auto again = [&](float (&w)[16], float (&uu)[16]) {
+      Raw r2;
+      load_block<XF32>(x + Raw::kPieces * (base + (tid < live ? tid : live - 1)), r2);
+      unpack16(r2, w);
+      if (RHT) rht16(w, sign_word);
+      if (ROUNDING != kRTN) uniforms(uu);
+    };
+    const BlockResult res = quantize_block<ROUNDING, SELECT>(v, u, sc, tab, again);
     if (OUT == kOutCodes) {
       store_as<kNtCodes>(codes + base + tid, make_uint2(res.lo, res.hi));
       store_as<kNtCodes>(scales + base + tid, (uint8_t)res.scale);
@@ -343,11 +360,22 @@ __global__ __launch_bounds__(kThreads) void k_flat(
   // stored), because they store pieces of their neighbours' blocks; elsewhere they skip
   // the round.
   // The loads are unconditional (a conditional load would have to be waited for right
-  // where the two control paths join): a round past the end re-reads the last round and
-  // a lane past the end of a ragged last round re-reads that round's last block; what
-  // they fetch is never used.
-  auto fetch = [&](uint32_t r, Raw &raw) {
-    const uint32_t rr = r < rounds ? r : rounds - 1;
+  // where the two control paths join): a round past the workgroup's share re-reads its
+  // current round and a lane past the end of a ragged last round re-reads that round's
+  // last block; what they fetch is never used.
+  uint32_t r, step, end;
+  if (blockIdx.x < n_long) {
+    r = blockIdx.x;
+    step = n_long;
+    end = n_long * rounds_long;
+  } else {
+    r = n_long * rounds_long + (blockIdx.x - n_long);
+    step = gridDim.x - n_long;
+    end = rounds;
+  }
+  // A round past the workgroup's share re-reads its current round (never used).
+  auto fetch = [&](uint32_t next, Raw &raw) {
+    const uint32_t rr = next < end ? next : r;
     const uint32_t last = lanes_in_round(rr) - 1;
     const uint32_t lane = tid < last ? tid : last;
     const uint4 *xb = x + Raw::kPieces * ((int64_t)rr * kThreads);
@@ -357,16 +385,14 @@ __global__ __launch_bounds__(kThreads) void k_flat(
     const uint32_t live = lanes_in_round(r);
     if (OUT == kOutFake || tid < live) work(r, live, raw);
   };
-  const uint32_t step = gridDim.x;
-  uint32_t r = blockIdx.x;
   Raw a, b;
   fetch(r, a);
   if (OUT != kOutAmax) sc = build_scale_table(tab, *alpha_p);
-  while (r < rounds) {
+  while (r < end) {
     fetch(r + step, b);
     run(r, a);
     r += step;
-    if (r >= rounds) break;
+    if (r >= end) break;
     fetch(r + step, a);
     run(r, b);
     r += step;
@@ -494,17 +520,21 @@ __global__ __launch_bounds__(kThreads) void k_tile(
       const int64_t gr = r0 + row, gc = c0 + rbk * 16;
       if (gr < rows && gc < cols) {
         float v[16], u[16];
-        const uint4 *own = reinterpret_cast<const uint4 *>(tile) + unit * Raw::kPieces;
-        Raw mine;
-#pragma unroll
-        for (int q = 0; q < Raw::kPieces; ++q) mine.w[q] = own[q];
-        unpack16(mine, v);
         const int64_t k = gr * nb_per_row + (gc >> 4);
-        if (ROUNDING != kRTN) {
+        // the lane's block out of the tile, with its uniforms
+        auto take = [&](float (&w)[16], float (&uu)[16]) {
+          const uint4 *own = reinterpret_cast<const uint4 *>(tile) + unit * Raw::kPieces;
+          Raw mine;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) sr_uniforms4(sr_seed, (uint64_t)k * 4u + q, &u[4 * q]);
-        }
-        BlockResult r = quantize_block<ROUNDING, SELECT>(v, u, sc, tab);
+          for (int q = 0; q < Raw::kPieces; ++q) mine.w[q] = own[q];
+          unpack16(mine, w);
+          if (ROUNDING != kRTN) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) sr_uniforms4(sr_seed, (uint64_t)k * 4u + q, &uu[4 * q]);
+          }
+        };
+        take(v, u);
+        BlockResult r = quantize_block<ROUNDING, SELECT>(v, u, sc, tab, take);
         reinterpret_cast<uint2 *>(codes_row)[k] = make_uint2(r.lo, r.hi);
         scales_row[k] = (uint8_t)r.scale;
         if (choice_row) choice_row[k] = (uint8_t)r.four;
@@ -523,40 +553,50 @@ __global__ __launch_bounds__(kThreads) void k_tile(
     const int64_t gc = c0 + 2 * cp;               // even column of the pair
     if (gr >= rows || gc >= cols) continue;       // (cols is even, so the pair is in or out together)
     float va[16], vb[16], ua[16], ub[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      if constexpr (XF32) {
-        const uint2 pair = kDirect
-            ? static_cast<const uint2 *>(x_any)[((gr + i) * cols + gc) >> 1]
-            : reinterpret_cast<const uint2 *>(tile)[(rb * 16 + i) * kColPairs + cp];
-        va[i] = u2f(pair.x);
-        vb[i] = u2f(pair.y);
-      } else {
-        const uint32_t pair = kDirect ? static_cast<const uint32_t *>(x_any)[((gr + i) * cols + gc) >> 1]
-                                      : tile[(rb * 16 + i) * kColPairs + cp];
-        va[i] = bf16_lo(pair);
-        vb[i] = bf16_hi(pair);
-      }
-    }
-    if (RHT) {
-      const uint32_t sw = rht_sign_word(rht_seed, (uint64_t)(gr >> 4));
-      rht16(va, sw);
-      rht16(vb, sw);
-    }
-    if (ROUNDING != kRTN) {
-      // element (row, col) has flat index g = row*cols + col; the pair (gc, gc+1) shares a
-      // Philox call because gc is even and cols is a multiple of 4
+    // the lane's two column blocks (transformed, with their uniforms) out of the tile or memory
+    auto take = [&](float (&wa)[16], float (&wb)[16], float (&uua)[16], float (&uub)[16]) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const uint64_t g = (uint64_t)(gr + i) * (uint64_t)cols + (uint64_t)gc;
-        float uu[4];
-        sr_uniforms4(sr_seed, g >> 2, uu);
-        ua[i] = (g & 2u) ? uu[2] : uu[0];
-        ub[i] = (g & 2u) ? uu[3] : uu[1];
+        if constexpr (XF32) {
+          const uint2 pair = kDirect
+              ? static_cast<const uint2 *>(x_any)[((gr + i) * cols + gc) >> 1]
+              : reinterpret_cast<const uint2 *>(tile)[(rb * 16 + i) * kColPairs + cp];
+          wa[i] = u2f(pair.x);
+          wb[i] = u2f(pair.y);
+        } else {
+          const uint32_t pair = kDirect ? static_cast<const uint32_t *>(x_any)[((gr + i) * cols + gc) >> 1]
+                                        : tile[(rb * 16 + i) * kColPairs + cp];
+          wa[i] = bf16_lo(pair);
+          wb[i] = bf16_hi(pair);
+        }
       }
-    }
-    BlockResult ra = quantize_block<ROUNDING, SELECT>(va, ua, sc, tab);
-    BlockResult rbk = quantize_block<ROUNDING, SELECT>(vb, ub, sc, tab);
+      if (RHT) {
+        const uint32_t sw = rht_sign_word(rht_seed, (uint64_t)(gr >> 4));
+        rht16(wa, sw);
+        rht16(wb, sw);
+      }
+      if (ROUNDING != kRTN) {
+        // element (row, col) has flat index g = row*cols + col; the pair (gc, gc+1) shares a
+        // Philox call because gc is even and cols is a multiple of 4
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const uint64_t g = (uint64_t)(gr + i) * (uint64_t)cols + (uint64_t)gc;
+          float uu[4];
+          sr_uniforms4(sr_seed, g >> 2, uu);
+          uua[i] = (g & 2u) ? uu[2] : uu[0];
+          uub[i] = (g & 2u) ? uu[3] : uu[1];
+        }
+      }
+    };
+    take(va, vb, ua, ub);
+    BlockResult ra = quantize_block<ROUNDING, SELECT>(va, ua, sc, tab, [&](float (&w)[16], float (&uu)[16]) {
+      float other[16], other_u[16];
+      take(w, other, uu, other_u);
+    });
+    BlockResult rbk = quantize_block<ROUNDING, SELECT>(vb, ub, sc, tab, [&](float (&w)[16], float (&uu)[16]) {
+      float other[16], other_u[16];
+      take(other, w, other_u, uu);
+    });
     if (OUT == kOutCodes) {
       const int ia = (2 * cp) * kColBlockRows + rb, ib = ia + kColBlockRows;
       stage_codes[ia] = make_uint2(ra.lo, ra.hi);
@@ -783,7 +823,7 @@ __global__ __launch_bounds__(kThreads) void k_block2d(
       over_tile(E6, E4);      // evaluated as defined
       four = E4 < E6;
     } else if (SELECT == kSel46) {
-      // E6, E4 are row estimates (see decide_four).  Outside the margin of
+      // E6, E4 are row estimates (see decide_from_estimates).  Outside the margin of
       // tile_decision_tolerance() the summed estimates order the defined errors; inside it
       // the defined errors are evaluated.  All sixteen lanes hold the same sums and take the
       // same path.
@@ -946,20 +986,37 @@ struct FlatArgs {
 
 template <bool XF32, int ROUNDING, int SELECT, bool RHT, int OUT>
 static int launch_flat(const FlatArgs &a) {
-  // the amax pass ends with one access per workgroup to the one result word: fewer, longer-lived
-  // workgroups than the passes that write their own outputs
-  int grid = grid_for(a.nblocks, OUT == kOutAmax ? kFlatAmaxWgPerCu : kFlatWgPerCu);
+  const int64_t rounds = (a.nblocks + kThreads - 1) / kThreads;
+  const int cus = compute_units();
+  int64_t n_long = 0, rounds_long = 0, grid;
+  if (OUT == kOutAmax) {
+    // the amax pass ends with one access per workgroup to the one result word: few,
+    // long-lived workgroups that stride over the whole tensor
+    grid = (int64_t)cus * kFlatAmaxWgPerCu;
+    if (grid > rounds) grid = rounds;
+  } else {
+    n_long = (int64_t)cus * kFlatLongWgPerCu;
+    rounds_long = (rounds - (int64_t)cus * kFlatShortRoundsPerCu) / n_long;
+    if (rounds_long < 2) n_long = rounds_long = 0;   // a small tensor: one round per workgroup
+    grid = n_long + (rounds - n_long * rounds_long);
+  }
   if (RHT) {
-    // round r of a workgroup starts at block 256*r; if 256*grid is a multiple of the
+    // round r starts at block 256*r; if 256 * (a workgroup's stride) is a multiple of the
     // blocks per row, every lane sees one position along the row in all its rounds
     uint32_t g = a.nb_per_row, t = kThreads;
     while (t) { const uint32_t q = g % t; g = t; t = q; }      // gcd(nb_per_row, 256)
-    const int period = (int)(a.nb_per_row / g);
-    if (period <= grid / 2) grid -= grid % period;
+    const int64_t period = a.nb_per_row / g;
+    if (OUT == kOutAmax) {
+      if (period <= grid / 2) grid -= grid % period;
+    } else if (n_long && period <= n_long / 2) {
+      n_long -= n_long % period;
+      rounds_long = (rounds - (int64_t)cus * kFlatShortRoundsPerCu) / n_long;
+      grid = n_long + (rounds - n_long * rounds_long);
+    }
   }
-  return launch(k_flat<XF32, ROUNDING, SELECT, RHT, OUT>, dim3(grid), dim3(kThreads), a.stream, a.x,
-                a.alpha, a.codes, a.scales, a.choice, a.out, a.amax, a.nblocks, a.nb_per_row,
-                a.sr_seed, a.rht_seed);
+  return launch(k_flat<XF32, ROUNDING, SELECT, RHT, OUT>, dim3((uint32_t)grid), dim3(kThreads),
+                a.stream, a.x, a.alpha, a.codes, a.scales, a.choice, a.out, a.amax, a.nblocks,
+                a.nb_per_row, a.sr_seed, a.rht_seed, (uint32_t)n_long, (uint32_t)rounds_long);
 }
 
 template <bool XF32, int ROUNDING, int SELECT>

@@ -57,6 +57,8 @@ def lib() -> C.CDLL:
         L.hm_quantize_blocks.restype = None
         L.hm_quantize_blocks.argtypes = [f32p, f32p, C.c_int64, C.c_float, C.c_int, C.c_int, u32p,
                                          u8p, u8p]
+        L.hm_second_passes.restype = C.c_int
+        L.hm_second_passes.argtypes = []
         L.hm_tile_decision.restype = C.c_int
         L.hm_tile_decision.argtypes = [f32p, f32p, C.c_float, C.c_int, u8p, u8p, C.POINTER(C.c_int)]
         L.hm_e2m1_sr.restype = None
@@ -91,6 +93,11 @@ def quantize_blocks(v: np.ndarray, alpha: float, rounding: int = RTN, select: in
     lib().hm_quantize_blocks(_p(v, C.c_float), _p(u, C.c_float), n, alpha, rounding, select,
                              _p(codes, C.c_uint32), _p(scale, C.c_uint8), _p(four, C.c_uint8))
     return codes.view(np.uint8).reshape(n, 8), scale, four
+
+
+def second_passes() -> int:
+    """Blocks so far that the estimate pass could not decide (redone with the defined errors)."""
+    return lib().hm_second_passes()
 
 
 def tile_decision(v: np.ndarray, alpha: float, rounding: int = RTN, u: np.ndarray | None = None):

@@ -8,15 +8,25 @@ using namespace nvfp4_46;
 
 namespace {
 
+int g_second_passes = 0;   // blocks that the estimates could not decide
+
 template <int ROUNDING>
 BlockResult run_block(const float (&v)[16], const float (&u)[16], const ScaleConsts &k,
                       const ScaleTable &tab, int select) {
+  // the kernels fetch the block again from memory; here it is simply copied
+  auto again = [&](float (&w)[16], float (&uu)[16]) {
+    ++g_second_passes;
+    for (int i = 0; i < 16; ++i) {
+      w[i] = v[i];
+      uu[i] = u[i];
+    }
+  };
   switch (select) {
-    case kSel46: return quantize_block<ROUNDING, kSel46>(v, u, k, tab);
-    case kSelForce6: return quantize_block<ROUNDING, kSelForce6>(v, u, k, tab);
-    case kSelForce4: return quantize_block<ROUNDING, kSelForce4>(v, u, k, tab);
-    case kSel46Mae: return quantize_block<ROUNDING, kSel46Mae>(v, u, k, tab);
-    default: return quantize_block<ROUNDING, kSel46AbsMax>(v, u, k, tab);
+    case kSel46: return quantize_block<ROUNDING, kSel46>(v, u, k, tab, again);
+    case kSelForce6: return quantize_block<ROUNDING, kSelForce6>(v, u, k, tab, again);
+    case kSelForce4: return quantize_block<ROUNDING, kSelForce4>(v, u, k, tab, again);
+    case kSel46Mae: return quantize_block<ROUNDING, kSel46Mae>(v, u, k, tab, again);
+    default: return quantize_block<ROUNDING, kSel46AbsMax>(v, u, k, tab, again);
   }
 }
 
@@ -33,6 +43,8 @@ void over_tile(float (&e)[16], bool use_max) {
 }  // namespace
 
 extern "C" {
+
+int hm_second_passes() { return g_second_passes; }
 
 // quantize_block<rounding, select> on `n` blocks of 16 values (u: the uniforms of stochastic
 // rounding, ignored for round-to-nearest).  codes: 2 words per block.
