@@ -42,6 +42,7 @@
 #ifndef NVFP4_46_H
 #define NVFP4_46_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -127,6 +128,22 @@ typedef struct {
  * bad fp8_max / layout / x_dtype -> ERR_PARAM; rht with both layouts -> ERR_UNSUPPORTED.        */
 int nvfp4_46_tensor_scale(const void *x, const nvfp4_46_params *p, float *alpha,
                           void *stream);
+
+/* nvfp4_46_tensor_scale in one kernel launch instead of three, for callers that can lend it
+ * a few bytes of device memory: the reduction keeps its running maximum and a completion
+ * count there instead of in the alpha word, and the last workgroup to finish applies Eq. (1).
+ * Same result, bit for bit.
+ *   workspace        in/out  at least NVFP4_46_TENSOR_SCALE_WS_BYTES bytes (device), 16-byte
+ *                            aligned, owned by the caller.  Must be zero when the call's work
+ *                            starts (zero it once after allocating it); the call leaves it zero,
+ *                            so it can serve any number of calls -- one at a time: calls whose
+ *                            work may overlap (different streams) need a workspace each.
+ *   workspace_bytes  in      size of the workspace
+ * Errors: as nvfp4_46_tensor_scale, plus workspace NULL -> ERR_NULL, too small -> ERR_PARAM,
+ * misaligned -> ERR_ALIGN.                                                                      */
+#define NVFP4_46_TENSOR_SCALE_WS_BYTES 64
+int nvfp4_46_tensor_scale_ws(const void *x, const nvfp4_46_params *p, float *alpha,
+                             void *workspace, size_t workspace_bytes, void *stream);
 
 /* The 4/6 quantizer (Eq. (2), Eq. (3), Table 3 lines 1-14) in the requested
  * orientation(s).

@@ -27,7 +27,7 @@ STATUS_NAMES = {0: "NVFP4_OK", 1: "NVFP4_ERR_NULL", 2: "NVFP4_ERR_SHAPE", 3: "NV
                 4: "NVFP4_ERR_PARAM", 5: "NVFP4_ERR_UNSUPPORTED", 6: "NVFP4_ERR_HIP"}
 
 EXPORTS = (
-    "nvfp4_46_tensor_scale", "nvfp4_46_quantize", "nvfp4_46_dequantize", "nvfp4_46_fake_quant",
+    "nvfp4_46_tensor_scale", "nvfp4_46_tensor_scale_ws", "nvfp4_46_quantize", "nvfp4_46_dequantize", "nvfp4_46_fake_quant",
     "nvfp4_46_gemm", "nvfp4_46_status_string", "nvfp4_46_debug_e2m1_rtn_range", "nvfp4_46_debug_e4m3_range",
     "nvfp4_46_debug_decode_tables", "nvfp4_46_debug_bf16_range", "nvfp4_46_debug_e2m1_sr",
     "nvfp4_46_debug_philox",
@@ -69,6 +69,8 @@ def lib() -> C.CDLL:
         pp = C.POINTER(Params)
         L.nvfp4_46_tensor_scale.restype = C.c_int
         L.nvfp4_46_tensor_scale.argtypes = [vp, pp, vp, vp]
+        L.nvfp4_46_tensor_scale_ws.restype = C.c_int
+        L.nvfp4_46_tensor_scale_ws.argtypes = [vp, pp, vp, vp, C.c_size_t, vp]
         L.nvfp4_46_quantize.restype = C.c_int
         L.nvfp4_46_quantize.argtypes = [vp, pp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.nvfp4_46_dequantize.restype = C.c_int
@@ -133,6 +135,15 @@ def tensor_scale_raw(x, params: Params, alpha, stream=None) -> int:
                                        _ptr(alpha), _stream(stream))
 
 
+TENSOR_SCALE_WS_BYTES = 64
+
+
+def tensor_scale_ws_raw(x, params: Params, alpha, workspace, workspace_bytes: int, stream=None) -> int:
+    return lib().nvfp4_46_tensor_scale_ws(_ptr(x), C.byref(params) if params is not None else None,
+                                          _ptr(alpha), _ptr(workspace), workspace_bytes,
+                                          _stream(stream))
+
+
 def quantize_raw(x, params, alpha, codes_row, scales_row, codes_col, scales_col, choice_row,
                  choice_col, stream=None) -> int:
     return lib().nvfp4_46_quantize(_ptr(x), C.byref(params) if params is not None else None,
@@ -178,6 +189,24 @@ def nvfp4_46_tensor_scale(x: torch.Tensor, layout: int = ROWWISE, rht: int = 0, 
     p = make_params(rows, cols, layout=layout, rht=rht, rht_seed=rht_seed, fp8_max=fp8_max,
                     x_dtype=x_dtype_of(x))
     _check(tensor_scale_raw(x, p, alpha, stream), "nvfp4_46_tensor_scale")
+    return alpha
+
+
+def new_workspace(device="cuda") -> torch.Tensor:
+    """A zeroed workspace for nvfp4_46_tensor_scale_ws (the calls leave it zeroed)."""
+    return torch.zeros(TENSOR_SCALE_WS_BYTES, dtype=torch.uint8, device=device)
+
+
+def nvfp4_46_tensor_scale_ws(x: torch.Tensor, workspace: torch.Tensor, layout: int = ROWWISE,
+                             rht: int = 0, rht_seed: int = 0, fp8_max: float = 256.0,
+                             out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """nvfp4_46_tensor_scale in one launch, with a caller-owned zeroed workspace."""
+    rows, cols = _shape_of(x)
+    alpha = out if out is not None else torch.empty(1, dtype=torch.float32, device=x.device)
+    p = make_params(rows, cols, layout=layout, rht=rht, rht_seed=rht_seed, fp8_max=fp8_max,
+                    x_dtype=x_dtype_of(x))
+    _check(tensor_scale_ws_raw(x, p, alpha, workspace, workspace.numel(), stream),
+           "nvfp4_46_tensor_scale_ws")
     return alpha
 
 

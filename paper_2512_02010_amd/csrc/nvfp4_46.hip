@@ -127,12 +127,28 @@ NV_DEV float wave_max(float m) {
   return m;
 }
 
+// Where a reduction kernel leaves its result.  Plain form (finish == nullptr): `amax_bits` is
+// the caller's alpha word, zeroed by a launch before and turned into alpha by a launch after.
+// One-launch form: `amax_bits` and `finish->ticket` are two words of scratch memory that are
+// zero when the kernel starts; the workgroup that draws the last ticket applies Eq. (1),
+// writes alpha and leaves both words zero again.
+struct AmaxFinish {
+  uint32_t *ticket;
+  float *alpha;
+  float fp8_max;
+};
+
+// Eq. (1): alpha = amax / (6 * fp8_max); an all-zero tensor gets alpha = 1.
+NV_DEV float alpha_of(float amax, float fp8_max) {
+  return (amax == 0.0f) ? 1.0f : amax / (6.0f * fp8_max);
+}
+
 // Fold a workgroup's maximum magnitude into the global one.  Bit patterns of
 // non-negative floats order like the values, so an integer atomic max is exact
 // and order-free.  All atomics hit one address and serialise in L2, hence one
 // per workgroup at most, and none when a plain read already shows a value that
 // is at least as large (the value only ever grows).
-NV_DEV void publish_amax(float m, uint32_t *amax_bits) {
+NV_DEV void publish_amax(float m, uint32_t *amax_bits, const AmaxFinish &fin) {
   __shared__ float wave_part[kThreads / 64];
   m = wave_max(m);
   if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = m;
@@ -141,7 +157,23 @@ NV_DEV void publish_amax(float m, uint32_t *amax_bits) {
 #pragma unroll
     for (int w = 1; w < kThreads / 64; ++w) m = fmaxf(m, wave_part[w]);
     const uint32_t bits = f2u(m);
-    if (bits > __atomic_load_n(amax_bits, __ATOMIC_RELAXED)) atomicMax(amax_bits, bits);
+    if (bits > __hip_atomic_load(amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+      // the returning form, waited for: the maximum is in before a ticket is drawn below
+      uint32_t old = __hip_atomic_fetch_max(amax_bits, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      asm volatile("s_waitcnt vmcnt(0)" : "+v"(old) : : "memory");
+    }
+    if (fin.ticket) {
+      // Device-scope atomics are carried out at the one place all compute dies share, so
+      // "carried out before" needs no cache maintenance, only program order: every
+      // workgroup's maximum is in before its ticket is drawn, and the drawer of the last
+      // ticket reads the maximum after that.
+      const uint32_t t = __hip_atomic_fetch_add(fin.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (t == gridDim.x - 1) {
+        const uint32_t top = __hip_atomic_exchange(amax_bits, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(fin.ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *fin.alpha = alpha_of(u2f(top), fin.fp8_max);
+      }
+    }
   }
 }
 
@@ -150,11 +182,7 @@ NV_DEV void publish_amax(float m, uint32_t *amax_bits) {
 #if NVFP4_46_MAIN
 __global__ void k_store_u32(uint32_t *p, uint32_t v) { *p = v; }
 
-// Eq. (1): alpha = amax / (6 * fp8_max); an all-zero tensor gets alpha = 1.
-__global__ void k_finish_alpha(float *alpha, float fp8_max) {
-  float amax = *alpha;
-  *alpha = (amax == 0.0f) ? 1.0f : amax / (6.0f * fp8_max);
-}
+__global__ void k_finish_alpha(float *alpha, float fp8_max) { *alpha = alpha_of(*alpha, fp8_max); }
 #endif
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
@@ -163,7 +191,7 @@ typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 // of an fp32 value).  Several independent 128-bit loads per lane are in flight at a time.
 template <bool XF32>
 __global__ __launch_bounds__(kThreads) void k_amax_plain(const uint4 *__restrict__ x, int64_t n16,
-                                                         uint32_t *amax_bits) {
+                                                         uint32_t *amax_bits, AmaxFinish fin) {
   u16x2 acc = {0, 0};
   uint32_t acc32 = 0;
   auto fold = [&](const uint4 &w) {
@@ -191,7 +219,7 @@ __global__ __launch_bounds__(kThreads) void k_amax_plain(const uint4 *__restrict
   }
   for (; i < n16; i += stride) fold(load_stream(x + i));
   const uint32_t top = XF32 ? acc32 : (uint32_t)(acc.x > acc.y ? acc.x : acc.y) << 16;
-  publish_amax(u2f(top), amax_bits);
+  publish_amax(u2f(top), amax_bits, fin);
 }
 
 // max|y| over the Hadamard-transformed column blocks (16 consecutive rows of one column),
@@ -203,7 +231,8 @@ __global__ __launch_bounds__(kThreads) void k_amax_plain(const uint4 *__restrict
 template <bool XF32>
 __global__ __launch_bounds__(kThreads) void k_amax_rht_col(const uint4 *__restrict__ x,
                                                            int64_t row_blocks, int64_t pieces_per_row,
-                                                           uint64_t rht_seed, uint32_t *amax_bits) {
+                                                           uint64_t rht_seed, uint32_t *amax_bits,
+                                                           AmaxFinish fin) {
   const int64_t items = row_blocks * pieces_per_row;
   const int64_t stride = (int64_t)gridDim.x * kThreads;
   float m = 0.0f;
@@ -252,7 +281,7 @@ __global__ __launch_bounds__(kThreads) void k_amax_rht_col(const uint4 *__restri
       for (int j = 0; j < 16; j += 2) m = fmaxf(m, fmaxf(fabsf(v[j]), fabsf(v[j + 1])));
     }
   }
-  publish_amax(m * 0.25f, amax_bits);
+  publish_amax(m * 0.25f, amax_bits, fin);
 }
 
 // -------------------------------------------------------- rowwise (flat)
@@ -262,7 +291,7 @@ __global__ __launch_bounds__(kThreads) void k_flat(
     const uint4 *__restrict__ x, const float *__restrict__ alpha_p, uint2 *__restrict__ codes,
     uint8_t *__restrict__ scales, uint8_t *__restrict__ choice, uint4 *__restrict__ out_bf16,
     uint32_t *amax_bits, int64_t nblocks, uint32_t nb_per_row, uint64_t sr_seed,
-    uint64_t rht_seed, uint32_t n_long, uint32_t rounds_long) {
+    uint64_t rht_seed, uint32_t n_long, uint32_t rounds_long, AmaxFinish fin) {
   __shared__ ScaleTable tab;
   // fake-quant only: a wave's 2 KiB of output is turned round in LDS so that each of its
   // two store instructions writes 1 KiB of whole cache lines (streaming stores of half
@@ -397,7 +426,7 @@ __global__ __launch_bounds__(kThreads) void k_flat(
     run(r, b);
     r += step;
   }
-  if (OUT == kOutAmax) publish_amax(amax, amax_bits);
+  if (OUT == kOutAmax) publish_amax(amax, amax_bits, fin);
 }
 
 #if NVFP4_46_MAIN
@@ -982,6 +1011,7 @@ struct FlatArgs {
   uint32_t nb_per_row;
   uint64_t sr_seed, rht_seed;
   hipStream_t stream;
+  AmaxFinish fin{nullptr, nullptr, 0.0f};   // the amax pass only
 };
 
 template <bool XF32, int ROUNDING, int SELECT, bool RHT, int OUT>
@@ -1016,7 +1046,7 @@ static int launch_flat(const FlatArgs &a) {
   }
   return launch(k_flat<XF32, ROUNDING, SELECT, RHT, OUT>, dim3((uint32_t)grid), dim3(kThreads),
                 a.stream, a.x, a.alpha, a.codes, a.scales, a.choice, a.out, a.amax, a.nblocks,
-                a.nb_per_row, a.sr_seed, a.rht_seed, (uint32_t)n_long, (uint32_t)rounds_long);
+                a.nb_per_row, a.sr_seed, a.rht_seed, (uint32_t)n_long, (uint32_t)rounds_long, a.fin);
 }
 
 template <bool XF32, int ROUNDING, int SELECT>
@@ -1192,6 +1222,47 @@ static int check_params(const void *x, const nvfp4_46_params *p, bool one_layout
   return NVFP4_OK;
 }
 
+// Eq. (1) for all three entry points.  scratch == nullptr: the reduction runs on the caller's
+// alpha word between a zeroing launch and a finishing launch.  Otherwise scratch points at
+// two zeroed words (maximum, ticket) and one launch does it all (see AmaxFinish).
+static int tensor_scale(const void *x, const nvfp4_46_params *p, float *alpha, uint32_t *scratch,
+                        hipStream_t s) {
+  if (!alpha) return NVFP4_ERR_NULL;
+  int rc = check_params(x, p, false);
+  if (rc != NVFP4_OK) return rc;
+  uint32_t *amax = scratch ? scratch : reinterpret_cast<uint32_t *>(alpha);
+  const AmaxFinish fin{scratch ? scratch + 1 : nullptr, alpha, p->fp8_max};
+  if (!scratch) {
+    rc = launch(k_store_u32, dim3(1), dim3(1), s, amax, 0u);
+    if (rc != NVFP4_OK) return rc;
+  }
+  const int64_t n = p->rows * p->cols;
+  const bool xf32 = p->x_dtype == NVFP4_X_F32;
+  const uint4 *x4 = static_cast<const uint4 *>(x);
+  if (!p->rht) {
+    // 128-bit pieces (n is a multiple of 8 by the shape checks)
+    const int64_t n16 = xf32 ? n / 4 : n / 8;
+    const dim3 grid(grid_for(n16, kAmaxWgPerCu));
+    rc = xf32 ? launch(k_amax_plain<true>, grid, dim3(kThreads), s, x4, n16, amax, fin)
+              : launch(k_amax_plain<false>, grid, dim3(kThreads), s, x4, n16, amax, fin);
+  } else if (p->layout == NVFP4_ROWWISE) {
+    FlatArgs a{xf32, x4, nullptr, nullptr, nullptr, nullptr, nullptr, amax,
+               n / 16, (uint32_t)(p->cols / 16), 0, p->rht_seed, s, fin};
+    rc = xf32 ? launch_flat<true, kRTN, kSel46, true, kOutAmax>(a)
+              : launch_flat<false, kRTN, kSel46, true, kOutAmax>(a);
+  } else {
+    // columnwise blocks (rows % 16 == 0, cols % 8 == 0): 16-byte pieces of 8 BF16 / 4 fp32 columns
+    const int64_t row_blocks = p->rows / 16, pieces = xf32 ? p->cols / 4 : p->cols / 8;
+    const dim3 grid(grid_for(row_blocks * pieces, kAmaxRhtColWgPerCu));
+    rc = xf32 ? launch(k_amax_rht_col<true>, grid, dim3(kThreads), s, x4, row_blocks, pieces,
+                       p->rht_seed, amax, fin)
+              : launch(k_amax_rht_col<false>, grid, dim3(kThreads), s, x4, row_blocks, pieces,
+                       p->rht_seed, amax, fin);
+  }
+  if (rc != NVFP4_OK || scratch) return rc;
+  return launch(k_finish_alpha, dim3(1), dim3(1), s, alpha, p->fp8_max);
+}
+
 #endif  // NVFP4_46_MAIN
 
 }  // namespace nvfp4_46
@@ -1203,38 +1274,15 @@ using namespace nvfp4_46;
 extern "C" {
 
 int nvfp4_46_tensor_scale(const void *x, const nvfp4_46_params *p, float *alpha, void *stream) {
-  if (!alpha) return NVFP4_ERR_NULL;
-  int rc = check_params(x, p, false);
-  if (rc != NVFP4_OK) return rc;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  uint32_t *amax = reinterpret_cast<uint32_t *>(alpha);
-  rc = launch(k_store_u32, dim3(1), dim3(1), s, amax, 0u);
-  if (rc != NVFP4_OK) return rc;
-  const int64_t n = p->rows * p->cols;
-  const bool xf32 = p->x_dtype == NVFP4_X_F32;
-  const uint4 *x4 = static_cast<const uint4 *>(x);
-  if (!p->rht) {
-    // 128-bit pieces (n is a multiple of 8 by the shape checks)
-    const int64_t n16 = xf32 ? n / 4 : n / 8;
-    const dim3 grid(grid_for(n16, kAmaxWgPerCu));
-    rc = xf32 ? launch(k_amax_plain<true>, grid, dim3(kThreads), s, x4, n16, amax)
-              : launch(k_amax_plain<false>, grid, dim3(kThreads), s, x4, n16, amax);
-  } else if (p->layout == NVFP4_ROWWISE) {
-    FlatArgs a{xf32, x4, nullptr, nullptr, nullptr, nullptr, nullptr, amax,
-               n / 16, (uint32_t)(p->cols / 16), 0, p->rht_seed, s};
-    rc = xf32 ? launch_flat<true, kRTN, kSel46, true, kOutAmax>(a)
-              : launch_flat<false, kRTN, kSel46, true, kOutAmax>(a);
-  } else {
-    // columnwise blocks (rows % 16 == 0, cols % 8 == 0): 16-byte pieces of 8 BF16 / 4 fp32 columns
-    const int64_t row_blocks = p->rows / 16, pieces = xf32 ? p->cols / 4 : p->cols / 8;
-    const dim3 grid(grid_for(row_blocks * pieces, kAmaxRhtColWgPerCu));
-    rc = xf32 ? launch(k_amax_rht_col<true>, grid, dim3(kThreads), s, x4, row_blocks, pieces,
-                       p->rht_seed, amax)
-              : launch(k_amax_rht_col<false>, grid, dim3(kThreads), s, x4, row_blocks, pieces,
-                       p->rht_seed, amax);
-  }
-  if (rc != NVFP4_OK) return rc;
-  return launch(k_finish_alpha, dim3(1), dim3(1), s, alpha, p->fp8_max);
+  return tensor_scale(x, p, alpha, nullptr, static_cast<hipStream_t>(stream));
+}
+
+int nvfp4_46_tensor_scale_ws(const void *x, const nvfp4_46_params *p, float *alpha,
+                             void *workspace, size_t workspace_bytes, void *stream) {
+  if (!workspace) return NVFP4_ERR_NULL;
+  if (workspace_bytes < NVFP4_46_TENSOR_SCALE_WS_BYTES) return NVFP4_ERR_PARAM;
+  if (!aligned16(workspace)) return NVFP4_ERR_ALIGN;
+  return tensor_scale(x, p, alpha, static_cast<uint32_t *>(workspace), static_cast<hipStream_t>(stream));
 }
 
 int nvfp4_46_quantize(const void *x, const nvfp4_46_params *p, const float *alpha,

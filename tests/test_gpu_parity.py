@@ -32,6 +32,17 @@ def _alpha_bits(a):
     return np.array([a], np.float32).view(np.uint32)[0]
 
 
+_WS = None
+
+
+def _workspace():
+    """One workspace for all cases: each call must leave it zeroed for the next."""
+    global _WS
+    if _WS is None:
+        _WS = B.new_workspace()
+    return _WS
+
+
 def check_case(x: torch.Tensor, layout=B.ROWWISE, rounding=B.RTN, select=B.SEL_46_MSE, rht=0,
                fp8_max=256.0, alpha_value=None, tag=""):
     """Run tensor_scale -> quantize -> dequantize -> fake_quant on the GPU and compare every
@@ -50,6 +61,10 @@ def check_case(x: torch.Tensor, layout=B.ROWWISE, rounding=B.RTN, select=B.SEL_4
         a_ref = ref.tensor_scale(xb, layout=l, rht=rht, rht_seed=RHT_SEED, fp8_max=fp8_max)
         a_gpu = B.nvfp4_46_tensor_scale(xd, layout=l, rht=rht, rht_seed=RHT_SEED, fp8_max=fp8_max)
         assert _alpha_bits(a_gpu.item()) == _alpha_bits(a_ref), (tag, l, a_gpu.item(), a_ref)
+        # the one-launch form, on a workspace that every case of this module shares
+        a_ws = B.nvfp4_46_tensor_scale_ws(xd, _workspace(), layout=l, rht=rht, rht_seed=RHT_SEED,
+                                          fp8_max=fp8_max)
+        assert _alpha_bits(a_ws.item()) == _alpha_bits(a_ref), (tag, l, "ws", a_ws.item(), a_ref)
         alphas[l] = a_gpu
     if alpha_value is not None:
         alphas = {l: torch.tensor([alpha_value], dtype=torch.float32, device="cuda") for l in layouts}
@@ -566,3 +581,19 @@ def test_tensor_larger_than_four_gibibytes():
         assert np.array_equal(_np(out["codes_row"][r0:r0 + 32]), c), r0
         assert np.array_equal(_np(out["scales_row"][r0:r0 + 32]), s), r0
         assert np.array_equal(_bits(fq[r0:r0 + 32]), d), r0
+
+
+def test_tensor_scale_workspace_is_left_zeroed_and_full_size_matches():
+    ws = B.new_workspace()
+    for name in ("c2", "c5"):
+        x = wl.make(name, 4096, 8192)
+        xb, xd = wl.bf16_bits(x), x.cuda()
+        for kw in (dict(), dict(rht=1, rht_seed=RHT_SEED), dict(rht=1, rht_seed=RHT_SEED, layout=B.COLWISE)):
+            a_ref = ref.tensor_scale(xb, **{k: (ref.COLWISE if v == B.COLWISE else v) for k, v in kw.items()})
+            for _ in range(3):
+                a = B.nvfp4_46_tensor_scale_ws(xd, ws, **kw)
+                assert _alpha_bits(a.item()) == _alpha_bits(a_ref), (name, kw)
+                assert int(ws.cpu().sum()) == 0
+    # an all-zero tensor: alpha = 1
+    z = torch.zeros((64, 256), dtype=torch.bfloat16, device="cuda")
+    assert B.nvfp4_46_tensor_scale_ws(z, ws).item() == 1.0
