@@ -145,6 +145,22 @@ int nvfp4_46_tensor_scale(const void *x, const nvfp4_46_params *p, float *alpha,
 int nvfp4_46_tensor_scale_ws(const void *x, const nvfp4_46_params *p, float *alpha,
                              void *workspace, size_t workspace_bytes, void *stream);
 
+/* nvfp4_46_tensor_scale_ws for callers that can neither allocate device memory nor lend any:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The two
+ * words of scratch live in a 256-byte static device array inside the library (one copy per
+ * GPU, held until the process ends); the call allocates nothing.  The scratch need does not
+ * grow with the tensor, so every shape the other entry points accept is accepted (rows, cols
+ * <= 2^31, rows * cols <= 2^40; beyond that ERR_SHAPE as everywhere).  Same result as
+ * nvfp4_46_tensor_scale, bit for bit.
+ * The array is zero when the library is loaded and every call's last workgroup leaves it zero
+ * again.  All calls on one GPU share it: two calls whose work may overlap on that GPU (two
+ * streams, two host threads) race and give wrong results -- use nvfp4_46_tensor_scale_ws
+ * with a workspace each for those.  The first call on a device looks the array's address up
+ * (hipGetSymbolAddress); make that call before starting a stream capture.
+ * Errors: as nvfp4_46_tensor_scale; ERR_HIP if the address lookup fails.                       */
+int nvfp4_46_tensor_scale_static(const void *x, const nvfp4_46_params *p, float *alpha,
+                                 void *stream);
+
 /* The 4/6 quantizer (Eq. (2), Eq. (3), Table 3 lines 1-14) in the requested
  * orientation(s).
  *   x           in   [rows][cols] BF16 (fp32 with x_dtype = NVFP4_X_F32)

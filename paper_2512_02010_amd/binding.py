@@ -27,7 +27,8 @@ STATUS_NAMES = {0: "NVFP4_OK", 1: "NVFP4_ERR_NULL", 2: "NVFP4_ERR_SHAPE", 3: "NV
                 4: "NVFP4_ERR_PARAM", 5: "NVFP4_ERR_UNSUPPORTED", 6: "NVFP4_ERR_HIP"}
 
 EXPORTS = (
-    "nvfp4_46_tensor_scale", "nvfp4_46_tensor_scale_ws", "nvfp4_46_quantize", "nvfp4_46_dequantize", "nvfp4_46_fake_quant",
+    "nvfp4_46_tensor_scale", "nvfp4_46_tensor_scale_ws", "nvfp4_46_tensor_scale_static",
+    "nvfp4_46_quantize", "nvfp4_46_dequantize", "nvfp4_46_fake_quant",
     "nvfp4_46_gemm", "nvfp4_46_status_string", "nvfp4_46_debug_e2m1_rtn_range", "nvfp4_46_debug_e4m3_range",
     "nvfp4_46_debug_decode_tables", "nvfp4_46_debug_bf16_range", "nvfp4_46_debug_e2m1_sr",
     "nvfp4_46_debug_philox",
@@ -71,6 +72,8 @@ def lib() -> C.CDLL:
         L.nvfp4_46_tensor_scale.argtypes = [vp, pp, vp, vp]
         L.nvfp4_46_tensor_scale_ws.restype = C.c_int
         L.nvfp4_46_tensor_scale_ws.argtypes = [vp, pp, vp, vp, C.c_size_t, vp]
+        L.nvfp4_46_tensor_scale_static.restype = C.c_int
+        L.nvfp4_46_tensor_scale_static.argtypes = [vp, pp, vp, vp]
         L.nvfp4_46_quantize.restype = C.c_int
         L.nvfp4_46_quantize.argtypes = [vp, pp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.nvfp4_46_dequantize.restype = C.c_int
@@ -142,6 +145,11 @@ def tensor_scale_ws_raw(x, params: Params, alpha, workspace, workspace_bytes: in
     return lib().nvfp4_46_tensor_scale_ws(_ptr(x), C.byref(params) if params is not None else None,
                                           _ptr(alpha), _ptr(workspace), workspace_bytes,
                                           _stream(stream))
+
+
+def tensor_scale_static_raw(x, params: Params, alpha, stream=None) -> int:
+    return lib().nvfp4_46_tensor_scale_static(_ptr(x), C.byref(params) if params is not None else None,
+                                              _ptr(alpha), _stream(stream))
 
 
 def quantize_raw(x, params, alpha, codes_row, scales_row, codes_col, scales_col, choice_row,

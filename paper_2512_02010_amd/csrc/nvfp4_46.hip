@@ -17,6 +17,8 @@
 //             staging loads, so x is read from HBM once.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "block.hpp"
 #include "launch.hpp"
 #include "nvfp4_46.h"
@@ -1283,6 +1285,34 @@ int nvfp4_46_tensor_scale_ws(const void *x, const nvfp4_46_params *p, float *alp
   if (workspace_bytes < NVFP4_46_TENSOR_SCALE_WS_BYTES) return NVFP4_ERR_PARAM;
   if (!aligned16(workspace)) return NVFP4_ERR_ALIGN;
   return tensor_scale(x, p, alpha, static_cast<uint32_t *>(workspace), static_cast<hipStream_t>(stream));
+}
+
+// Scratch of nvfp4_46_tensor_scale_static: the two words of the one-launch reduction (running
+// maximum, ticket count) in the first 8 bytes; every GPU the library runs on holds its own
+// copy until the process ends.  In host code the array's name only stands for the symbol:
+// the device address is looked up once per device and that pointer is what kernels get.
+static __device__ __align__(256) uint32_t scratch[64];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+uint32_t *g_scratch_ptr[kMaxDevices];   // per device; nullptr until that device's first call
+}  // namespace
+
+int nvfp4_46_tensor_scale_static(const void *x, const nvfp4_46_params *p, float *alpha, void *stream) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return NVFP4_ERR_HIP;
+  uint32_t *ptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+      void *sym = nullptr;
+      if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) return NVFP4_ERR_HIP;
+      g_scratch_ptr[dev] = static_cast<uint32_t *>(sym);
+    }
+    ptr = g_scratch_ptr[dev];
+  }
+  return tensor_scale(x, p, alpha, ptr, static_cast<hipStream_t>(stream));
 }
 
 int nvfp4_46_quantize(const void *x, const nvfp4_46_params *p, const float *alpha,

@@ -21,7 +21,7 @@ def _declared():
 def test_library_exports_every_declared_symbol():
     L = B.lib()
     names = _declared()
-    assert len(names) == 13
+    assert len(names) == 14
     assert sorted(B.EXPORTS) == names
     for n in names:
         assert hasattr(L, n), n
