@@ -44,8 +44,12 @@ _lib = None
 def lib() -> C.CDLL:
     global _lib
     if _lib is None:
-        build(force=False)
-        L = C.CDLL(str(_SO))
+        # NVFP4_46_REF_LIB names another build of the oracle to load instead (the mutation
+        # test points the pin tests at deliberately broken copies this way)
+        other = os.environ.get("NVFP4_46_REF_LIB")
+        if not other:
+            build(force=False)
+        L = C.CDLL(other or str(_SO))
         u8p, u16p, f32p, u32p = (C.POINTER(C.c_uint8), C.POINTER(C.c_uint16),
                                  C.POINTER(C.c_float), C.POINTER(C.c_uint32))
         i64, u64, i32, f32 = C.c_int64, C.c_uint64, C.c_int, C.c_float

@@ -111,6 +111,20 @@ def make_params(rows: int, cols: int, layout: int = ROWWISE, rounding: int = RTN
                   x_dtype)
 
 
+def _device_empty(shape, dtype, device) -> torch.Tensor:
+    return torch.empty(shape, dtype=dtype, device=device)
+
+
+# Every output tensor the helpers below create comes from this callable (shape, dtype,
+# device) -> tensor.  The GPU tests swap in an allocator that places each output inside a
+# larger sentinel-filled buffer and checks afterwards that nothing wrote past its ends.
+OUTPUT_ALLOCATOR = _device_empty
+
+
+def _new(shape, dtype, device) -> torch.Tensor:
+    return OUTPUT_ALLOCATOR(shape, dtype, device)
+
+
 def _ptr(t):
     if t is None:
         return None
@@ -193,7 +207,7 @@ def nvfp4_46_tensor_scale(x: torch.Tensor, layout: int = ROWWISE, rht: int = 0, 
                           stream=None) -> torch.Tensor:
     """alpha (1-element fp32 device tensor) of a BF16 or fp32 device tensor."""
     rows, cols = _shape_of(x)
-    alpha = out if out is not None else torch.empty(1, dtype=torch.float32, device=x.device)
+    alpha = out if out is not None else _new((1,), torch.float32, x.device)
     p = make_params(rows, cols, layout=layout, rht=rht, rht_seed=rht_seed, fp8_max=fp8_max,
                     x_dtype=x_dtype_of(x))
     _check(tensor_scale_raw(x, p, alpha, stream), "nvfp4_46_tensor_scale")
@@ -210,7 +224,7 @@ def nvfp4_46_tensor_scale_ws(x: torch.Tensor, workspace: torch.Tensor, layout: i
                              out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
     """nvfp4_46_tensor_scale in one launch, with a caller-owned zeroed workspace."""
     rows, cols = _shape_of(x)
-    alpha = out if out is not None else torch.empty(1, dtype=torch.float32, device=x.device)
+    alpha = out if out is not None else _new((1,), torch.float32, x.device)
     p = make_params(rows, cols, layout=layout, rht=rht, rht_seed=rht_seed, fp8_max=fp8_max,
                     x_dtype=x_dtype_of(x))
     _check(tensor_scale_ws_raw(x, p, alpha, workspace, workspace.numel(), stream),
@@ -223,19 +237,21 @@ def alloc_outputs(rows: int, cols: int, layout: int, device, want_choice: bool =
     """uint8 device tensors for nvfp4_46_quantize's outputs in the requested layout(s)."""
     o = dict.fromkeys(("codes_row", "scales_row", "choice_row", "codes_col", "scales_col",
                        "choice_col"))
-    u8 = dict(dtype=torch.uint8, device=device)
+    def u8(shape):
+        return _new(shape, torch.uint8, device)
+
     if layout & ROWWISE:
         srows = rows // 16 if block2d else rows
-        o["codes_row"] = torch.empty((rows, cols // 2), **u8)
-        o["scales_row"] = torch.empty((srows, cols // 16), **u8)
+        o["codes_row"] = u8((rows, cols // 2))
+        o["scales_row"] = u8((srows, cols // 16))
         if want_choice:
-            o["choice_row"] = torch.empty((srows, cols // 16), **u8)
+            o["choice_row"] = u8((srows, cols // 16))
     if layout & COLWISE:
         scols = cols // 16 if block2d else cols
-        o["codes_col"] = torch.empty((cols, rows // 2), **u8)
-        o["scales_col"] = torch.empty((scols, rows // 16), **u8)
+        o["codes_col"] = u8((cols, rows // 2))
+        o["scales_col"] = u8((scols, rows // 16))
         if want_choice:
-            o["choice_col"] = torch.empty((scols, rows // 16), **u8)
+            o["choice_col"] = u8((scols, rows // 16))
     return o
 
 
@@ -259,7 +275,7 @@ def nvfp4_46_dequantize(codes: torch.Tensor, scales: torch.Tensor, alpha: torch.
                         cols: int, layout: int = ROWWISE, out: torch.Tensor | None = None,
                         stream=None) -> torch.Tensor:
     if out is None:
-        out = torch.empty((rows, cols), dtype=torch.bfloat16, device=codes.device)
+        out = _new((rows, cols), torch.bfloat16, codes.device)
     _check(dequantize_raw(codes, scales, alpha, rows, cols, layout, out, stream),
            "nvfp4_46_dequantize")
     return out
@@ -272,7 +288,7 @@ def nvfp4_46_fake_quant(x: torch.Tensor, alpha: torch.Tensor, layout: int = ROWW
                         block2d: int = 0) -> torch.Tensor:
     rows, cols = _shape_of(x)
     if out is None:
-        out = torch.empty(x.shape, dtype=torch.bfloat16, device=x.device)
+        out = _new(tuple(x.shape), torch.bfloat16, x.device)
     p = make_params(rows, cols, layout, rounding, select, rht, sr_seed, rht_seed, fp8_max,
                     block2d, x_dtype_of(x))
     _check(fake_quant_raw(x, p, alpha, out, stream), "nvfp4_46_fake_quant")
@@ -290,8 +306,7 @@ def nvfp4_46_gemm(codes_a: torch.Tensor, scales_a: torch.Tensor, alpha_a: torch.
     assert tuple(scales_a.shape) == (M // 16 if flags & GEMM_A_TILE_SCALES else M, K // 16)
     assert tuple(scales_b.shape) == (N // 16 if flags & GEMM_B_TILE_SCALES else N, K // 16)
     if out is None:
-        out = torch.empty((M, N), device=codes_a.device,
-                          dtype=torch.float32 if out_dtype == OUT_F32 else torch.bfloat16)
+        out = _new((M, N), torch.float32 if out_dtype == OUT_F32 else torch.bfloat16, codes_a.device)
     _check(gemm_raw(codes_a, scales_a, alpha_a, codes_b, scales_b, alpha_b, M, N, K, out_dtype,
                     out, stream, flags), "nvfp4_46_gemm")
     return out
