@@ -276,6 +276,32 @@ NV_DEV bool scale_byte_at_risk(float q) {
   return near_midpoint | subnormal_range;
 }
 
+// The same for the two quotients of one block, q4 = 1.5 q6 up to rounding: the subnormal
+// range is tested once, on the union [2^-12 / 1.5, 2^-6) for q6 (a superset of both ranges:
+// more false alarms on a sliver of values, never a missed one).
+NV_DEV bool scale_bytes_at_risk(float q6, float q4) {
+  const uint32_t b6 = f2u(q6), b4 = f2u(q4);
+  const bool near_midpoint = (((b6 & 0xfffffu) - 0x7fff0u) <= 32u) | (((b4 & 0xfffffu) - 0x7fff0u) <= 32u);
+  // q4 in [2^-12, 2^-6) implies q6 >= 2^-12 / 1.51 > 2^-13 and q6 < 2^-6; q6 in its own range too
+  const bool subnormal_range = (b6 - 0x39000000u) < (0x3c800000u - 0x39000000u);
+  return near_midpoint | subnormal_range;
+}
+
+// Eq. (2) for both candidates: S_M = e4m3(b / (alpha*M)).  The quotients are first
+// approximated by one multiplication each and converted together; the exact divisions run
+// only for the rare block whose bytes could depend on the difference (so the result is always
+// that of the divisions).
+NV_DEV void block_scales(float b, const ScaleConsts &k, uint32_t &S6, uint32_t &S4) {
+  const float q6 = b * k.rc6, q4 = b * k.rc4;
+  const uint32_t both = e4m3_encode2(q6, q4);
+  S6 = both & 0xffu;
+  S4 = both >> 8;
+  if (scale_bytes_at_risk(q6, q4)) {
+    S6 = e4m3_encode(b / k.c6);
+    S4 = e4m3_encode(b / k.c4);
+  }
+}
+
 // The per-block procedure (Table 3 lines 1-14) in one pass.  DEFINED_ERRORS = false: the
 // squared-error rule compares the cheap estimates and reports through `undecided` when they
 // cannot tell (the result is then provisional).  DEFINED_ERRORS = true: the errors are
@@ -288,23 +314,15 @@ NV_DEV BlockResult quantize_block_pass(const float (&v)[16], const float (&u)[16
 #pragma unroll
   for (int i = 0; i < 16; i += 2) b = fmaxf(fmaxf(b, fabsf(v[i])), fabsf(v[i + 1]));
 
-  // Eq. (2): S_M = e4m3(b / (alpha*M)).  The quotient is first approximated by one
-  // multiplication; the exact division runs only for the rare block whose byte could
-  // depend on the difference (so the result is always that of the division).
   uint32_t S6 = 0u, S4 = 0u;
-  const float q6 = b * k.rc6, q4 = b * k.rc4;
-  bool risk = false;
-  if (SELECT != kSelForce4) {
-    S6 = e4m3_encode(q6);
-    risk |= scale_byte_at_risk(q6);
-  }
-  if (SELECT != kSelForce6) {
-    S4 = e4m3_encode(q4);
-    risk |= scale_byte_at_risk(q4);
-  }
-  if (risk) {
-    if (SELECT != kSelForce4) S6 = e4m3_encode(b / k.c6);
-    if (SELECT != kSelForce6) S4 = e4m3_encode(b / k.c4);
+  if (SELECT == kSelForce4 || SELECT == kSelForce6) {
+    // one candidate only: the same multiply-then-guard for its scale alone
+    const float c = SELECT == kSelForce4 ? k.c4 : k.c6, q = b * (SELECT == kSelForce4 ? k.rc4 : k.rc6);
+    uint32_t S = e4m3_encode(q);
+    if (scale_byte_at_risk(q)) S = e4m3_encode(b / c);
+    (SELECT == kSelForce4 ? S4 : S6) = S;
+  } else {
+    block_scales(b, k, S6, S4);
   }
 
   constexpr int kErr = SELECT == kSel46 ? (DEFINED_ERRORS ? kErrNone : kErrMseEstimate)

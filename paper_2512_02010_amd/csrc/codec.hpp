@@ -82,6 +82,11 @@ NV_DEV uint32_t e4m3_encode(float x) {
   return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(x, x, 0, false) & 0xffu;
 }
 
+// Two of them with one conversion instruction: byte 0 = e4m3(a), byte 1 = e4m3(b).
+NV_DEV uint32_t e4m3_encode2(float a, float b) {
+  return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(fminf(a, 448.0f), fminf(b, 448.0f), 0, false) & 0xffffu;
+}
+
 // --------------------------------------------------------------- Philox
 
 // a ^ b ^ c in one instruction (v_bitop3_b32 with the truth table of a 3-input XOR)

@@ -812,14 +812,9 @@ __global__ __launch_bounds__(kThreads) void k_block2d(
 #pragma unroll
     for (int m = 1; m < 16; m <<= 1) b = fmaxf(b, __shfl_xor(b, m, 64));
 
-    // Eq. (2) for the tile: one multiplication, the division only where the scale byte could
-    // depend on the difference (as for 1x16 blocks; the same for all sixteen lanes of the tile)
-    const float q6 = b * sc.rc6, q4 = b * sc.rc4;
-    uint32_t S6 = e4m3_encode(q6), S4 = e4m3_encode(q4);
-    if ((int)scale_byte_at_risk(q6) | (int)scale_byte_at_risk(q4)) {
-      S6 = e4m3_encode(b / sc.c6);
-      S4 = e4m3_encode(b / sc.c4);
-    }
+    // Eq. (2) for the tile, as for 1x16 blocks (the same for all sixteen lanes of the tile)
+    uint32_t S6, S4;
+    block_scales(b, sc, S6, S4);
     BlockResult r6{}, r4{};
     float E6 = 0.0f, E4 = 0.0f, enc6 = 0.0f, enc4 = 0.0f;
     if (SELECT != kSelForce4) {

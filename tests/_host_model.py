@@ -64,7 +64,7 @@ def lib() -> C.CDLL:
         L.hm_e2m1_sr.restype = None
         L.hm_e2m1_sr.argtypes = [f32p, f32p, C.c_int64, u8p]
         L.hm_block_scale.restype = C.c_int
-        L.hm_block_scale.argtypes = [C.c_float, C.c_float, C.c_int]
+        L.hm_block_scale.argtypes = [C.c_float, C.c_float, C.c_int, C.c_int]
         L.hm_philox.restype = None
         L.hm_philox.argtypes = [u32p, C.c_uint32, C.c_uint32, u32p]
         L.hm_rht16.restype = None
@@ -121,7 +121,14 @@ def e2m1_sr(y: np.ndarray, u: np.ndarray) -> np.ndarray:
 
 
 def block_scale(b: float, alpha: float, M: int) -> int:
-    return lib().hm_block_scale(b, alpha, M)
+    """The byte for one M as the always-6 / always-4 kernels compute it."""
+    return lib().hm_block_scale(b, alpha, M, 0)
+
+
+def block_scale_pair(b: float, alpha: float):
+    """(S6, S4) as the 4/6 kernels compute them, in one go."""
+    r = lib().hm_block_scale(b, alpha, 6, 1)
+    return r & 0xFF, r >> 8
 
 
 def philox(ctr, key):

@@ -77,12 +77,8 @@ int hm_tile_decision(const float *v, const float *u, float alpha, int rounding, 
   const ScaleConsts sc = build_scale_table(tab, alpha);
   float b = 0.0f;
   for (int i = 0; i < 256; ++i) b = fmaxf(b, fabsf(v[i]));
-  const float q6 = b * sc.rc6, q4 = b * sc.rc4;
-  uint32_t S6 = e4m3_encode(q6), S4 = e4m3_encode(q4);
-  if ((int)scale_byte_at_risk(q6) | (int)scale_byte_at_risk(q4)) {
-    S6 = e4m3_encode(b / sc.c6);
-    S4 = e4m3_encode(b / sc.c4);
-  }
+  uint32_t S6, S4;
+  block_scales(b, sc, S6, S4);
   *scale6 = (uint8_t)S6;
   *scale4 = (uint8_t)S4;
   const float2 t6 = tab.e[S6], t4 = tab.e[S4];
@@ -124,10 +120,16 @@ void hm_e2m1_sr(const float *y, const float *u, int64_t n, uint8_t *out) {
   for (int64_t i = 0; i < n; ++i) out[i] = (uint8_t)e2m1_code_of_grid_value(e2m1_sr_value(y[i], u[i]));
 }
 
-// the scale byte of Eq. (2) as quantize_block computes it (multiply, guard, division)
-int hm_block_scale(float b, float alpha, int M) {
+// the scale byte of Eq. (2) as the kernels compute it (multiply, guard, division): with
+// pair != 0 both bytes at once as the 4/6 rules do (result = S6 | S4 << 8), else the one for M
+int hm_block_scale(float b, float alpha, int M, int pair) {
   ScaleTable tab;
   const ScaleConsts k = build_scale_table(tab, alpha);
+  if (pair) {
+    uint32_t S6, S4;
+    block_scales(b, k, S6, S4);
+    return (int)(S6 | (S4 << 8));
+  }
   const float q = b * (M == 6 ? k.rc6 : k.rc4);
   uint32_t S = e4m3_encode(q);
   if (scale_byte_at_risk(q)) S = e4m3_encode(b / (M == 6 ? k.c6 : k.c4));

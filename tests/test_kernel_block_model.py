@@ -143,9 +143,13 @@ def test_block_scale_shortcut_is_exact_around_every_rounding_boundary():
                     if not (b > 0):
                         continue
                     assert hm.block_scale(float(b), a32, M) == ref.block_scale(float(b), a32, float(M))
+                    assert hm.block_scale_pair(float(b), a32) == (ref.block_scale(float(b), a32, 6.0),
+                                                                 ref.block_scale(float(b), a32, 4.0))
                     n += 1
             for b in rng.lognormal(0.0, 3.0, 300).astype(np.float32):
                 assert hm.block_scale(float(b * c), a32, M) == ref.block_scale(float(b * c), a32, float(M))
+                assert hm.block_scale_pair(float(b * c), a32) == (ref.block_scale(float(b * c), a32, 6.0),
+                                                                 ref.block_scale(float(b * c), a32, 4.0))
     assert n > 15000
 
 
