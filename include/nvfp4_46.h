@@ -130,8 +130,8 @@ int nvfp4_46_tensor_scale(const void *x, const nvfp4_46_params *p, float *alpha,
                           void *stream);
 
 /* nvfp4_46_tensor_scale in one kernel launch instead of three, for callers that can lend it
- * a few bytes of device memory: the reduction keeps its running maximum and a completion
- * count there instead of in the alpha word, and the last workgroup to finish applies Eq. (1).
+ * a few KiB of device memory: the reduction keeps its running maxima and completion counts
+ * there instead of in the alpha word, and the last workgroup to finish applies Eq. (1).
  * Same result, bit for bit.
  *   workspace        in/out  at least NVFP4_46_TENSOR_SCALE_WS_BYTES bytes (device), 16-byte
  *                            aligned, owned by the caller.  Must be zero when the call's work
@@ -141,13 +141,13 @@ int nvfp4_46_tensor_scale(const void *x, const nvfp4_46_params *p, float *alpha,
  *   workspace_bytes  in      size of the workspace
  * Errors: as nvfp4_46_tensor_scale, plus workspace NULL -> ERR_NULL, too small -> ERR_PARAM,
  * misaligned -> ERR_ALIGN.                                                                      */
-#define NVFP4_46_TENSOR_SCALE_WS_BYTES 64
+#define NVFP4_46_TENSOR_SCALE_WS_BYTES 4352
 int nvfp4_46_tensor_scale_ws(const void *x, const nvfp4_46_params *p, float *alpha,
                              void *workspace, size_t workspace_bytes, void *stream);
 
 /* nvfp4_46_tensor_scale_ws for callers that can neither allocate device memory nor lend any:
- * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The two
- * words of scratch live in a 256-byte static device array inside the library (one copy per
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * scratch words live in a 4352-byte static device array inside the library (one copy per
  * GPU, held until the process ends); the call allocates nothing.  The scratch need does not
  * grow with the tensor, so every shape the other entry points accept is accepted (rows, cols
  * <= 2^31, rows * cols <= 2^40; beyond that ERR_SHAPE as everywhere).  Same result as

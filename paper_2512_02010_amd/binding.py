@@ -152,7 +152,7 @@ def tensor_scale_raw(x, params: Params, alpha, stream=None) -> int:
                                        _ptr(alpha), _stream(stream))
 
 
-TENSOR_SCALE_WS_BYTES = 64
+TENSOR_SCALE_WS_BYTES = 4352
 
 
 def tensor_scale_ws_raw(x, params: Params, alpha, workspace, workspace_bytes: int, stream=None) -> int:

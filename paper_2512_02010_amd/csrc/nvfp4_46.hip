@@ -129,54 +129,77 @@ NV_DEV float wave_max(float m) {
   return m;
 }
 
-// Where a reduction kernel leaves its result.  Plain form (finish == nullptr): `amax_bits` is
+// Where a reduction kernel leaves its result.  Plain form (scratch == nullptr): `amax_bits` is
 // the caller's alpha word, zeroed by a launch before and turned into alpha by a launch after.
-// One-launch form: `amax_bits` and `finish->ticket` are two words of scratch memory that are
-// zero when the kernel starts; the workgroup that draws the last ticket applies Eq. (1),
-// writes alpha and leaves both words zero again.
+// One-launch form: `scratch` is zeroed scratch memory (layout below); the workgroup that
+// finishes last applies Eq. (1), writes alpha, and the scratch is all zero again.
+//
+// Device-scope atomics on one address are carried out one after the other at the memory side
+// (about 15-35 ns each here: 256 workgroups that all finish together queued up for 9 of the
+// 27 us of a pass over 8192 x 8192).  So the workgroups report in a two-level tree: sixteen
+// groups, each with its own maximum and ticket words on cache lines of their own, and the
+// last workgroup of a group reports to the top pair.  Two chains of at most ~grid/16 + 16
+// atomics replace one of 2 x grid.
 struct AmaxFinish {
-  uint32_t *ticket;
+  uint32_t *scratch;   // kScratchWords words, or nullptr
   float *alpha;
   float fp8_max;
 };
+constexpr uint32_t kAmaxGroups = 16;
+constexpr uint32_t kScratchStride = 32;   // words between two slots: one 128-byte line each
+// slot g: maximum of group g; slot 16 + g: its ticket; slot 32: top maximum; slot 33: top ticket
+constexpr uint32_t kScratchWords = (2 * kAmaxGroups + 2) * kScratchStride;
+NV_DEV uint32_t *scratch_slot(uint32_t *scratch, uint32_t i) { return scratch + i * kScratchStride; }
 
 // Eq. (1): alpha = amax / (6 * fp8_max); an all-zero tensor gets alpha = 1.
 NV_DEV float alpha_of(float amax, float fp8_max) {
   return (amax == 0.0f) ? 1.0f : amax / (6.0f * fp8_max);
 }
 
-// Fold a workgroup's maximum magnitude into the global one.  Bit patterns of
-// non-negative floats order like the values, so an integer atomic max is exact
-// and order-free.  All atomics hit one address and serialise in L2, hence one
-// per workgroup at most, and none when a plain read already shows a value that
-// is at least as large (the value only ever grows).
+// max into *word, skipped when a plain read already shows a value at least as large (the
+// value only ever grows); the returning form, waited for, so that the maximum is in before
+// anything the caller does next.
+NV_DEV void atomic_max_now(uint32_t *word, uint32_t bits) {
+  if (bits > __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+    uint32_t old = __hip_atomic_fetch_max(word, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(old) : : "memory");
+  }
+}
+
+// Fold a workgroup's maximum magnitude into the global one.  Bit patterns of non-negative
+// floats order like the values, so an integer atomic max is exact and order-free.
+// Device-scope atomics are carried out at the one place all compute dies share, so "carried
+// out before" needs no cache maintenance, only program order: a workgroup's maximum is in
+// before its ticket is drawn, and whoever draws a group's (the grid's) last ticket reads the
+// maximum after that.
 NV_DEV void publish_amax(float m, uint32_t *amax_bits, const AmaxFinish &fin) {
   __shared__ float wave_part[kThreads / 64];
   m = wave_max(m);
   if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = m;
   __syncthreads();
-  if (threadIdx.x == 0) {
+  if (threadIdx.x != 0) return;
 #pragma unroll
-    for (int w = 1; w < kThreads / 64; ++w) m = fmaxf(m, wave_part[w]);
-    const uint32_t bits = f2u(m);
-    if (bits > __hip_atomic_load(amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
-      // the returning form, waited for: the maximum is in before a ticket is drawn below
-      uint32_t old = __hip_atomic_fetch_max(amax_bits, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      asm volatile("s_waitcnt vmcnt(0)" : "+v"(old) : : "memory");
-    }
-    if (fin.ticket) {
-      // Device-scope atomics are carried out at the one place all compute dies share, so
-      // "carried out before" needs no cache maintenance, only program order: every
-      // workgroup's maximum is in before its ticket is drawn, and the drawer of the last
-      // ticket reads the maximum after that.
-      const uint32_t t = __hip_atomic_fetch_add(fin.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (t == gridDim.x - 1) {
-        const uint32_t top = __hip_atomic_exchange(amax_bits, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(fin.ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *fin.alpha = alpha_of(u2f(top), fin.fp8_max);
-      }
-    }
+  for (int w = 1; w < kThreads / 64; ++w) m = fmaxf(m, wave_part[w]);
+  const uint32_t bits = f2u(m);
+  if (!fin.scratch) {
+    atomic_max_now(amax_bits, bits);
+    return;
   }
+  const uint32_t groups = gridDim.x < kAmaxGroups ? gridDim.x : kAmaxGroups;
+  const uint32_t g = blockIdx.x % groups;
+  const uint32_t members = (gridDim.x - g + groups - 1) / groups;     // workgroups b with b % groups == g
+  uint32_t *gmax = scratch_slot(fin.scratch, g), *gticket = scratch_slot(fin.scratch, kAmaxGroups + g);
+  uint32_t *top = scratch_slot(fin.scratch, 2 * kAmaxGroups), *top_ticket = scratch_slot(fin.scratch, 2 * kAmaxGroups + 1);
+  atomic_max_now(gmax, bits);
+  if (__hip_atomic_fetch_add(gticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != members - 1) return;
+  // last of its group: hand the group's maximum on and leave the group's words zero
+  const uint32_t group_bits = __hip_atomic_exchange(gmax, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(gticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  atomic_max_now(top, group_bits);
+  if (__hip_atomic_fetch_add(top_ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != groups - 1) return;
+  const uint32_t all = __hip_atomic_exchange(top, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(top_ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  *fin.alpha = alpha_of(u2f(all), fin.fp8_max);
 }
 
 // ------------------------------------------------------------ tensor scale
@@ -1245,14 +1268,14 @@ static int check_params(const void *x, const nvfp4_46_params *p, bool one_layout
 
 // Eq. (1) for all three entry points.  scratch == nullptr: the reduction runs on the caller's
 // alpha word between a zeroing launch and a finishing launch.  Otherwise scratch points at
-// two zeroed words (maximum, ticket) and one launch does it all (see AmaxFinish).
+// kScratchWords zeroed words and one launch does it all (see AmaxFinish).
 static int tensor_scale(const void *x, const nvfp4_46_params *p, float *alpha, uint32_t *scratch,
                         hipStream_t s) {
   if (!alpha) return NVFP4_ERR_NULL;
   int rc = check_params(x, p, false);
   if (rc != NVFP4_OK) return rc;
-  uint32_t *amax = scratch ? scratch : reinterpret_cast<uint32_t *>(alpha);
-  const AmaxFinish fin{scratch ? scratch + 1 : nullptr, alpha, p->fp8_max};
+  uint32_t *amax = reinterpret_cast<uint32_t *>(alpha);      // the plain form's running maximum
+  const AmaxFinish fin{scratch, alpha, p->fp8_max};
   if (!scratch) {
     rc = launch(k_store_u32, dim3(1), dim3(1), s, amax, 0u);
     if (rc != NVFP4_OK) return rc;
@@ -1306,11 +1329,12 @@ int nvfp4_46_tensor_scale_ws(const void *x, const nvfp4_46_params *p, float *alp
   return tensor_scale(x, p, alpha, static_cast<uint32_t *>(workspace), static_cast<hipStream_t>(stream));
 }
 
-// Scratch of nvfp4_46_tensor_scale_static: the two words of the one-launch reduction (running
-// maximum, ticket count) in the first 8 bytes; every GPU the library runs on holds its own
-// copy until the process ends.  In host code the array's name only stands for the symbol:
+// Scratch of nvfp4_46_tensor_scale_static: the maximum and ticket words of the one-launch
+// reduction (see AmaxFinish), 4352 bytes; every GPU the library runs on holds its own copy
+// until the process ends.  In host code the array's name only stands for the symbol:
 // the device address is looked up once per device and that pointer is what kernels get.
-static __device__ __align__(256) uint32_t scratch[64];
+static __device__ __align__(256) uint32_t scratch[kScratchWords];
+static_assert(kScratchWords * sizeof(uint32_t) == NVFP4_46_TENSOR_SCALE_WS_BYTES, "header and kernels agree on the scratch size");
 
 namespace {
 constexpr int kMaxDevices = 64;

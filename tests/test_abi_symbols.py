@@ -105,10 +105,10 @@ def test_other_entry_points_validation_codes():
     assert B.dequantize_raw(P, P, P, 32, 40, B.ROWWISE, P, stream=0) == 2
     assert B.dequantize_raw(P, P, P, 24, 64, B.COLWISE, P, stream=0) == 2
     assert B.dequantize_raw(P, P + 3, P, 32, 64, B.ROWWISE, P, stream=0) == 3
-    assert B.tensor_scale_ws_raw(P, ok, P, None, 64, stream=0) == 1
-    assert B.tensor_scale_ws_raw(P, ok, P, P, 8, stream=0) == 4
-    assert B.tensor_scale_ws_raw(P, ok, P, P + 4, 64, stream=0) == 3
-    assert B.tensor_scale_ws_raw(P, ok, None, P, 64, stream=0) == 1
+    assert B.tensor_scale_ws_raw(P, ok, P, None, 4352, stream=0) == 1
+    assert B.tensor_scale_ws_raw(P, ok, P, P, 4096, stream=0) == 4
+    assert B.tensor_scale_ws_raw(P, ok, P, P + 4, 4352, stream=0) == 3
+    assert B.tensor_scale_ws_raw(P, ok, None, P, 4352, stream=0) == 1
     L = B.lib()
     assert L.nvfp4_46_debug_e2m1_rtn_range(0, 16, None, None) == 1
     assert L.nvfp4_46_debug_e4m3_range(0, 0, C.c_void_p(P), None) == 2
