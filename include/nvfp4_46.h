@@ -241,10 +241,15 @@ int nvfp4_46_debug_decode_tables(void *out_f32, void *stream);
  * first_bits + i * stride.  out: n uint16 (device). */
 int nvfp4_46_debug_bf16_range(uint32_t first_bits, uint32_t stride, int64_t n, void *out_u16,
                               void *stream);
-/* out[i] = E2M1 code of stochastic rounding of y[i] with uniform u[i] (both fp32 device
- * arrays of n elements). */
-int nvfp4_46_debug_e2m1_sr(const float *y, const float *u, int64_t n, void *out_u8,
-                           void *stream);
+/* Stochastic rounding of y[i] (fp32, device) with the uniform u = (words[i] >> 8) * 2^-24
+ * (uint32, device), by the two device routines the kernels use:
+ *   out_u8[i]      = E2M1 code by the rule evaluated in software;
+ *   out_fast_u8[i] = E2M1 code by the conversion instruction in bits 0-3, and bit 7 set when
+ *                    the kernels would not trust that code and redo the element's block with
+ *                    the software rule.
+ * Both n bytes (device). */
+int nvfp4_46_debug_e2m1_sr(const float *y, const uint32_t *words, int64_t n, void *out_u8,
+                           void *out_fast_u8, void *stream);
 /* Philox4x32-10: ctr [n][4] (uint32, device), key words by value -> out [n][4] (device). */
 int nvfp4_46_debug_philox(const uint32_t *ctr, uint32_t key0, uint32_t key1, int64_t n,
                           uint32_t *out, void *stream);

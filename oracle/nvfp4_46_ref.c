@@ -742,6 +742,23 @@ void ref_e2m1_rtn_bits_range(uint32_t first_bits, int64_t n, uint8_t *out) {
   }
 }
 
+/* ref_e2m1_sr on n consecutive fp32 bit patterns, all with the uniform u. */
+void ref_e2m1_sr_bits_range(uint32_t first_bits, int64_t n, float u, uint8_t *out) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < n; ++i) {
+    uint32_t b = first_bits + (uint32_t)i;
+    float f;
+    memcpy(&f, &b, 4);
+    out[i] = ref_e2m1_sr(f, u);
+  }
+}
+
+/* ref_e2m1_sr on n (y, u) pairs. */
+void ref_e2m1_sr_n(const float *y, const float *u, int64_t n, uint8_t *out) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < n; ++i) out[i] = ref_e2m1_sr(y[i], u[i]);
+}
+
 void ref_e4m3_encode_bits_range(uint32_t first_bits, int64_t n, uint8_t *out) {
 #pragma omp parallel for schedule(static)
   for (int64_t i = 0; i < n; ++i) {

@@ -110,6 +110,10 @@ def lib() -> C.CDLL:
                                         f64p, f64p]
         L.ref_e2m1_rtn_bits_range.restype = None
         L.ref_e2m1_rtn_bits_range.argtypes = [C.c_uint32, i64, u8p]
+        L.ref_e2m1_sr_bits_range.restype = None
+        L.ref_e2m1_sr_bits_range.argtypes = [C.c_uint32, i64, C.c_float, u8p]
+        L.ref_e2m1_sr_n.restype = None
+        L.ref_e2m1_sr_n.argtypes = [f32p, f32p, i64, u8p]
         L.ref_e4m3_encode_bits_range.restype = None
         L.ref_e4m3_encode_bits_range.argtypes = [C.c_uint32, i64, u8p]
         _lib = L
@@ -409,6 +413,24 @@ def gemm(codes_a: np.ndarray, scales_a: np.ndarray, alpha_a: float, codes_b: np.
 def e2m1_rtn_bits_range(first_bits: int, n: int) -> np.ndarray:
     out = np.zeros(n, np.uint8)
     lib().ref_e2m1_rtn_bits_range(first_bits, n, _p(out, C.c_uint8))
+    return out
+
+
+def e2m1_sr_bits_range(first_bits: int, n: int, u: float) -> np.ndarray:
+    """e2m1_sr of the n fp32 values with bit patterns first_bits .. first_bits + n - 1, all
+    with the uniform u."""
+    out = np.empty(n, dtype=np.uint8)
+    lib().ref_e2m1_sr_bits_range(first_bits, n, u, _p(out, C.c_uint8))
+    return out
+
+
+def e2m1_sr_n(y: np.ndarray, u: np.ndarray) -> np.ndarray:
+    """e2m1_sr of n (y, u) pairs (float32 arrays)."""
+    y = np.ascontiguousarray(y, dtype=np.float32)
+    u = np.ascontiguousarray(u, dtype=np.float32)
+    assert y.shape == u.shape
+    out = np.empty(y.size, dtype=np.uint8)
+    lib().ref_e2m1_sr_n(_p(y, C.c_float), _p(u, C.c_float), y.size, _p(out, C.c_uint8))
     return out
 
 

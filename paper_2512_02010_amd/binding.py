@@ -93,7 +93,7 @@ def lib() -> C.CDLL:
         L.nvfp4_46_debug_bf16_range.restype = C.c_int
         L.nvfp4_46_debug_bf16_range.argtypes = [u32, u32, i64, vp, vp]
         L.nvfp4_46_debug_e2m1_sr.restype = C.c_int
-        L.nvfp4_46_debug_e2m1_sr.argtypes = [vp, vp, i64, vp, vp]
+        L.nvfp4_46_debug_e2m1_sr.argtypes = [vp, vp, i64, vp, vp, vp]
         L.nvfp4_46_debug_philox.restype = C.c_int
         L.nvfp4_46_debug_philox.argtypes = [vp, u32, u32, i64, vp, vp]
         _lib = L
@@ -342,12 +342,15 @@ def nvfp4_46_debug_bf16_range(first_bits: int, stride: int, n: int, device="cuda
     return out
 
 
-def nvfp4_46_debug_e2m1_sr(y: torch.Tensor, u: torch.Tensor) -> torch.Tensor:
-    assert y.dtype == torch.float32 and u.dtype == torch.float32 and y.numel() == u.numel()
-    out = torch.empty(y.numel(), dtype=torch.uint8, device=y.device)
-    _check(lib().nvfp4_46_debug_e2m1_sr(_ptr(y), _ptr(u), y.numel(), _ptr(out), _stream(None)),
-           "nvfp4_46_debug_e2m1_sr")
-    return out
+def nvfp4_46_debug_e2m1_sr(y: torch.Tensor, words: torch.Tensor):
+    """(codes by the software rule, codes by the conversion instruction with bit 7 = not trusted)
+    for fp32 values `y` and int32 random words `words` (uniform = top 24 bits)."""
+    assert y.dtype == torch.float32 and words.dtype == torch.int32 and y.numel() == words.numel()
+    out = _new(y.numel(), dtype=torch.uint8, device=y.device)
+    fast = _new(y.numel(), dtype=torch.uint8, device=y.device)
+    _check(lib().nvfp4_46_debug_e2m1_sr(_ptr(y), _ptr(words), y.numel(), _ptr(out), _ptr(fast),
+                                        _stream(None)), "nvfp4_46_debug_e2m1_sr")
+    return out, fast
 
 
 def nvfp4_46_debug_philox(ctr: torch.Tensor, key0: int, key1: int) -> torch.Tensor:

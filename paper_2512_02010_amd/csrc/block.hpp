@@ -62,6 +62,14 @@ NV_DEV uint32_t hw_pk_fp4_sel(uint32_t old, float a, float b, int sel) {
     default: return hw_pk_fp4<3>(old, a, b);
   }
 }
+NV_DEV uint32_t e2m1_sr_code_fast_sel(uint32_t old, float y, uint32_t w, float &margin, int sel) {
+  switch (sel) {
+    case 0: return e2m1_sr_code_fast<0>(old, y, w, margin);
+    case 1: return e2m1_sr_code_fast<1>(old, y, w, margin);
+    case 2: return e2m1_sr_code_fast<2>(old, y, w, margin);
+    default: return e2m1_sr_code_fast<3>(old, y, w, margin);
+  }
+}
 template <int SEL>
 NV_DEV f32x2 hw_pk_f32_fp4(uint32_t src) {
   return __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(src, 1.0f, SEL);
@@ -107,9 +115,13 @@ NV_DEV void grid8(uint32_t codes, float (&g)[8]) {
 // error: d' = fma(g, dec, -v) and a running fma(d', d', E'), i.e. two instructions per
 // element where the defining sequence (product, difference, square, tree sum, each
 // rounded) takes four.  E' is only ever used through decide_from_estimates() below.
-template <int ROUNDING, int ERR>
-NV_DEV float candidate(const float (&v)[16], const float (&u)[16], float dec, float enc,
-                       uint32_t &lo, uint32_t &hi) {
+// Stochastic rounding (rw: the elements' random words) comes in two forms: FAST_SR = true
+// rounds with the conversion instruction and lowers `sr_margin` (see e2m1_sr_code_fast: the
+// codes are only valid if sr_margin stays above kSrMarginAtRisk); FAST_SR = false applies the
+// rule in software and is always valid.
+template <int ROUNDING, int ERR, bool FAST_SR>
+NV_DEV float candidate_as(const float (&v)[16], const uint32_t (&rw)[16], float dec, float enc,
+                          uint32_t &lo, uint32_t &hi, float &sr_margin) {
   uint32_t c[2] = {0u, 0u};
   float acc[2] = {0.0f, 0.0f};
 #pragma unroll
@@ -125,10 +137,23 @@ NV_DEV float candidate(const float (&v)[16], const float (&u)[16], float dec, fl
         w = hw_pk_fp4_sel(w, v[8 * h + 2 * j] * enc, v[8 * h + 2 * j + 1] * enc, j);
       if (ERR != kErrNone) grid8(w, g);
       c[h] = w;
+    } else if (FAST_SR) {
+      // one conversion per element (only the first source position rounds as defined):
+      // even elements into the bytes of one word, odd ones into another
+      uint32_t we = 0u, wo = 0u;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        we = e2m1_sr_code_fast_sel(we, v[8 * h + 2 * j] * enc, rw[8 * h + 2 * j], sr_margin, j);
+        wo = e2m1_sr_code_fast_sel(wo, v[8 * h + 2 * j + 1] * enc, rw[8 * h + 2 * j + 1], sr_margin, j);
+      }
+      const uint32_t w = (we & 0x0f0f0f0fu) | ((wo << 4) & 0xf0f0f0f0u);
+      if (ERR != kErrNone) grid8(w, g);
+      c[h] = w;
     } else {
       // the rounded values are on the grid, so the conversion that packs them is exact
 #pragma unroll
-      for (int j = 0; j < 8; ++j) g[j] = e2m1_sr_value(v[8 * h + j] * enc, u[8 * h + j]);
+      for (int j = 0; j < 8; ++j)
+        g[j] = e2m1_sr_value(v[8 * h + j] * enc, sr_uniform_of_word(rw[8 * h + j]));
       uint32_t w = 0u;
 #pragma unroll
       for (int j = 0; j < 4; ++j) w = hw_pk_fp4_sel(w, g[2 * j], g[2 * j + 1], j);
@@ -161,6 +186,19 @@ NV_DEV float candidate(const float (&v)[16], const float (&u)[16], float dec, fl
   lo = c[0];
   hi = c[1];
   return ERR == kErrAbsMax ? fmaxf(acc[0], acc[1]) : acc[0] + acc[1];
+}
+
+// The candidate as the kernels use it: stochastic rounding by the conversion instruction,
+// redone in software for the rare block in which an element came too close to the one case
+// where the instruction's answer may differ.
+template <int ROUNDING, int ERR>
+NV_DEV float candidate(const float (&v)[16], const uint32_t (&rw)[16], float dec, float enc,
+                       uint32_t &lo, uint32_t &hi) {
+  float margin = __builtin_inff();
+  float E = candidate_as<ROUNDING, ERR, true>(v, rw, dec, enc, lo, hi, margin);
+  if (ROUNDING != kRTN && !(margin > kSrMarginAtRisk))
+    E = candidate_as<ROUNDING, ERR, false>(v, rw, dec, enc, lo, hi, margin);
+  return E;
 }
 
 // The block's squared error exactly as it is defined (Table 3 lines 5-6 / 11-12 in fp32):
@@ -307,7 +345,7 @@ NV_DEV void block_scales(float b, const ScaleConsts &k, uint32_t &S6, uint32_t &
 // cannot tell (the result is then provisional).  DEFINED_ERRORS = true: the errors are
 // evaluated exactly as defined.  The other rules are always evaluated as defined.
 template <int ROUNDING, int SELECT, bool DEFINED_ERRORS>
-NV_DEV BlockResult quantize_block_pass(const float (&v)[16], const float (&u)[16],
+NV_DEV BlockResult quantize_block_pass(const float (&v)[16], const uint32_t (&rw)[16],
                                        const ScaleConsts &k, const ScaleTable &tab,
                                        bool &undecided) {
   float b = 0.0f;
@@ -340,7 +378,7 @@ NV_DEV BlockResult quantize_block_pass(const float (&v)[16], const float (&u)[16
     r6.four = 0u;
     enc6 = t.y;
     if (!(ROUNDING == kSRAfterRtnSelect && SELECT == kSelForce6))
-      E6p = candidate<kCandRounding, kErr>(v, u, t.x, t.y, r6.lo, r6.hi);
+      E6p = candidate<kCandRounding, kErr>(v, rw, t.x, t.y, r6.lo, r6.hi);
   }
   if (SELECT != kSelForce6) {
     float2 t = tab.e[S4];
@@ -349,7 +387,7 @@ NV_DEV BlockResult quantize_block_pass(const float (&v)[16], const float (&u)[16
     r4.four = 1u;
     enc4 = t.y;
     if (!(ROUNDING == kSRAfterRtnSelect && SELECT == kSelForce4))
-      E4p = candidate<kCandRounding, kErr>(v, u, t.x, t.y, r4.lo, r4.hi);
+      E4p = candidate<kCandRounding, kErr>(v, rw, t.x, t.y, r4.lo, r4.hi);
   }
   bool four;
   if (SELECT == kSelForce6) {
@@ -367,24 +405,25 @@ NV_DEV BlockResult quantize_block_pass(const float (&v)[16], const float (&u)[16
   }
   BlockResult r = four ? r4 : r6;
   if (ROUNDING == kSRAfterRtnSelect)
-    (void)candidate<kSR, kErrNone>(v, u, r.dec, four ? enc4 : enc6, r.lo, r.hi);
+    (void)candidate<kSR, kErrNone>(v, rw, r.dec, four ? enc4 : enc6, r.lo, r.hi);
   return r;
 }
 
-// The whole per-block procedure.  `again(w, uu)` must produce the block's values (and its
-// stochastic-rounding uniforms) once more: the rare block that the estimates cannot decide
+// The whole per-block procedure.  `again(w, ww)` must produce the block's values (and its
+// stochastic-rounding words) once more: the rare block that the estimates cannot decide
 // is redone from those with the defined errors, so that nothing of the first pass has to
 // stay in registers for it -- keeping the sixteen values and both candidates alive across
 // the common path cost the rowwise kernel three of its eight waves per SIMD.
 template <int ROUNDING, int SELECT, typename Again>
-NV_DEV BlockResult quantize_block(const float (&v)[16], const float (&u)[16],
+NV_DEV BlockResult quantize_block(const float (&v)[16], const uint32_t (&rw)[16],
                                   const ScaleConsts &k, const ScaleTable &tab, Again &&again) {
   bool undecided = false;
-  BlockResult r = quantize_block_pass<ROUNDING, SELECT, false>(v, u, k, tab, undecided);
+  BlockResult r = quantize_block_pass<ROUNDING, SELECT, false>(v, rw, k, tab, undecided);
   if (SELECT == kSel46 && undecided) {
-    float w[16], uu[16];
-    again(w, uu);
-    r = quantize_block_pass<ROUNDING, SELECT, true>(w, uu, k, tab, undecided);
+    float w[16];
+    uint32_t ww[16];
+    again(w, ww);
+    r = quantize_block_pass<ROUNDING, SELECT, true>(w, ww, k, tab, undecided);
   }
   return r;
 }

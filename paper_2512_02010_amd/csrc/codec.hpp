@@ -59,6 +59,60 @@ NV_DEV float e2m1_sr_value(float y, float u) {
   return u2f(f2u(r) | (f2u(y) & 0x80000000u));
 }
 
+// v_cvt_scalef32_sr_pk_fp4_f32: byte SEL of `old` <- the stochastically rounded E2M1 codes of
+// the two values of src (first in the low nibble), the other bytes kept.  Written as inline
+// assembly because the compiler's builtin for it drops `old` (the other bytes come out as
+// whatever the destination register held); the s_nop gives the partial register write its one
+// wait state before any reader, which the compiler only inserts for instructions it emits
+// itself.  (The host-side test build of this header substitutes a description of the
+// instruction.)
+template <int SEL>
+NV_DEV uint32_t cvt_sr_pk_fp4(uint32_t old, f32x2 src, uint32_t rnd) {
+#ifdef NVFP4_46_CVT_SR_PK_FP4_ON_HOST
+  return NVFP4_46_CVT_SR_PK_FP4_ON_HOST(old, src, rnd, SEL);
+#else
+  if constexpr (SEL == 0)
+    asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, 1.0\n\ts_nop 0" : "+v"(old) : "v"(src), "v"(rnd));
+  else if constexpr (SEL == 1)
+    asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, 1.0 op_sel:[0,0,1,0]\n\ts_nop 0" : "+v"(old) : "v"(src), "v"(rnd));
+  else if constexpr (SEL == 2)
+    asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, 1.0 op_sel:[0,0,0,1]\n\ts_nop 0" : "+v"(old) : "v"(src), "v"(rnd));
+  else
+    asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, 1.0 op_sel:[0,0,1,1]\n\ts_nop 0" : "+v"(old) : "v"(src), "v"(rnd));
+  return old;
+#endif
+}
+
+// The rounding of e2m1_sr_value() by that instruction, for the element whose random word is
+// w.  Only the first source position is used: with ~w as the random operand the instruction
+// adds the operand's top 22 bits to the 22 bits below the kept mantissa bit and truncates
+// (the second position reads other bits of the operand and cannot be given an independent
+// uniform; its nibble is left to be masked off by the caller).  With k = w >> 8, so that
+// u = k * 2^-24:
+//   |y| >= 1: one step up iff (k >> 2) < (low 22 mantissa bits): exactly u < p, because p has
+//             22 bits there;
+//   |y| < 1 : the grid step is 0.5 and p = frac(2|y|); the instruction cuts |y| to a multiple
+//             of 2^-23 first, i.e. compares k >> 2 with P = floor(|y| * 2^23) mod 2^22.  That
+//             is u < p unless k >> 2 == P, which implies |A - k| < 4 for A = |y| * 2^25 (below
+//             0.5) or A = |y| * 2^25 - 2^24 (from 0.5 up).
+// Magnitudes above 6 give 6, the sign bit is the input's also when the magnitude becomes 0.
+// (The GPU tests compare the instruction, used this way, with the CPU oracle and with this
+// description on every fp32 value, for several words.)  `margin` is lowered to the smaller of
+// the two |A - k| where that is smaller still (each computed with an error below 1.5): a caller
+// that finds margin <= kSrMarginAtRisk after a group of elements must redo the group with
+// e2m1_sr_value().  Returns `old` with the low nibble of byte SEL replaced by the code; the
+// high nibble of that byte is left undefined.
+template <int SEL>
+NV_DEV uint32_t e2m1_sr_code_fast(uint32_t old, float y, uint32_t w, float &margin) {
+  const float t = __builtin_fmaf(fabsf(y), 0x1p25f, -(float)(w >> 8));
+  margin = fminf(fminf(margin, fabsf(t)), fabsf(t - 0x1p24f));   // one v_min3_f32
+  // the second source position only has to be some register: t is at hand, and as a value
+  // computed here it can be placed next to y without a copy
+  const f32x2 src = {y, t};
+  return cvt_sr_pk_fp4<SEL>(old, src, ~w);
+}
+constexpr float kSrMarginAtRisk = 6.0f;
+
 // Code of a value that is already on the grid (sign included).
 NV_DEV uint32_t e2m1_code_of_grid_value(float r) {
   uint32_t u = f2u(r);
@@ -115,13 +169,15 @@ NV_DEV Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
   return Philox4{{c0, c1, c2, c3}};
 }
 
-// The four uniforms of the element group q = g >> 2 (g = flat element index).
-NV_DEV void sr_uniforms4(uint64_t seed, uint64_t q, float u[4]) {
+// The four random words of the element group q = g >> 2 (g = flat element index).  An
+// element's uniform is the top 24 bits of its word, u = (w >> 8) * 2^-24.
+NV_DEV void sr_words4(uint64_t seed, uint64_t q, uint32_t w[4]) {
   Philox4 p = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), 0u, 0u, (uint32_t)seed,
                             (uint32_t)(seed >> 32));
 #pragma unroll
-  for (int j = 0; j < 4; ++j) u[j] = (float)(p.w[j] >> 8) * 0x1p-24f;
+  for (int j = 0; j < 4; ++j) w[j] = p.w[j];
 }
+NV_DEV float sr_uniform_of_word(uint32_t w) { return (float)(w >> 8) * 0x1p-24f; }
 
 // Sign word of the block at position B along the blocked axis (bit j = negate element j).
 NV_DEV uint32_t rht_sign_word(uint64_t seed, uint64_t B) {

@@ -346,7 +346,8 @@ __global__ __launch_bounds__(kThreads) void k_flat(
   using Raw = RawBlock<XF32>;
   auto work = [&](uint32_t r, uint32_t live, const Raw &raw) {
     const int64_t base = (int64_t)r * kThreads;
-    float v[16], u[16];
+    float v[16];
+    uint32_t u[16];
     unpack16(raw, v);
     if (RHT) {
       // the sign word depends on the block's position in its row only; with the usual
@@ -364,15 +365,15 @@ __global__ __launch_bounds__(kThreads) void k_flat(
       for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(v[i]));
       return;
     }
-    auto uniforms = [&](float (&uu)[16]) {
+    auto uniforms = [&](uint32_t (&uu)[16]) {
       const uint64_t q0 = ((uint64_t)base + tid) * 4u;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) sr_uniforms4(sr_seed, q0 + j, &uu[4 * j]);
+      for (int j = 0; j < 4; ++j) sr_words4(sr_seed, q0 + j, &uu[4 * j]);
     };
     if (ROUNDING != kRTN) uniforms(u);
     // the block once more, from memory (a lane without a block of its own holds a copy of
     // the round's last block, as fetch() gave it)
-    auto again = [&](float (&w)[16], float (&uu)[16]) {
+    auto again = [&](float (&w)[16], uint32_t (&uu)[16]) {
       Raw r2;
       load_block<XF32>(x + Raw::kPieces * (base + (tid < live ? tid : live - 1)), r2);
       unpack16(r2, w);
@@ -414,9 +415,9 @@ __global__ __launch_bounds__(kThreads) void k_flat(
   // stored), because they store pieces of their neighbours' blocks; elsewhere they skip
   // the round.
   // The loads are unconditional (a conditional load would have to be waited for right
-  // where the two control paths join): a round past the workgroup's share re-reads its
-  // current round and a lane past the end of a ragged last round re-reads that round's
-  // last block; what they fetch is never used.
+  // where the two control paths join): a round past the workgroup's share re-reads round 0
+  // (every workgroup ends with that, so the L2 serves it) and a lane past the end of a ragged
+  // last round re-reads that round's last block; what they fetch is never used.
   uint32_t r, step, end;
   if (blockIdx.x < n_long) {
     r = blockIdx.x;
@@ -427,9 +428,8 @@ __global__ __launch_bounds__(kThreads) void k_flat(
     step = gridDim.x - n_long;
     end = rounds;
   }
-  // A round past the workgroup's share re-reads its current round (never used).
   auto fetch = [&](uint32_t next, Raw &raw) {
-    const uint32_t rr = next < end ? next : r;
+    const uint32_t rr = next < end ? next : 0u;
     const uint32_t last = lanes_in_round(rr) - 1;
     const uint32_t lane = tid < last ? tid : last;
     const uint4 *xb = x + Raw::kPieces * ((int64_t)rr * kThreads);
@@ -587,10 +587,11 @@ __global__ __launch_bounds__(kThreads) void k_tile(
       const int row = unit / kRowBlocksPerTileRow, rbk = unit % kRowBlocksPerTileRow;
       const int64_t gr = r0 + row, gc = c0 + rbk * 16;
       if (gr < rows && gc < cols) {
-        float v[16], u[16];
+        float v[16];
+        uint32_t u[16];
         const int64_t k = gr * nb_per_row + (gc >> 4);
-        // the lane's block out of the tile, with its uniforms
-        auto take = [&](float (&w)[16], float (&uu)[16]) {
+        // the lane's block out of the tile, with its random words
+        auto take = [&](float (&w)[16], uint32_t (&uu)[16]) {
           const uint4 *own = reinterpret_cast<const uint4 *>(tile) + unit * Raw::kPieces;
           Raw mine;
 #pragma unroll
@@ -598,7 +599,7 @@ __global__ __launch_bounds__(kThreads) void k_tile(
           unpack16(mine, w);
           if (ROUNDING != kRTN) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) sr_uniforms4(sr_seed, (uint64_t)k * 4u + q, &uu[4 * q]);
+            for (int q = 0; q < 4; ++q) sr_words4(sr_seed, (uint64_t)k * 4u + q, &uu[4 * q]);
           }
         };
         take(v, u);
@@ -620,9 +621,10 @@ __global__ __launch_bounds__(kThreads) void k_tile(
     const int64_t gr = r0 + rb * 16;              // first row of the block
     const int64_t gc = c0 + 2 * cp;               // even column of the pair
     if (gr >= rows || gc >= cols) continue;       // (cols is even, so the pair is in or out together)
-    float va[16], vb[16], ua[16], ub[16];
-    // the lane's two column blocks (transformed, with their uniforms) out of the tile or memory
-    auto take = [&](float (&wa)[16], float (&wb)[16], float (&uua)[16], float (&uub)[16]) {
+    float va[16], vb[16];
+    uint32_t ua[16], ub[16];
+    // the lane's two column blocks (transformed, with their random words) out of the tile or memory
+    auto take = [&](float (&wa)[16], float (&wb)[16], uint32_t (&uua)[16], uint32_t (&uub)[16]) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         if constexpr (XF32) {
@@ -649,20 +651,22 @@ __global__ __launch_bounds__(kThreads) void k_tile(
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const uint64_t g = (uint64_t)(gr + i) * (uint64_t)cols + (uint64_t)gc;
-          float uu[4];
-          sr_uniforms4(sr_seed, g >> 2, uu);
+          uint32_t uu[4];
+          sr_words4(sr_seed, g >> 2, uu);
           uua[i] = (g & 2u) ? uu[2] : uu[0];
           uub[i] = (g & 2u) ? uu[3] : uu[1];
         }
       }
     };
     take(va, vb, ua, ub);
-    BlockResult ra = quantize_block<ROUNDING, SELECT>(va, ua, sc, tab, [&](float (&w)[16], float (&uu)[16]) {
-      float other[16], other_u[16];
+    BlockResult ra = quantize_block<ROUNDING, SELECT>(va, ua, sc, tab, [&](float (&w)[16], uint32_t (&uu)[16]) {
+      float other[16];
+      uint32_t other_u[16];
       take(w, other, uu, other_u);
     });
-    BlockResult rbk = quantize_block<ROUNDING, SELECT>(vb, ub, sc, tab, [&](float (&w)[16], float (&uu)[16]) {
-      float other[16], other_u[16];
+    BlockResult rbk = quantize_block<ROUNDING, SELECT>(vb, ub, sc, tab, [&](float (&w)[16], uint32_t (&uu)[16]) {
+      float other[16];
+      uint32_t other_u[16];
       take(other, w, other_u, uu);
     });
     if (OUT == kOutCodes) {
@@ -837,11 +841,12 @@ __global__ __launch_bounds__(kThreads) void k_block2d(
     const int64_t first = row * cols + tc * 16;           // flat index of the lane's first element
     RawBlock<XF32> raw;
     load_block<XF32>(static_cast<const uint4 *>(x_any) + first / (XF32 ? 4 : 8), raw);
-    float v[16], u[16];
+    float v[16];
+    uint32_t u[16];
     unpack16(raw, v);
     if (ROUNDING != kRTN) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) sr_uniforms4(sr_seed, (uint64_t)(first >> 2) + j, &u[4 * j]);
+      for (int j = 0; j < 4; ++j) sr_words4(sr_seed, (uint64_t)(first >> 2) + j, &u[4 * j]);
     }
     float b = 0.0f;
 #pragma unroll
@@ -988,10 +993,15 @@ __global__ void k_dbg_bf16(uint32_t first, uint32_t stride_bits, int64_t n, uint
     out[i] = (uint16_t)pack_bf16x2(u2f(first + (uint32_t)i * stride_bits), 0.0f);
 }
 
-__global__ void k_dbg_e2m1_sr(const float *y, const float *u, int64_t n, uint8_t *out) {
+__global__ void k_dbg_e2m1_sr(const float *y, const uint32_t *w, int64_t n, uint8_t *out,
+                              uint8_t *out_fast) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
-    out[i] = (uint8_t)e2m1_code_of_grid_value(e2m1_sr_value(y[i], u[i]));
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+    out[i] = (uint8_t)e2m1_code_of_grid_value(e2m1_sr_value(y[i], sr_uniform_of_word(w[i])));
+    float margin = __builtin_inff();
+    const uint32_t code = e2m1_sr_code_fast<0>(0u, y[i], w[i], margin) & 0x0fu;
+    out_fast[i] = (uint8_t)(code | (margin > kSrMarginAtRisk ? 0u : 0x80u));
+  }
 }
 
 __global__ void k_dbg_philox(const uint32_t *ctr, uint32_t k0, uint32_t k1, int64_t n,
@@ -1493,11 +1503,13 @@ int nvfp4_46_debug_bf16_range(uint32_t first_bits, uint32_t stride, int64_t n, v
                 static_cast<uint16_t *>(out_u16));
 }
 
-int nvfp4_46_debug_e2m1_sr(const float *y, const float *u, int64_t n, void *out_u8, void *stream) {
-  if (!y || !u || !out_u8) return NVFP4_ERR_NULL;
+int nvfp4_46_debug_e2m1_sr(const float *y, const uint32_t *words, int64_t n, void *out_u8,
+                           void *out_fast_u8, void *stream) {
+  if (!y || !words || !out_u8 || !out_fast_u8) return NVFP4_ERR_NULL;
   if (n <= 0) return NVFP4_ERR_SHAPE;
   return launch(k_dbg_e2m1_sr, dim3(grid_for(n, 8)), dim3(kThreads),
-                static_cast<hipStream_t>(stream), y, u, n, static_cast<uint8_t *>(out_u8));
+                static_cast<hipStream_t>(stream), y, words, n, static_cast<uint8_t *>(out_u8),
+                static_cast<uint8_t *>(out_fast_u8));
 }
 
 int nvfp4_46_debug_philox(const uint32_t *ctr, uint32_t key0, uint32_t key1, int64_t n,

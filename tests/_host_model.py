@@ -62,7 +62,7 @@ def lib() -> C.CDLL:
         L.hm_tile_decision.restype = C.c_int
         L.hm_tile_decision.argtypes = [f32p, f32p, C.c_float, C.c_int, u8p, u8p, C.POINTER(C.c_int)]
         L.hm_e2m1_sr.restype = None
-        L.hm_e2m1_sr.argtypes = [f32p, f32p, C.c_int64, u8p]
+        L.hm_e2m1_sr.argtypes = [f32p, f32p, C.c_int64, u8p, u8p]
         L.hm_block_scale.restype = C.c_int
         L.hm_block_scale.argtypes = [C.c_float, C.c_float, C.c_int, C.c_int]
         L.hm_philox.restype = None
@@ -112,12 +112,15 @@ def tile_decision(v: np.ndarray, alpha: float, rounding: int = RTN, u: np.ndarra
     return four, s6.value, s4.value, path.value
 
 
-def e2m1_sr(y: np.ndarray, u: np.ndarray) -> np.ndarray:
+def e2m1_sr(y: np.ndarray, u: np.ndarray):
+    """(codes by the software rule, codes by the conversion instruction | 0x80 where the
+    kernels would redo the block in software)."""
     y = np.ascontiguousarray(y, dtype=np.float32)
     u = np.ascontiguousarray(u, dtype=np.float32)
     out = np.zeros(y.shape, np.uint8)
-    lib().hm_e2m1_sr(_p(y, C.c_float), _p(u, C.c_float), y.size, _p(out, C.c_uint8))
-    return out
+    fast = np.zeros(y.shape, np.uint8)
+    lib().hm_e2m1_sr(_p(y, C.c_float), _p(u, C.c_float), y.size, _p(out, C.c_uint8), _p(fast, C.c_uint8))
+    return out, fast
 
 
 def block_scale(b: float, alpha: float, M: int) -> int:

@@ -10,11 +10,15 @@ namespace {
 
 int g_second_passes = 0;   // blocks that the estimates could not decide
 
+// a uniform k * 2^-24 as the random word whose top 24 bits are k (the low byte, which nothing
+// may depend on, is filled with a pattern)
+uint32_t word_of(float u) { return ((uint32_t)(u * 0x1p24f) << 8) | 0xa5u; }
+
 template <int ROUNDING>
-BlockResult run_block(const float (&v)[16], const float (&u)[16], const ScaleConsts &k,
+BlockResult run_block(const float (&v)[16], const uint32_t (&u)[16], const ScaleConsts &k,
                       const ScaleTable &tab, int select) {
   // the kernels fetch the block again from memory; here it is simply copied
-  auto again = [&](float (&w)[16], float (&uu)[16]) {
+  auto again = [&](float (&w)[16], uint32_t (&uu)[16]) {
     ++g_second_passes;
     for (int i = 0; i < 16; ++i) {
       w[i] = v[i];
@@ -53,10 +57,11 @@ void hm_quantize_blocks(const float *v, const float *u, int64_t n, float alpha, 
   ScaleTable tab;
   const ScaleConsts k = build_scale_table(tab, alpha);
   for (int64_t b = 0; b < n; ++b) {
-    float vv[16], uu[16];
+    float vv[16];
+    uint32_t uu[16];
     for (int i = 0; i < 16; ++i) {
       vv[i] = v[16 * b + i];
-      uu[i] = u ? u[16 * b + i] : 0.0f;
+      uu[i] = u ? word_of(u[16 * b + i]) : 0u;
     }
     const BlockResult r = rounding == kRTN  ? run_block<kRTN>(vv, uu, k, tab, select)
                           : rounding == kSR ? run_block<kSR>(vv, uu, k, tab, select)
@@ -84,10 +89,11 @@ int hm_tile_decision(const float *v, const float *u, float alpha, int rounding, 
   const float2 t6 = tab.e[S6], t4 = tab.e[S4];
   float E6[16], E4[16], e6[16], e4[16];
   for (int r = 0; r < 16; ++r) {
-    float vv[16], uu[16];
+    float vv[16];
+    uint32_t uu[16];
     for (int i = 0; i < 16; ++i) {
       vv[i] = v[16 * r + i];
-      uu[i] = u ? u[16 * r + i] : 0.0f;
+      uu[i] = u ? word_of(u[16 * r + i]) : 0u;
     }
     uint32_t lo6, hi6, lo4, hi4;
     if (rounding == kSR) {
@@ -115,9 +121,16 @@ int hm_tile_decision(const float *v, const float *u, float alpha, int rounding, 
   return four ? 1 : 0;
 }
 
-// e2m1_sr_value on n (y, u) pairs -> codes
-void hm_e2m1_sr(const float *y, const float *u, int64_t n, uint8_t *out) {
-  for (int64_t i = 0; i < n; ++i) out[i] = (uint8_t)e2m1_code_of_grid_value(e2m1_sr_value(y[i], u[i]));
+// stochastic rounding of n (y, u) pairs by the two device routines: the rule in software, and
+// the conversion instruction (code in bits 0-3, bit 7 = the kernels would not trust it)
+void hm_e2m1_sr(const float *y, const float *u, int64_t n, uint8_t *out, uint8_t *out_fast) {
+  for (int64_t i = 0; i < n; ++i) {
+    const uint32_t w = word_of(u[i]);
+    out[i] = (uint8_t)e2m1_code_of_grid_value(e2m1_sr_value(y[i], sr_uniform_of_word(w)));
+    float margin = __builtin_inff();
+    const uint32_t code = e2m1_sr_code_fast<0>(0u, y[i], w, margin) & 0x0fu;
+    out_fast[i] = (uint8_t)(code | (margin > kSrMarginAtRisk ? 0u : 0x80u));
+  }
 }
 
 // the scale byte of Eq. (2) as the kernels compute it (multiply, guard, division): with
