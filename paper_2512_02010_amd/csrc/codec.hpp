@@ -66,13 +66,18 @@ NV_DEV float e2m1_sr_value(float y, float u) {
 // wait state before any reader, which the compiler only inserts for instructions it emits
 // itself.  (The host-side test build of this header substitutes a description of the
 // instruction.)
+// SEL = kSrFirstByteOfNewWord writes byte 0 and leaves the other three bytes undefined (no
+// previous word has to be brought into the destination register).
+constexpr int kSrFirstByteOfNewWord = 4;
 template <int SEL>
 NV_DEV uint32_t cvt_sr_pk_fp4(uint32_t old, f32x2 src, uint32_t rnd) {
 #ifdef NVFP4_46_CVT_SR_PK_FP4_ON_HOST
-  return NVFP4_46_CVT_SR_PK_FP4_ON_HOST(old, src, rnd, SEL);
+  return NVFP4_46_CVT_SR_PK_FP4_ON_HOST(old, src, rnd, SEL & 3);
 #else
   if constexpr (SEL == 0)
     asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, 1.0\n\ts_nop 0" : "+v"(old) : "v"(src), "v"(rnd));
+  else if constexpr (SEL == kSrFirstByteOfNewWord)
+    asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, 1.0\n\ts_nop 0" : "=v"(old) : "v"(src), "v"(rnd));
   else if constexpr (SEL == 1)
     asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, 1.0 op_sel:[0,0,1,0]\n\ts_nop 0" : "+v"(old) : "v"(src), "v"(rnd));
   else if constexpr (SEL == 2)
@@ -84,7 +89,9 @@ NV_DEV uint32_t cvt_sr_pk_fp4(uint32_t old, f32x2 src, uint32_t rnd) {
 }
 
 // The rounding of e2m1_sr_value() by that instruction, for the element whose random word is
-// w.  Only the first source position is used: with ~w as the random operand the instruction
+// w (passed as not_w = ~w and k = (float)(w >> 8), which a caller rounding the same element
+// under several scales computes once).  Only the first source position is used: with ~w as
+// the random operand the instruction
 // adds the operand's top 22 bits to the 22 bits below the kept mantissa bit and truncates
 // (the second position reads other bits of the operand and cannot be given an independent
 // uniform; its nibble is left to be masked off by the caller).  With k = w >> 8, so that
@@ -102,14 +109,24 @@ NV_DEV uint32_t cvt_sr_pk_fp4(uint32_t old, f32x2 src, uint32_t rnd) {
 // that finds margin <= kSrMarginAtRisk after a group of elements must redo the group with
 // e2m1_sr_value().  Returns `old` with the low nibble of byte SEL replaced by the code; the
 // high nibble of that byte is left undefined.
+// A constant the compiler must keep in a vector register: it would otherwise put a literal
+// used this often into a scalar register, and an fp32 instruction with a scalar-register source
+// issues at half the rate (measured: v_fma_f32 2.7 against 4.2 cycles per wave and SIMD).
+NV_DEV float in_vector_register(float c) {
+#ifndef NVFP4_46_CVT_SR_PK_FP4_ON_HOST
+  asm("v_mov_b32 %0, %1" : "=v"(c) : "s"(c));
+#endif
+  return c;
+}
+
 template <int SEL>
-NV_DEV uint32_t e2m1_sr_code_fast(uint32_t old, float y, uint32_t w, float &margin) {
-  const float t = __builtin_fmaf(fabsf(y), 0x1p25f, -(float)(w >> 8));
+NV_DEV uint32_t e2m1_sr_code_fast(uint32_t old, float y, uint32_t not_w, float k, float &margin) {
+  const float t = __builtin_fmaf(fabsf(y), in_vector_register(0x1p25f), -k);
   margin = fminf(fminf(margin, fabsf(t)), fabsf(t - 0x1p24f));   // one v_min3_f32
   // the second source position only has to be some register: t is at hand, and as a value
   // computed here it can be placed next to y without a copy
   const f32x2 src = {y, t};
-  return cvt_sr_pk_fp4<SEL>(old, src, ~w);
+  return cvt_sr_pk_fp4<SEL>(old, src, not_w);
 }
 constexpr float kSrMarginAtRisk = 6.0f;
 
@@ -177,7 +194,8 @@ NV_DEV void sr_words4(uint64_t seed, uint64_t q, uint32_t w[4]) {
 #pragma unroll
   for (int j = 0; j < 4; ++j) w[j] = p.w[j];
 }
-NV_DEV float sr_uniform_of_word(uint32_t w) { return (float)(w >> 8) * 0x1p-24f; }
+NV_DEV float sr_k_of_word(uint32_t w) { return (float)(w >> 8); }   // exact: 24 bits
+NV_DEV float sr_uniform_of_k(float k) { return k * 0x1p-24f; }
 
 // Sign word of the block at position B along the blocked axis (bit j = negate element j).
 NV_DEV uint32_t rht_sign_word(uint64_t seed, uint64_t B) {
@@ -187,10 +205,8 @@ NV_DEV uint32_t rht_sign_word(uint64_t seed, uint64_t B) {
 
 // ------------------------------------------------------------ Hadamard
 
-// v <- (1/4) H16 (s .* v): sign flips, then butterflies with strides 1, 2, 4, 8.
-NV_DEV void rht16(float (&v)[16], uint32_t sign_word) {
-#pragma unroll
-  for (int j = 0; j < 16; ++j) v[j] = u2f(f2u(v[j]) ^ (((sign_word >> j) & 1u) << 31));
+// v <- (1/4) H16 v: butterflies with strides 1, 2, 4, 8.
+NV_DEV void hadamard16_quarter(float (&v)[16]) {
 #pragma unroll
   for (int h = 1; h < 16; h <<= 1) {
 #pragma unroll
@@ -204,6 +220,24 @@ NV_DEV void rht16(float (&v)[16], uint32_t sign_word) {
   }
 #pragma unroll
   for (int j = 0; j < 16; ++j) v[j] *= 0.25f;
+}
+// v <- (1/4) H16 (s .* v): sign flips (bit j of sign_word negates element j), then the butterflies.
+NV_DEV void rht16(float (&v)[16], uint32_t sign_word) {
+#pragma unroll
+  for (int j = 0; j < 16; ++j) v[j] = u2f(f2u(v[j]) ^ (((sign_word >> j) & 1u) << 31));
+  hadamard16_quarter(v);
+}
+
+// The same with the sign flips given as sixteen XOR masks (0 or 0x80000000), for callers
+// that meet the same sign word block after block.
+NV_DEV void rht_sign_masks(uint32_t sign_word, uint32_t (&mask)[16]) {
+#pragma unroll
+  for (int j = 0; j < 16; ++j) mask[j] = ((sign_word >> j) & 1u) << 31;
+}
+NV_DEV void rht16_masked(float (&v)[16], const uint32_t (&mask)[16]) {
+#pragma unroll
+  for (int j = 0; j < 16; ++j) v[j] = u2f(f2u(v[j]) ^ mask[j]);
+  hadamard16_quarter(v);
 }
 
 }  // namespace nvfp4_46

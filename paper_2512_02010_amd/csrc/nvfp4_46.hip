@@ -334,8 +334,24 @@ __global__ __launch_bounds__(kThreads) void k_flat(
   const uint32_t tid = threadIdx.x;
   const uint32_t rounds = (uint32_t)((nblocks + kThreads - 1) / kThreads);
   const uint32_t tail = (uint32_t)(nblocks - (int64_t)(rounds - 1) * kThreads);  // 1..256
-  uint32_t B_lane = 0, sign_B = 0xffffffffu, sign_word = 0;
+  // The sign flips of the transform as sixteen XOR masks per lane, in LDS (piece q of lane t at
+  // [q][t]: a wave's 128-bit reads are conflict-free).  A lane writes and reads only its own
+  // slots, and the LDS operations of one wave execute in order, so no barrier is involved.
+  __shared__ uint4 sign_masks[RHT ? 4 : 1][RHT ? kThreads : 1];
+  uint32_t B_lane = 0, sign_B = 0xffffffffu;
   if (RHT) B_lane = tid % nb_per_row;
+  auto transform = [&](float (&w)[16]) {
+    uint32_t mask[16];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const uint4 m = sign_masks[q][tid];
+      mask[4 * q] = m.x;
+      mask[4 * q + 1] = m.y;
+      mask[4 * q + 2] = m.z;
+      mask[4 * q + 3] = m.w;
+    }
+    rht16_masked(w, mask);
+  };
   float amax = 0.0f;
   ScaleConsts sc{};
 
@@ -351,14 +367,18 @@ __global__ __launch_bounds__(kThreads) void k_flat(
     unpack16(raw, v);
     if (RHT) {
       // the sign word depends on the block's position in its row only; with the usual
-      // shapes a lane meets the same position in every round and keeps the word
+      // shapes a lane meets the same position in every round and keeps its masks
       uint32_t B = (uint32_t)(base % nb_per_row) + B_lane;
       if (B >= nb_per_row) B -= nb_per_row;
       if (B != sign_B) {
         sign_B = B;
-        sign_word = rht_sign_word(rht_seed, B);
+        uint32_t mask[16];
+        rht_sign_masks(rht_sign_word(rht_seed, B), mask);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          sign_masks[q][tid] = make_uint4(mask[4 * q], mask[4 * q + 1], mask[4 * q + 2], mask[4 * q + 3]);
       }
-      rht16(v, sign_word);
+      transform(v);
     }
     if (OUT == kOutAmax) {
 #pragma unroll
@@ -377,7 +397,7 @@ __global__ __launch_bounds__(kThreads) void k_flat(
       Raw r2;
       load_block<XF32>(x + Raw::kPieces * (base + (tid < live ? tid : live - 1)), r2);
       unpack16(r2, w);
-      if (RHT) rht16(w, sign_word);
+      if (RHT) transform(w);
       if (ROUNDING != kRTN) uniforms(uu);
     };
     const BlockResult res = quantize_block<ROUNDING, SELECT>(v, u, sc, tab, again);
@@ -997,9 +1017,10 @@ __global__ void k_dbg_e2m1_sr(const float *y, const uint32_t *w, int64_t n, uint
                               uint8_t *out_fast) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
-    out[i] = (uint8_t)e2m1_code_of_grid_value(e2m1_sr_value(y[i], sr_uniform_of_word(w[i])));
+    const float k = sr_k_of_word(w[i]);
+    out[i] = (uint8_t)e2m1_code_of_grid_value(e2m1_sr_value(y[i], sr_uniform_of_k(k)));
     float margin = __builtin_inff();
-    const uint32_t code = e2m1_sr_code_fast<0>(0u, y[i], w[i], margin) & 0x0fu;
+    const uint32_t code = e2m1_sr_code_fast<0>(0u, y[i], ~w[i], k, margin) & 0x0fu;
     out_fast[i] = (uint8_t)(code | (margin > kSrMarginAtRisk ? 0u : 0x80u));
   }
 }
