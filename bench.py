@@ -31,22 +31,24 @@ from paper_2512_02010_amd import workloads as wl  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
 # fp32 vector rate of the chip in lane-operations/s: 157.3 TFLOP/s counts a fused
-# multiply-add as two, i.e. 256 CUs x 128 lanes x 2.4 GHz.  `--valu-rates` measures that the
-# plain (unpacked) v_fma/v_mul/v_add and the two-operand logic operations do issue at about
-# this rate (a wave's instruction in two passes) while conversions, comparisons, selects,
-# min/max, integer multiplies and three-operand integer operations take four passes and the
-# FP4/FP8 packing conversions eight (profiles/valu_issue_rates.txt).
+# multiply-add as two, i.e. 256 CUs x 128 lanes x 2.4 GHz.  Measured issue rates
+# (profiles/valu_issue_rates.txt): the plain (unpacked) v_fma/v_mul/v_add and the two-operand
+# logic operations do issue at about this rate (a wave's instruction in two passes) while
+# conversions, comparisons, selects, min/max, integer multiplies, three-operand integer
+# operations and any fp32 instruction with a scalar-register source take four passes, the
+# FP4/FP8 packing conversions eight and the stochastic-rounding FP4 conversion twelve.
 VALU_PEAK_TOPS = 256 * 128 * 2.4e9 / 1e12
 # VALU wave-instructions per block of 16 elements in the rowwise 4/6 kernel, from
-# rocprofv3 --pmc SQ_INSTS_VALU (profiles/c2_step_counters.txt): 14,920,024 per 4,194,304/64 wave-blocks
-VALU_INSTS_PER_BLOCK_46 = 14920024.0 / (4194304.0 / 64.0)
-# the same for the kernels of c4 (both orientations, per 16 elements) and c5 (Hadamard +
-# stochastic rounding), profiles/c5_rowwise_rht_sr_counters.txt
-VALU_INSTS_PER_BLOCK_C4 = 30731260.0 / (4194304.0 / 64.0)
-VALU_INSTS_PER_BLOCK_C5 = 64939446.0 / (4194304.0 / 64.0)
+# rocprofv3 --pmc SQ_INSTS_VALU (profiles/c2_step_counters.txt): 14,730,144 per 4,194,304/64 wave-blocks
+VALU_INSTS_PER_BLOCK_46 = 14730144.0 / (4194304.0 / 64.0)
+# the same for the kernels of c4 (both orientations, per 16 elements;
+# profiles/c4_both_and_fake_quant_counters.txt) and c5 (Hadamard + stochastic rounding;
+# profiles/c5_rowwise_rht_sr_counters.txt)
+VALU_INSTS_PER_BLOCK_C4 = 31557668.0 / (4194304.0 / 64.0)
+VALU_INSTS_PER_BLOCK_C5 = 46391083.0 / (4194304.0 / 64.0)
 # HBM bytes per element of the same kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled
-# by a plain copy's readings (same file): (65612.8 * 2.000 + 36864.3 * 1.000) KiB per 67,108,864
-HBM_TRAFFIC_PER_ELEM_46 = (65612.8 * 2.0 + 36864.3) * 1024.0 / 67108864.0
+# by a plain copy's readings (same file): (65650.9 * 2.000 + 36889.5 * 1.000) KiB per 67,108,864
+HBM_TRAFFIC_PER_ELEM_46 = (65650.9 * 2.0 + 36889.5) * 1024.0 / 67108864.0
 BYTES_PER_ELEM_QUANT = 2.0 + 0.5 + 1.0 / 16.0        # read x, write codes, write scales
 BYTES_PER_ELEM_AMAX = 2.0
 BYTES_PER_ELEM_DEQUANT = 0.5 + 1.0 / 16.0 + 2.0
@@ -146,9 +148,10 @@ class BufferSet:
         self.stream = torch.cuda.current_stream()
 
 
-def step(bs: BufferSet, ev=None):
+def step(bs: BufferSet, ev=None, quantize_params=None):
     """tensor_scale -> quantize -> dequantize, all on the current stream.  `ev`: two events
-    recorded around the quantize call, or four around all three calls."""
+    recorded around the quantize call, or four around all three calls.  `quantize_params`
+    replaces the 4/6 options of the quantize call (context measurements only)."""
     st = bs.stream
     he = hip_events() if ev else None
     every = ev is not None and len(ev) == 4
@@ -157,8 +160,8 @@ def step(bs: BufferSet, ev=None):
     rc = B.tensor_scale_ws_raw(bs.x, bs.params, bs.alpha, bs.workspace, B.TENSOR_SCALE_WS_BYTES, st)
     if ev:
         he.record(ev[1] if every else ev[0], st)
-    rc |= B.quantize_raw(bs.x, bs.params, bs.alpha, bs.out["codes_row"], bs.out["scales_row"], None,
-                         None, None, None, st)
+    rc |= B.quantize_raw(bs.x, quantize_params or bs.params, bs.alpha, bs.out["codes_row"],
+                         bs.out["scales_row"], None, None, None, None, st)
     if ev:
         he.record(ev[2] if every else ev[1], st)
     rc |= B.dequantize_raw(bs.out["codes_row"], bs.out["scales_row"], bs.alpha, bs.rows, bs.cols,
@@ -638,6 +641,15 @@ def main():
     t46 = (sum(t46) / len(t46), t46[len(t46) // 2], t46[0])
     t6 = (sum(t6) / len(t6), t6[len(t6) // 2], t6[0])
     hot = time_single(q46, sets[:1], 100)
+    # the same comparison inside the step (the quantize call follows the tensor-scale pass over
+    # the same tensor, as in the timed region): steps alternate between the two quantizers
+    evs_alt = [[he.new() for _ in range(2)] for _ in range(120)]
+    torch.cuda.synchronize()
+    for i, e in enumerate(evs_alt):
+        step(sets[i % len(sets)], e, p6 if i % 2 else None)
+    torch.cuda.synchronize()
+    t46_step = statistics.median(he.elapsed_ms(e[0], e[1]) for e in evs_alt[0::2])
+    t6_step = statistics.median(he.elapsed_ms(e[0], e[1]) for e in evs_alt[1::2])
 
     # what the method buys on this tensor (config 2 asks for it): squared error of 4/6 against
     # always-6 under both tensor-scale constants, and how often 4 is chosen; the sums run in
@@ -766,8 +778,14 @@ def main():
             "cold_us_avg_median_min": [t * 1e3 for t in t46],
             "hot_us_avg_median_min": [t * 1e3 for t in hot],
             "force6_cold_us_avg_median_min": [t * 1e3 for t in t6],
-            "t46_over_t6": t46[1] / t6[1],
-            "t46_over_t6_note": "ratio of medians of 60 alternating launches each",
+            "t46_over_t6": t46_step / t6_step,
+            "t46_over_t6_note": "ratio of the medians of the quantize call inside 60 + 60 steps that "
+                                "alternate between 4/6 and always-6 (the call follows the "
+                                "tensor-scale pass over the same tensor, as in the timed region)",
+            "in_step_us_46_and_always6": [t46_step * 1e3, t6_step * 1e3],
+            "t46_over_t6_cold": t46[1] / t6[1],
+            "t46_over_t6_cold_note": "the same for 60 + 60 alternating launches on their own, each "
+                                     "on a tensor that no recent kernel touched",
             "paper_context": "the paper reports <15% overhead of 4/6 over plain NVFP4 "
                              "quantization on NVIDIA Blackwell (Sections 1, 3.2)",
         },
