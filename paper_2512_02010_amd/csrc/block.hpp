@@ -126,6 +126,7 @@ NV_DEV float candidate_as(const float (&v)[16], const uint32_t (&not_w)[16], con
                           float dec, float enc, uint32_t &lo, uint32_t &hi, float &sr_margin) {
   uint32_t c[2] = {0u, 0u};
   float acc[2] = {0.0f, 0.0f};
+  f32x2 sq = {0.0f, 0.0f};
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     float g[8];
@@ -163,10 +164,17 @@ NV_DEV float candidate_as(const float (&v)[16], const uint32_t (&not_w)[16], con
       c[h] = w;
     }
     if (ERR == kErrMseEstimate) {
+      // A three-source instruction issues at half rate when all three sources sit in registers
+      // of the same parity (measured), which d * d + acc is whenever d and acc do.  The two
+      // differences of a pair of elements are therefore kept in an aligned register pair (even,
+      // odd) and each is added into the accumulator of the other parity.
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const float d = __builtin_fmaf(g[j], dec, -v[8 * h + j]);
-        acc[j & 1] = __builtin_fmaf(d, d, acc[j & 1]);
+      for (int j = 0; j < 8; j += 2) {
+        f32x2 d = {__builtin_fmaf(g[j], dec, -v[8 * h + j]), __builtin_fmaf(g[j + 1], dec, -v[8 * h + j + 1])};
+        in_register_pair(d);
+        sq.y = __builtin_fmaf(d.x, d.x, sq.y);
+        sq.x = __builtin_fmaf(d.y, d.y, sq.x);
+        in_register_pair(sq);
       }
     }
     if (ERR == kErrMae || ERR == kErrAbsMax) {
@@ -188,6 +196,7 @@ NV_DEV float candidate_as(const float (&v)[16], const uint32_t (&not_w)[16], con
   }
   lo = c[0];
   hi = c[1];
+  if (ERR == kErrMseEstimate) return sq.x + sq.y;
   return ERR == kErrAbsMax ? fmaxf(acc[0], acc[1]) : acc[0] + acc[1];
 }
 

@@ -109,22 +109,39 @@ NV_DEV uint32_t cvt_sr_pk_fp4(uint32_t old, f32x2 src, uint32_t rnd) {
 // that finds margin <= kSrMarginAtRisk after a group of elements must redo the group with
 // e2m1_sr_value().  Returns `old` with the low nibble of byte SEL replaced by the code; the
 // high nibble of that byte is left undefined.
-// A constant the compiler must keep in a vector register: it would otherwise put a literal
-// used this often into a scalar register, and an fp32 instruction with a scalar-register source
-// issues at half the rate (measured: v_fma_f32 2.7 against 4.2 cycles per wave and SIMD).
-NV_DEV float in_vector_register(float c) {
+// Makes the compiler hold a two-float vector in an aligned pair of vector registers at this
+// point (.x in the even one, .y in the odd one).
+NV_DEV void in_register_pair(f32x2 &p) {
 #ifndef NVFP4_46_CVT_SR_PK_FP4_ON_HOST
-  asm("v_mov_b32 %0, %1" : "=v"(c) : "s"(c));
+  asm("" : "+v"(p));
 #endif
+}
+
+// A constant the compiler must keep in a vector register, and in an odd-numbered one: it would
+// otherwise put a literal used this often into a scalar register, and an fp32 instruction with
+// a scalar-register source issues at half the rate (measured: v_fma_f32 2.4 against 4.2 cycles
+// per wave and SIMD); a three-source instruction also falls to half rate when all three sources
+// sit in registers of the same parity, which a known parity of one of them can rule out.
+NV_DEV float in_odd_vector_register(float c) {
+#ifndef NVFP4_46_CVT_SR_PK_FP4_ON_HOST
+  f32x2 p;
+  asm("v_mov_b32 %0, %1" : "=v"(p.y) : "s"(c));
+  p.x = p.y;
+  asm("" : "+v"(p));
+  return p.y;
+#else
   return c;
+#endif
 }
 
 template <int SEL>
 NV_DEV uint32_t e2m1_sr_code_fast(uint32_t old, float y, uint32_t not_w, float k, float &margin) {
-  const float t = __builtin_fmaf(fabsf(y), in_vector_register(0x1p25f), -k);
+  // {y, t} is the register pair the conversion reads: y in its even half, so with the constant
+  // in an odd register the three sources of the fma never share a parity.  The second source
+  // position of the conversion only has to be some register: t is at hand, and as a value
+  // computed here it can be placed next to y without a copy.
+  const float t = __builtin_fmaf(fabsf(y), in_odd_vector_register(0x1p25f), -k);
   margin = fminf(fminf(margin, fabsf(t)), fabsf(t - 0x1p24f));   // one v_min3_f32
-  // the second source position only has to be some register: t is at hand, and as a value
-  // computed here it can be placed next to y without a copy
   const f32x2 src = {y, t};
   return cvt_sr_pk_fp4<SEL>(old, src, not_w);
 }
