@@ -45,10 +45,10 @@ VALU_INSTS_PER_BLOCK_46 = 14730144.0 / (4194304.0 / 64.0)
 # profiles/c4_both_and_fake_quant_counters.txt) and c5 (Hadamard + stochastic rounding;
 # profiles/c5_rowwise_rht_sr_counters.txt)
 VALU_INSTS_PER_BLOCK_C4 = 31557668.0 / (4194304.0 / 64.0)
-VALU_INSTS_PER_BLOCK_C5 = 46391083.0 / (4194304.0 / 64.0)
+VALU_INSTS_PER_BLOCK_C5 = 46524183.0 / (4194304.0 / 64.0)
 # HBM bytes per element of the same kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled
-# by a plain copy's readings (same file): (65650.9 * 2.000 + 36889.5 * 1.000) KiB per 67,108,864
-HBM_TRAFFIC_PER_ELEM_46 = (65650.9 * 2.0 + 36889.5) * 1024.0 / 67108864.0
+# by a plain copy's readings (same file): (65665.8 * 2.000 + 36891.5 * 1.000) KiB per 67,108,864
+HBM_TRAFFIC_PER_ELEM_46 = (65665.8 * 2.0 + 36891.5) * 1024.0 / 67108864.0
 BYTES_PER_ELEM_QUANT = 2.0 + 0.5 + 1.0 / 16.0        # read x, write codes, write scales
 BYTES_PER_ELEM_AMAX = 2.0
 BYTES_PER_ELEM_DEQUANT = 0.5 + 1.0 / 16.0 + 2.0
