@@ -11,14 +11,15 @@ enum : int { kSel46 = 0, kSelForce6 = 1, kSelForce4 = 2, kSel46Mae = 3, kSel46Ab
 // what candidate() returns besides the codes
 enum : int { kErrNone = 0, kErrMseEstimate = 1, kErrMae = 2, kErrAbsMax = 3 };
 
-// (dec, enc) for every E4M3 scale byte under one tensor scale:
+// (dec, enc, dec^2) for every E4M3 scale byte under one tensor scale:
 //   dec = value(S) * alpha   -- what one unit of code is worth (Table 3 line 5)
 //   enc = 1 / dec            -- multiplying by it is the division of Eq. (3);
 //                               0 when dec is 0, so an all-zero block encodes to zeros
-// Both depend on (S, alpha) only, so a workgroup computes the 127 pairs once
+//   dec^2                    -- for the tolerance of the 4-vs-6 decision
+// All depend on (S, alpha) only, so a workgroup computes the 127 entries once
 // into LDS instead of one IEEE division per block and candidate.
 struct ScaleTable {
-  float2 e[128];
+  float4 e[128];   // .x dec, .y enc, .z dec * dec
 };
 
 // Per-tensor constants of Eq. (2): the denominators alpha*6 and alpha*4 and their
@@ -37,13 +38,13 @@ NV_DEV ScaleConsts build_scale_table(ScaleTable &tab, float alpha) {
     if (s < 127u) {
       float dec = e4m3_decode(s) * alpha;
       float enc = (dec == 0.0f) ? 0.0f : 1.0f / dec;
-      tab.e[s] = make_float2(dec, enc);
+      tab.e[s] = make_float4(dec, enc, dec * dec, 0.0f);
     } else {
-      tab.e[s] = make_float2(1.0f / k.c6, 1.0f / k.c4);
+      tab.e[s] = make_float4(1.0f / k.c6, 1.0f / k.c4, 0.0f, 0.0f);
     }
   }
   __syncthreads();
-  const float2 r = tab.e[127];
+  const float4 r = tab.e[127];
   k.rc6 = r.x;
   k.rc4 = r.y;
   return k;
@@ -134,7 +135,7 @@ NV_DEV float candidate_as(const float (&v)[16], const uint32_t (&not_w)[16], con
       // v_cvt_scalef32_pk_fp4_f32 fills byte j of the word (first source in the low
       // nibble); the word is complete before v_cvt_scalef32_pk_f32_fp4 reads the bytes
       // back, so no partial copies of it have to be kept.
-      uint32_t w = 0u;
+      uint32_t w = any_register();   // all four bytes are written below
 #pragma unroll
       for (int j = 0; j < 4; ++j)
         w = hw_pk_fp4_sel(w, v[8 * h + 2 * j] * enc, v[8 * h + 2 * j + 1] * enc, j);
@@ -255,19 +256,20 @@ NV_DEV float exact_error(const float (&v)[16], uint32_t lo, uint32_t hi, float d
 //     |E - S| <= 48.1 u m + 7.1 u S;
 //   estimate E':  one rounding in d', at most 9 more per term in the accumulation:
 //     |E' - S| <= 18.1 u S.
-// Hence |E - E'| <= 48.1 u m + 25.2 u S < 64 u (max(dec^2, E') + E').
+// Hence |E - E'| <= 48.1 u m + 25.2 u S <= 48.1 u dec^2 + 73.3 u S < 64 u (dec^2 + 2 E').
 // Underflow adds absolute errors that no relative bound covers: the contract keeps
 // dec >= 2^-109, so products g*dec and the differences are never inexact for being small,
 // but each of the 16 squares of the defined value and each of the 16 accumulation steps of
 // the estimate may round in the subnormal range, by at most 2^-150 each: 2^-145 per
 // candidate.  The tolerance therefore carries the absolute term 2^-126 (which also covers
 // dec*dec or the tolerance's own products flushing towards zero):
-//   tol := 64 u (max(dec6^2, E6') + E6' + max(dec4^2, E4') + E4') + 2^-126.
+//   tol := 64 u ((dec6^2 + dec4^2) + 2 (E6' + E4')) + 2^-126
+// (the squares come out of the scale table; four instructions).
 // If |E4' - E6'| > tol the order of E4 and E6 is the order of the estimates; tensors so
 // small that all squared errors lie below 2^-126 always take the defined path.
 // Overflowed (infinite / NaN) estimates fail the test and take the exact path.
 NV_DEV float decision_tolerance(float m6, float E6p, float m4, float E4p) {
-  return __builtin_fmaf(0x1p-18f, (fmaxf(m6, E6p) + E6p) + (fmaxf(m4, E4p) + E4p), 0x1p-126f);
+  return __builtin_fmaf(0x1p-18f, __builtin_fmaf(2.0f, E6p + E4p, m6 + m4), 0x1p-126f);
 }
 
 // The same for a 16x16 tile whose error is the sum of its sixteen row errors (each row an
@@ -305,9 +307,10 @@ enum : int { kKeepSix = 0, kKeepFour = 1, kUndecided = 2 };
 
 // kKeepFour / kKeepSix when the estimates (or the codes, for exact ties) settle Table 3
 // line 13, kUndecided when only the defined errors can.
-NV_DEV int decide_from_estimates(float E6p, float E4p, float dec6, float dec4, uint32_t lo6,
-                                 uint32_t hi6, uint32_t lo4, uint32_t hi4) {
-  const float tol = decision_tolerance(dec6 * dec6, E6p, dec4 * dec4, E4p);
+NV_DEV int decide_from_estimates(float E6p, float E4p, float dec6, float dec4, float dec6_squared,
+                                 float dec4_squared, uint32_t lo6, uint32_t hi6, uint32_t lo4,
+                                 uint32_t hi4) {
+  const float tol = decision_tolerance(dec6_squared, E6p, dec4_squared, E4p);
   const float diff = E4p - E6p;
   if (fabsf(diff) > tol) return diff < 0.0f ? kKeepFour : kKeepSix;
   // identical dequantized values: equal errors, and ties keep 6
@@ -393,9 +396,10 @@ NV_DEV BlockResult quantize_block_pass(const float (&v)[16], const uint32_t (&rw
   // only the winner stochastically.
   constexpr int kCandRounding = ROUNDING == kSRAfterRtnSelect ? kRTN : ROUNDING;
   BlockResult r6{}, r4{};
-  float E6p = 0.0f, E4p = 0.0f, enc6 = 0.0f, enc4 = 0.0f;
+  float E6p = 0.0f, E4p = 0.0f, enc6 = 0.0f, enc4 = 0.0f, m6 = 0.0f, m4 = 0.0f;
   if (SELECT != kSelForce4) {
-    float2 t = tab.e[S6];
+    const float4 t = tab.e[S6];
+    m6 = t.z;
     r6.scale = S6;
     r6.dec = t.x;
     r6.four = 0u;
@@ -404,7 +408,8 @@ NV_DEV BlockResult quantize_block_pass(const float (&v)[16], const uint32_t (&rw
       E6p = candidate<kCandRounding, kErr>(v, rw, t.x, t.y, r6.lo, r6.hi);
   }
   if (SELECT != kSelForce6) {
-    float2 t = tab.e[S4];
+    const float4 t = tab.e[S4];
+    m4 = t.z;
     r4.scale = S4;
     r4.dec = t.x;
     r4.four = 1u;
@@ -422,7 +427,7 @@ NV_DEV BlockResult quantize_block_pass(const float (&v)[16], const uint32_t (&rw
   } else if (DEFINED_ERRORS) {
     four = exact_error(v, r4.lo, r4.hi, r4.dec) < exact_error(v, r6.lo, r6.hi, r6.dec);
   } else {
-    const int d = decide_from_estimates(E6p, E4p, r6.dec, r4.dec, r6.lo, r6.hi, r4.lo, r4.hi);
+    const int d = decide_from_estimates(E6p, E4p, r6.dec, r4.dec, m6, m4, r6.lo, r6.hi, r4.lo, r4.hi);
     four = d == kKeepFour;
     undecided = d == kUndecided;
   }

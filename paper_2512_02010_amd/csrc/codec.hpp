@@ -109,6 +109,17 @@ NV_DEV uint32_t cvt_sr_pk_fp4(uint32_t old, f32x2 src, uint32_t rnd) {
 // that finds margin <= kSrMarginAtRisk after a group of elements must redo the group with
 // e2m1_sr_value().  Returns `old` with the low nibble of byte SEL replaced by the code; the
 // high nibble of that byte is left undefined.
+// A word whose content does not matter (every byte of it is about to be overwritten by
+// instructions that replace one byte each): whatever register the compiler picks, with no
+// instruction spent on initialising it.
+NV_DEV uint32_t any_register() {
+  uint32_t w = 0u;
+#ifndef NVFP4_46_CVT_SR_PK_FP4_ON_HOST
+  asm("" : "=v"(w));
+#endif
+  return w;
+}
+
 // Makes the compiler hold a two-float vector in an aligned pair of vector registers at this
 // point (.x in the even one, .y in the odd one).
 NV_DEV void in_register_pair(f32x2 &p) {

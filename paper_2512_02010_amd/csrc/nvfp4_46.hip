@@ -881,7 +881,7 @@ __global__ __launch_bounds__(kThreads) void k_block2d(
     float E6 = 0.0f, E4 = 0.0f, enc6 = 0.0f, enc4 = 0.0f;
     if (SELECT != kSelForce4) {
       r6.scale = S6;
-      const float2 t = tab.e[r6.scale];
+      const float4 t = tab.e[r6.scale];
       r6.dec = t.x;
       enc6 = t.y;
       if (!(ROUNDING == kSRAfterRtnSelect && SELECT == kSelForce6))
@@ -890,7 +890,7 @@ __global__ __launch_bounds__(kThreads) void k_block2d(
     if (SELECT != kSelForce6) {
       r4.scale = S4;
       r4.four = 1u;
-      const float2 t = tab.e[r4.scale];
+      const float4 t = tab.e[r4.scale];
       r4.dec = t.x;
       enc4 = t.y;
       if (!(ROUNDING == kSRAfterRtnSelect && SELECT == kSelForce4))

@@ -86,7 +86,7 @@ int hm_tile_decision(const float *v, const float *u, float alpha, int rounding, 
   block_scales(b, sc, S6, S4);
   *scale6 = (uint8_t)S6;
   *scale4 = (uint8_t)S4;
-  const float2 t6 = tab.e[S6], t4 = tab.e[S4];
+  const float4 t6 = tab.e[S6], t4 = tab.e[S4];
   float E6[16], E4[16], e6[16], e4[16];
   for (int r = 0; r < 16; ++r) {
     float vv[16];
