@@ -105,6 +105,37 @@ def test_e2m1_sr_matches_oracle():
     assert np.array_equal(fast[trusted], want[trusted]) and trusted.mean() > 0.999
 
 
+def test_e2m1_sr_by_conversion_instruction_random_pairs_and_thresholds():
+    """32 M random (y, word) pairs, half of them with the uniform placed within a few units of
+    the threshold p = (|y| - lo) / (hi - lo): every code the kernels would keep is the oracle's,
+    from 1 up the instruction's code is the oracle's always, and the kernels keep nearly all."""
+    rng = np.random.default_rng(34)
+    n = 1 << 24
+    for part in range(2):
+        mag = np.where(rng.random(n) < 0.5, rng.uniform(0.0, 7.0, n), 2.0 ** rng.uniform(-30.0, 3.0, n))
+        y = (mag * rng.choice([-1.0, 1.0], n)).astype(np.float32)
+        k = rng.integers(0, 1 << 24, n)
+        if part == 1:
+            a = np.minimum(np.abs(y), np.float32(6.0)).astype(np.float64)
+            step = np.where(a < 2.0, 0.5, np.where(a < 4.0, 1.0, 2.0))
+            p = a / step - np.floor(a / step)
+            k = np.clip(np.floor(p * 2.0 ** 24).astype(np.int64) + rng.integers(-8, 9, n), 0, (1 << 24) - 1)
+        u = k.astype(np.float32) * np.float32(2.0 ** -24)
+        got, fast = B.nvfp4_46_debug_e2m1_sr(torch.from_numpy(y).cuda(), _words(k, rng))
+        got, fast = got.cpu().numpy(), fast.cpu().numpy()
+        want = ref.e2m1_sr_n(y, u)
+        assert np.array_equal(got, want)
+        trusted = (fast & 0x80) == 0
+        code = fast & 0x0F
+        assert np.array_equal(code[trusted], want[trusted])
+        big = np.abs(y) >= 1.0
+        assert np.array_equal(code[big], want[big])
+        _log(f"part {part}: trusted {trusted.mean():.6f}, instruction differs on {int((code != want).sum())}")
+        assert trusted.mean() > (0.999 if part == 0 else 0.5)
+        if part == 1:
+            assert (code != want).sum() > 1000      # the threshold cases do reach the difference
+
+
 @pytest.mark.parametrize("sign", [0, 0x80000000])
 def test_e2m1_sr_by_conversion_instruction_every_fp32(sign):
     """The stochastic-rounding conversion instruction as the kernels use it (value in the first
