@@ -9,7 +9,8 @@
  *
  * General conventions (all entry points)
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
- *     allocates no memory and keeps no state between calls.
+ *     allocates no memory and keeps no state between calls (the one exception is the
+ *     fixed scratch array of nvfp4_46_tensor_scale_static, described there).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Work is enqueued on it and the call returns without synchronising; a call
  *     that fails validation enqueues nothing.

@@ -385,12 +385,12 @@ __global__ __launch_bounds__(kThreads) void k_flat(
       for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(v[i]));
       return;
     }
-    auto uniforms = [&](uint32_t (&uu)[16]) {
+    auto random_words = [&](uint32_t (&uu)[16]) {
       const uint64_t q0 = ((uint64_t)base + tid) * 4u;
 #pragma unroll
       for (int j = 0; j < 4; ++j) sr_words4(sr_seed, q0 + j, &uu[4 * j]);
     };
-    if (ROUNDING != kRTN) uniforms(u);
+    if (ROUNDING != kRTN) random_words(u);
     // the block once more, from memory (a lane without a block of its own holds a copy of
     // the round's last block, as fetch() gave it)
     auto again = [&](float (&w)[16], uint32_t (&uu)[16]) {
@@ -398,7 +398,7 @@ __global__ __launch_bounds__(kThreads) void k_flat(
       load_block<XF32>(x + Raw::kPieces * (base + (tid < live ? tid : live - 1)), r2);
       unpack16(r2, w);
       if (RHT) transform(w);
-      if (ROUNDING != kRTN) uniforms(uu);
+      if (ROUNDING != kRTN) random_words(uu);
     };
     const BlockResult res = quantize_block<ROUNDING, SELECT>(v, u, sc, tab, again);
     if (OUT == kOutCodes) {
