@@ -118,10 +118,11 @@ NV_DEV void grid8(uint32_t codes, float (&g)[8]) {
 // error: d' = fma(g, dec, -v) and a running fma(d', d', E'), i.e. two instructions per
 // element where the defining sequence (product, difference, square, tree sum, each
 // rounded) takes four.  E' is only ever used through decide_from_estimates() below.
-// Stochastic rounding (rw: the elements' random words) comes in two forms: FAST_SR = true
-// rounds with the conversion instruction and lowers `sr_margin` (see e2m1_sr_code_fast: the
-// codes are only valid if sr_margin stays above kSrMarginAtRisk); FAST_SR = false applies the
-// rule in software and is always valid.
+// Stochastic rounding (not_w, k: the complement and the top 24 bits, as a float, of each
+// element's random word) comes in two forms: FAST_SR = true rounds with the conversion
+// instruction and lowers `sr_margin` (see e2m1_sr_code_fast: the codes are only valid if
+// sr_margin stays above kSrMarginAtRisk); FAST_SR = false applies the rule in software and is
+// always valid.
 template <int ROUNDING, int ERR, bool FAST_SR>
 NV_DEV float candidate_as(const float (&v)[16], const uint32_t (&not_w)[16], const float (&k)[16],
                           float dec, float enc, uint32_t &lo, uint32_t &hi, float &sr_margin) {
