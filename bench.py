@@ -45,7 +45,7 @@ VALU_INSTS_PER_BLOCK_46 = 14730144.0 / (4194304.0 / 64.0)
 # profiles/c4_both_and_fake_quant_counters.txt) and c5 (Hadamard + stochastic rounding;
 # profiles/c5_rowwise_rht_sr_counters.txt)
 VALU_INSTS_PER_BLOCK_C4 = 31557668.0 / (4194304.0 / 64.0)
-VALU_INSTS_PER_BLOCK_C5 = 46524183.0 / (4194304.0 / 64.0)
+VALU_INSTS_PER_BLOCK_C5 = 46169804.0 / (4194304.0 / 64.0)
 # HBM bytes per element of the same kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled
 # by a plain copy's readings (same file): (65665.8 * 2.000 + 36891.5 * 1.000) KiB per 67,108,864
 HBM_TRAFFIC_PER_ELEM_46 = (65665.8 * 2.0 + 36891.5) * 1024.0 / 67108864.0

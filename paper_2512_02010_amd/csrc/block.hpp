@@ -64,13 +64,13 @@ NV_DEV uint32_t hw_pk_fp4_sel(uint32_t old, float a, float b, int sel) {
   }
 }
 // byte `sel` of a word that is filled in the order 0, 1, 2, 3
-NV_DEV uint32_t e2m1_sr_code_fast_sel(uint32_t old, float y, uint32_t not_w, float k, float &margin,
+NV_DEV uint32_t e2m1_sr_code_fast_sel(uint32_t old, float y, uint32_t not_w, float wf, float &margin,
                                       int sel) {
   switch (sel) {
-    case 0: return e2m1_sr_code_fast<kSrFirstByteOfNewWord>(old, y, not_w, k, margin);
-    case 1: return e2m1_sr_code_fast<1>(old, y, not_w, k, margin);
-    case 2: return e2m1_sr_code_fast<2>(old, y, not_w, k, margin);
-    default: return e2m1_sr_code_fast<3>(old, y, not_w, k, margin);
+    case 0: return e2m1_sr_code_fast<kSrFirstByteOfNewWord>(old, y, not_w, wf, margin);
+    case 1: return e2m1_sr_code_fast<1>(old, y, not_w, wf, margin);
+    case 2: return e2m1_sr_code_fast<2>(old, y, not_w, wf, margin);
+    default: return e2m1_sr_code_fast<3>(old, y, not_w, wf, margin);
   }
 }
 template <int SEL>
@@ -118,13 +118,13 @@ NV_DEV void grid8(uint32_t codes, float (&g)[8]) {
 // error: d' = fma(g, dec, -v) and a running fma(d', d', E'), i.e. two instructions per
 // element where the defining sequence (product, difference, square, tree sum, each
 // rounded) takes four.  E' is only ever used through decide_from_estimates() below.
-// Stochastic rounding (not_w, k: the complement and the top 24 bits, as a float, of each
-// element's random word) comes in two forms: FAST_SR = true rounds with the conversion
+// Stochastic rounding (not_w, wf: the complement of each element's random word, and the word
+// rounded to a float) comes in two forms: FAST_SR = true rounds with the conversion
 // instruction and lowers `sr_margin` (see e2m1_sr_code_fast: the codes are only valid if
 // sr_margin stays above kSrMarginAtRisk); FAST_SR = false applies the rule in software and is
 // always valid.
 template <int ROUNDING, int ERR, bool FAST_SR>
-NV_DEV float candidate_as(const float (&v)[16], const uint32_t (&not_w)[16], const float (&k)[16],
+NV_DEV float candidate_as(const float (&v)[16], const uint32_t (&not_w)[16], const float (&wf)[16],
                           float dec, float enc, uint32_t &lo, uint32_t &hi, float &sr_margin) {
   uint32_t c[2] = {0u, 0u};
   float acc[2] = {0.0f, 0.0f};
@@ -149,8 +149,8 @@ NV_DEV float candidate_as(const float (&v)[16], const uint32_t (&not_w)[16], con
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int e = 8 * h + 2 * j, o = e + 1;
-        we = e2m1_sr_code_fast_sel(we, v[e] * enc, not_w[e], k[e], sr_margin, j);
-        wo = e2m1_sr_code_fast_sel(wo, v[o] * enc, not_w[o], k[o], sr_margin, j);
+        we = e2m1_sr_code_fast_sel(we, v[e] * enc, not_w[e], wf[e], sr_margin, j);
+        wo = e2m1_sr_code_fast_sel(wo, v[o] * enc, not_w[o], wf[o], sr_margin, j);
       }
       const uint32_t w = (we & 0x0f0f0f0fu) | ((wo << 4) & 0xf0f0f0f0u);
       if (ERR != kErrNone) grid8(w, g);
@@ -159,7 +159,7 @@ NV_DEV float candidate_as(const float (&v)[16], const uint32_t (&not_w)[16], con
       // the rounded values are on the grid, so the conversion that packs them is exact
 #pragma unroll
       for (int j = 0; j < 8; ++j)
-        g[j] = e2m1_sr_value(v[8 * h + j] * enc, sr_uniform_of_k(k[8 * h + j]));
+        g[j] = e2m1_sr_value(v[8 * h + j] * enc, sr_uniform_of_word(~not_w[8 * h + j]));
       uint32_t w = 0u;
 #pragma unroll
       for (int j = 0; j < 4; ++j) w = hw_pk_fp4_sel(w, g[2 * j], g[2 * j + 1], j);
@@ -211,18 +211,18 @@ NV_DEV float candidate(const float (&v)[16], const uint32_t (&rw)[16], float dec
   // (the same for every scale the block is tried under: computed once after inlining, and
   // the words themselves need not stay in registers)
   uint32_t not_w[16];
-  float k[16];
+  float wf[16];
   if (ROUNDING != kRTN) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       not_w[i] = ~rw[i];
-      k[i] = sr_k_of_word(rw[i]);
+      wf[i] = (float)rw[i];
     }
   }
   float margin = __builtin_inff();
-  float E = candidate_as<ROUNDING, ERR, true>(v, not_w, k, dec, enc, lo, hi, margin);
+  float E = candidate_as<ROUNDING, ERR, true>(v, not_w, wf, dec, enc, lo, hi, margin);
   if (ROUNDING != kRTN && !(margin > kSrMarginAtRisk))
-    E = candidate_as<ROUNDING, ERR, false>(v, not_w, k, dec, enc, lo, hi, margin);
+    E = candidate_as<ROUNDING, ERR, false>(v, not_w, wf, dec, enc, lo, hi, margin);
   return E;
 }
 

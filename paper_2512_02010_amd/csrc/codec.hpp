@@ -88,27 +88,6 @@ NV_DEV uint32_t cvt_sr_pk_fp4(uint32_t old, f32x2 src, uint32_t rnd) {
 #endif
 }
 
-// The rounding of e2m1_sr_value() by that instruction, for the element whose random word is
-// w (passed as not_w = ~w and k = (float)(w >> 8), which a caller rounding the same element
-// under several scales computes once).  Only the first source position is used: with ~w as
-// the random operand the instruction
-// adds the operand's top 22 bits to the 22 bits below the kept mantissa bit and truncates
-// (the second position reads other bits of the operand and cannot be given an independent
-// uniform; its nibble is left to be masked off by the caller).  With k = w >> 8, so that
-// u = k * 2^-24:
-//   |y| >= 1: one step up iff (k >> 2) < (low 22 mantissa bits): exactly u < p, because p has
-//             22 bits there;
-//   |y| < 1 : the grid step is 0.5 and p = frac(2|y|); the instruction cuts |y| to a multiple
-//             of 2^-23 first, i.e. compares k >> 2 with P = floor(|y| * 2^23) mod 2^22.  That
-//             is u < p unless k >> 2 == P, which implies |A - k| < 4 for A = |y| * 2^25 (below
-//             0.5) or A = |y| * 2^25 - 2^24 (from 0.5 up).
-// Magnitudes above 6 give 6, the sign bit is the input's also when the magnitude becomes 0.
-// (The GPU tests compare the instruction, used this way, with the CPU oracle and with this
-// description on every fp32 value, for several words.)  `margin` is lowered to the smaller of
-// the two |A - k| where that is smaller still (each computed with an error below 1.5): a caller
-// that finds margin <= kSrMarginAtRisk after a group of elements must redo the group with
-// e2m1_sr_value().  Returns `old` with the low nibble of byte SEL replaced by the code; the
-// high nibble of that byte is left undefined.
 // A word whose content does not matter (every byte of it is about to be overwritten by
 // instructions that replace one byte each): whatever register the compiler picks, with no
 // instruction spent on initialising it.
@@ -145,18 +124,41 @@ NV_DEV float in_odd_vector_register(float c) {
 #endif
 }
 
+// The rounding of e2m1_sr_value() by that instruction, for the element whose random word is
+// w (passed as not_w = ~w and wf = (float)w, which a caller rounding the same element under
+// several scales computes once).  Only the first source position is used: with ~w as the
+// random operand the instruction adds the operand's top 22 bits to the 22 bits below the kept
+// mantissa bit and truncates (the second position reads other bits of the operand and cannot
+// be given an independent uniform; its nibble is left to be masked off by the caller).  With
+// k = w >> 8, so that u = k * 2^-24:
+//   |y| >= 1: one step up iff (k >> 2) < (low 22 mantissa bits): exactly u < p, because p has
+//             22 bits there;
+//   |y| < 1 : the grid step is 0.5 and p = frac(2|y|); the instruction cuts |y| to a multiple
+//             of 2^-23 first, i.e. compares k >> 2 with P = floor(|y| * 2^23) mod 2^22.  That
+//             is u < p unless k >> 2 == P, which implies |A - k| < 4 for A = |y| * 2^25 (below
+//             0.5) or A = |y| * 2^25 - 2^24 (from 0.5 up).
+// Magnitudes above 6 give 6, the sign bit is the input's also when the magnitude becomes 0.
+// (The GPU tests compare the instruction, used this way, with the CPU oracle and with this
+// description on every fp32 value, for several words.)
+// The risk is tested 256 times larger, on the whole word, which saves the shift: with
+// t = fl(|y| * 2^33 - wf), |wf - w| <= 128 and w = 256 k + (0..255), |A - k| < 4 implies
+// |t| < 1024 + 383 + rounding, and |A - 2^24 - k| < 4 implies |t - 2^32| < 1407 + 256 (t is
+// rounded to a multiple of 512 up there).  `margin` is lowered to the smaller of |t| and
+// |t - 2^32| where that is smaller still: a caller that finds margin <= kSrMarginAtRisk after a
+// group of elements must redo the group with e2m1_sr_value().  Returns `old` with the low
+// nibble of byte SEL replaced by the code; the high nibble of that byte is left undefined.
 template <int SEL>
-NV_DEV uint32_t e2m1_sr_code_fast(uint32_t old, float y, uint32_t not_w, float k, float &margin) {
+NV_DEV uint32_t e2m1_sr_code_fast(uint32_t old, float y, uint32_t not_w, float wf, float &margin) {
   // {y, t} is the register pair the conversion reads: y in its even half, so with the constant
   // in an odd register the three sources of the fma never share a parity.  The second source
   // position of the conversion only has to be some register: t is at hand, and as a value
   // computed here it can be placed next to y without a copy.
-  const float t = __builtin_fmaf(fabsf(y), in_odd_vector_register(0x1p25f), -k);
-  margin = fminf(fminf(margin, fabsf(t)), fabsf(t - 0x1p24f));   // one v_min3_f32
+  const float t = __builtin_fmaf(fabsf(y), in_odd_vector_register(0x1p33f), -wf);
+  margin = fminf(fminf(margin, fabsf(t)), fabsf(t - 0x1p32f));   // one v_min3_f32
   const f32x2 src = {y, t};
   return cvt_sr_pk_fp4<SEL>(old, src, not_w);
 }
-constexpr float kSrMarginAtRisk = 6.0f;
+constexpr float kSrMarginAtRisk = 2048.0f;
 
 // Code of a value that is already on the grid (sign included).
 NV_DEV uint32_t e2m1_code_of_grid_value(float r) {
@@ -222,8 +224,7 @@ NV_DEV void sr_words4(uint64_t seed, uint64_t q, uint32_t w[4]) {
 #pragma unroll
   for (int j = 0; j < 4; ++j) w[j] = p.w[j];
 }
-NV_DEV float sr_k_of_word(uint32_t w) { return (float)(w >> 8); }   // exact: 24 bits
-NV_DEV float sr_uniform_of_k(float k) { return k * 0x1p-24f; }
+NV_DEV float sr_uniform_of_word(uint32_t w) { return (float)(w >> 8) * 0x1p-24f; }
 
 // Sign word of the block at position B along the blocked axis (bit j = negate element j).
 NV_DEV uint32_t rht_sign_word(uint64_t seed, uint64_t B) {

@@ -1017,10 +1017,9 @@ __global__ void k_dbg_e2m1_sr(const float *y, const uint32_t *w, int64_t n, uint
                               uint8_t *out_fast) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
-    const float k = sr_k_of_word(w[i]);
-    out[i] = (uint8_t)e2m1_code_of_grid_value(e2m1_sr_value(y[i], sr_uniform_of_k(k)));
+    out[i] = (uint8_t)e2m1_code_of_grid_value(e2m1_sr_value(y[i], sr_uniform_of_word(w[i])));
     float margin = __builtin_inff();
-    const uint32_t code = e2m1_sr_code_fast<0>(0u, y[i], ~w[i], k, margin) & 0x0fu;
+    const uint32_t code = e2m1_sr_code_fast<0>(0u, y[i], ~w[i], (float)w[i], margin) & 0x0fu;
     out_fast[i] = (uint8_t)(code | (margin > kSrMarginAtRisk ? 0u : 0x80u));
   }
 }

@@ -126,10 +126,9 @@ int hm_tile_decision(const float *v, const float *u, float alpha, int rounding, 
 void hm_e2m1_sr(const float *y, const float *u, int64_t n, uint8_t *out, uint8_t *out_fast) {
   for (int64_t i = 0; i < n; ++i) {
     const uint32_t w = word_of(u[i]);
-    const float k = sr_k_of_word(w);
-    out[i] = (uint8_t)e2m1_code_of_grid_value(e2m1_sr_value(y[i], sr_uniform_of_k(k)));
+    out[i] = (uint8_t)e2m1_code_of_grid_value(e2m1_sr_value(y[i], sr_uniform_of_word(w)));
     float margin = __builtin_inff();
-    const uint32_t code = e2m1_sr_code_fast<0>(0u, y[i], ~w, k, margin) & 0x0fu;
+    const uint32_t code = e2m1_sr_code_fast<0>(0u, y[i], ~w, (float)w, margin) & 0x0fu;
     out_fast[i] = (uint8_t)(code | (margin > kSrMarginAtRisk ? 0u : 0x80u));
   }
 }

@@ -119,7 +119,7 @@ def test_e2m1_sr_by_conversion_instruction_random_pairs_and_thresholds():
             a = np.minimum(np.abs(y), np.float32(6.0)).astype(np.float64)
             step = np.where(a < 2.0, 0.5, np.where(a < 4.0, 1.0, 2.0))
             p = a / step - np.floor(a / step)
-            k = np.clip(np.floor(p * 2.0 ** 24).astype(np.int64) + rng.integers(-8, 9, n), 0, (1 << 24) - 1)
+            k = np.clip(np.floor(p * 2.0 ** 24).astype(np.int64) + rng.integers(-32, 33, n), 0, (1 << 24) - 1)
         u = k.astype(np.float32) * np.float32(2.0 ** -24)
         got, fast = B.nvfp4_46_debug_e2m1_sr(torch.from_numpy(y).cuda(), _words(k, rng))
         got, fast = got.cpu().numpy(), fast.cpu().numpy()
