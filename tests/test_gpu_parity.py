@@ -310,6 +310,37 @@ def test_fp32_input_decision_stress():
     assert 0.02 < float(_np(out["choice_row"]).mean()) < 0.9
 
 
+@pytest.mark.parametrize("select", [B.SEL_FORCE6, B.SEL_46_MSE])
+def test_stochastic_rounding_at_its_thresholds_end_to_end(select):
+    """FP32 values placed within a few 2^-25 of the threshold their own uniform sets (the uniform
+    of an element is known from the seed and its index): the cases in which the conversion
+    instruction alone would round differently from the stated rule, so the kernel's margin test
+    and its software path decide most blocks here.  Every block's maximum is 6 and alpha is 1,
+    so under the scale-to-6 candidate the scaled value is the input itself."""
+    rows, cols = 64, 256
+    rng = np.random.default_rng(77)
+    k = np.array([round(ref.sr_uniform(SR_SEED, g) * 2.0 ** 24) for g in range(rows * cols)],
+                 np.int64).reshape(rows, cols)
+    d = rng.integers(-3, 4, (rows, cols))
+    half = rng.random((rows, cols)) < 0.5                   # lower grid point 0.5 instead of 0
+    n = np.clip(k + d, 0, (1 << 24) - 2)
+    n = np.where(half, n & ~1, n)                           # 2^24 + n must fit 24 bits: even n
+    mag = np.where(half, 0.5, 0.0) + n.astype(np.float64) * 2.0 ** -25
+    x = (mag * rng.choice([-1.0, 1.0], (rows, cols))).astype(np.float32)
+    assert np.array_equal(np.abs(x).astype(np.float64), mag)   # exactly representable
+    x[:, ::16] = 6.0
+    xt = torch.from_numpy(x)
+    # how many of these the instruction alone gets wrong (diagnostic, through the debug entry)
+    words = torch.from_numpy(((k << 8) | 0x33).astype(np.uint32).view(np.int32).reshape(-1)).cuda()
+    got, fast = B.nvfp4_46_debug_e2m1_sr(xt.reshape(-1).cuda(), words)
+    wrong = ((fast & 0x0F) != got).float().mean().item()
+    flagged = ((fast & 0x80) != 0).float().mean().item()
+    _log(f"instruction alone differs on {wrong:.3f} of the elements, margin test fires on {flagged:.3f}")
+    assert wrong > 0.05 and flagged > 0.5
+    check_case(xt, rounding=B.SR, select=select, alpha_value=1.0, tag="sr-thresholds")
+    check_case(xt, layout=B.COLWISE, rounding=B.SR, select=select, alpha_value=1.0, tag="sr-thresholds-col")
+
+
 def test_fp32_input_sees_the_low_mantissa_bits():
     """The fp32 path must not round x to BF16 on the way in: its result differs from that of
     the BF16-rounded tensor, and equals it when the values are BF16 values to begin with."""
