@@ -714,6 +714,8 @@ def main():
                         "seed 4602; step = tensor_scale (one launch, workspace form) + rowwise 4/6 "
                         "RTN quantize + dequantize",
             "buffer_sets": len(sets),
+            "generator": f"torch.Generator(cpu) of torch {torch.__version__} "
+                         "(paper_2512_02010_amd/workloads.py)",
         },
         "roofline": {
             "bound": "hbm",
