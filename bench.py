@@ -358,6 +358,14 @@ def time_other_workloads(iters=30):
         res["c2_variants_main_us"][name] = med(
             lambda i: B.quantize_raw(xs[i % 2], p, alpha, os_[i % 2]["codes_row"],
                                      os_[i % 2]["scales_row"], None, None, None, None, st))
+    # 16x16 tiles with the packing for the transposed matrix written in the same pass (what the
+    # layer's weight quantization runs): 3.125 B/elem, back-to-back launches
+    ob = [B.alloc_outputs(r, c, B.BOTH, "cuda", want_choice=False, block2d=1) for _ in range(2)]
+    p = B.make_params(r, c, layout=B.BOTH, block2d=1)
+    res["c2_variants_main_us"]["16x16 tiles, both packings"] = med(
+        lambda i: B.quantize_raw(xs[i % 2], p, alpha, ob[i % 2]["codes_row"], ob[i % 2]["scales_row"],
+                                 ob[i % 2]["codes_col"], ob[i % 2]["scales_col"], None, None, st))
+    del ob
     # quantization error of each block-scale rule on the same tensor (what Tables 2 and 4 of the
     # paper measure in perplexity, here as normalised mean squared / mean absolute error)
     xf = xs[0].double()

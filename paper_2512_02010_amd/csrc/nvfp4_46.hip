@@ -817,6 +817,10 @@ __global__ __launch_bounds__(kThreads) void k_dequant_col(const uint8_t *__restr
 // column j packed the same way (row i in bits 4i..4i+3).  The usual recursive transpose:
 // swap the off-diagonal 8x8 blocks between lanes 8 apart, then 4x4 blocks between lanes 4
 // apart inside every 8x8 block, and so on down to single codes.
+// 8-byte pieces per row of the LDS staging of transposed codes in k_block2d: 16 + 2, so that
+// sixteen lanes writing one piece each to sixteen rows fall in different banks
+constexpr uint32_t kColStagePitch = 18;
+
 NV_DEV void transpose_codes16(uint32_t &lo, uint32_t &hi) {
   const uint32_t lane = threadIdx.x;
   {
@@ -839,7 +843,7 @@ NV_DEV void transpose_codes16(uint32_t &lo, uint32_t &hi) {
   stage(hi, 1u, 0x0f0f0f0fu, 4);
 }
 
-template <bool XF32, int ROUNDING, int SELECT, int OUT>
+template <bool XF32, int ROUNDING, int SELECT, int OUT, bool BY_UNITS>
 __global__ __launch_bounds__(kThreads) void k_block2d(
     const void *__restrict__ x_any, const float *__restrict__ alpha_p, uint8_t *__restrict__ codes,
     uint8_t *__restrict__ scales, uint8_t *__restrict__ choice, uint8_t *__restrict__ codes_col,
@@ -848,17 +852,37 @@ __global__ __launch_bounds__(kThreads) void k_block2d(
   __shared__ ScaleTable tab;
   const ScaleConsts sc = build_scale_table(tab, *alpha_p);
   const uint32_t tid = threadIdx.x, r_in_tile = tid & 15u, grp = tid >> 4;
-  const int64_t ncb = cols / 16, n_tiles = (rows / 16) * ncb;
-  constexpr int kGroups = kThreads / 16;
+  // rows, cols <= 2^31 and rows * cols <= 2^40 (checked by the entry point): tile coordinates
+  // and tile numbers fit 32 bits
+  const uint32_t ncb = (uint32_t)(cols / 16), nrb = (uint32_t)(rows / 16);
+  const uint64_t n_tiles = (uint64_t)nrb * ncb;
   constexpr int kCandRounding = ROUNDING == kSRAfterRtnSelect ? kRTN : ROUNDING;
   constexpr int kErr = SELECT == kSel46     ? kErrMseEstimate
                        : SELECT == kSel46Mae ? kErrMae
                        : SELECT == kSel46AbsMax ? kErrAbsMax : kErrNone;
-  for (int64_t T = (int64_t)blockIdx.x * kGroups + grp; T < n_tiles;
-       T += (int64_t)gridDim.x * kGroups) {
-    const int64_t tr = T / ncb, tc = T - tr * ncb;
-    const int64_t row = tr * 16 + r_in_tile;
-    const int64_t first = row * cols + tc * 16;           // flat index of the lane's first element
+  // Two ways to hand tiles to workgroups (the launcher's grid matches):
+  //  * one packing: workgroup id -> sixteen consecutive tiles along a row of tiles, one per group
+  //    of sixteen lanes; a row of x is read, and its codes written, 128 contiguous bytes at a
+  //    time by the workgroup;
+  //  * with the packing for the transposed matrix as well, whose codes are 8 bytes per lane 4 KiB
+  //    and more apart (stored like that they cost 1.9x their bytes in HBM writes and 35 us on
+  //    8192 x 8192): workgroup id -> a unit of 16 tile rows x 4 tile columns, taken in four
+  //    steps of 4 x 4 tiles (wave w: tile row 4 * step + w; its four groups: the tile columns).
+  //    The unit's transposed codes (64 rows of the transposed matrix x 16 pieces of 8 bytes) are
+  //    gathered in LDS and leave as whole 128-byte lines; row codes leave as 32 contiguous bytes
+  //    per store instruction, and id -> unit keeps the four units that share their 128-byte
+  //    lines on one die's L2 (ids 8 apart).
+  constexpr bool by_units = BY_UNITS;
+  static_assert(!BY_UNITS || OUT == kOutCodes, "units are for the transposed packing");
+  __shared__ uint2 col_stage[BY_UNITS ? 64 * kColStagePitch : 1];
+  const uint32_t wave = tid >> 6, g4 = grp & 3u;
+  const uint32_t ncq = (ncb + 3u) / 4u, n_units = ((nrb + 15u) / 16u) * ncq;
+  const uint32_t n_ids = by_units ? ((n_units + 31u) / 32u) * 32u : (uint32_t)((n_tiles + 15u) / 16u);
+  const uint32_t n_steps = by_units ? 4u : 1u;
+  auto tile_body = [&](uint32_t tr, uint32_t tc, uint32_t trl) {
+    const uint64_t row = (uint64_t)tr * 16 + r_in_tile;
+    const uint64_t first = row * (uint64_t)cols + tc * 16u;  // flat index of the lane's first element
+    const uint64_t T = (uint64_t)tr * ncb + tc;
     RawBlock<XF32> raw;
     load_block<XF32>(static_cast<const uint4 *>(x_any) + first / (XF32 ? 4 : 8), raw);
     float v[16];
@@ -930,20 +954,19 @@ __global__ __launch_bounds__(kThreads) void k_block2d(
       (void)candidate<kSR, kErrNone>(v, u, res.dec, four ? enc4 : enc6, res.lo, res.hi);
     if (OUT == kOutCodes) {
       if (codes) {
-        *reinterpret_cast<uint2 *>(codes + row * (cols / 2) + tc * 8) = make_uint2(res.lo, res.hi);
+        *reinterpret_cast<uint2 *>(codes + first / 2) = make_uint2(res.lo, res.hi);
         if (r_in_tile == 0) {
           scales[T] = (uint8_t)res.scale;
           if (choice) choice[T] = (uint8_t)res.four;
         }
       }
-      if (codes_col) {
+      if (BY_UNITS) {
         // the same tile for the transposed matrix: column (tc*16 + lane) of x is its row
         uint32_t lo = res.lo, hi = res.hi;
         transpose_codes16(lo, hi);
-        const int64_t col = tc * 16 + r_in_tile;
-        *reinterpret_cast<uint2 *>(codes_col + col * (rows / 2) + tr * 8) = make_uint2(lo, hi);
+        col_stage[(g4 * 16u + r_in_tile) * kColStagePitch + trl] = make_uint2(lo, hi);
         if (r_in_tile == 0) {
-          const int64_t Tt = tc * (rows / 16) + tr;
+          const uint64_t Tt = (uint64_t)tc * nrb + tr;
           scales_col[Tt] = (uint8_t)res.scale;
           if (choice_col) choice_col[Tt] = (uint8_t)res.four;
         }
@@ -957,6 +980,44 @@ __global__ __launch_bounds__(kThreads) void k_block2d(
                           pack_bf16x2(D0[4], D0[5]), pack_bf16x2(D0[6], D0[7]));
       dst[1] = make_uint4(pack_bf16x2(D1[0], D1[1]), pack_bf16x2(D1[2], D1[3]),
                           pack_bf16x2(D1[4], D1[5]), pack_bf16x2(D1[6], D1[7]));
+    }
+  };
+  for (uint32_t id = blockIdx.x; id < n_ids; id += gridDim.x) {
+    // by units: the same for the whole workgroup
+    const uint32_t slot = id >> 3, unit = (((slot >> 2) << 3) + (id & 7u)) * 4u + (slot & 3u);
+    const uint32_t mr = unit / ncq, cq = unit - mr * ncq;
+#pragma unroll 1
+    for (uint32_t step = 0; step < n_steps; ++step) {
+      uint32_t tr, tc, trl = step * 4u + wave;
+      bool live;
+      if (by_units) {
+        tr = mr * 16u + trl;
+        tc = cq * 4u + g4;
+        live = unit < n_units && tr < nrb && tc < ncb;
+      } else {
+        const uint32_t t = id * 16u + grp;
+        tr = t / ncb;
+        tc = t - tr * ncb;
+        live = (uint64_t)id * 16u + grp < n_tiles;
+      }
+      if (live) tile_body(tr, tc, trl);
+      if (by_units && step == 3u) {
+        // the unit's 64 rows of the transposed matrix, 16 pieces of 8 bytes each: sixteen
+        // consecutive lanes store one 128-byte line
+        __syncthreads();
+        if (unit < n_units) {
+#pragma unroll 1
+          for (uint32_t j = 0; j < 4; ++j) {
+            const uint32_t piece = tid + j * kThreads, line = piece >> 4, k = piece & 15u;
+            const uint64_t col = ((uint64_t)cq * 4 + (line >> 4)) * 16 + (line & 15u);
+            const uint32_t tr_k = mr * 16u + k;
+            if (col < (uint64_t)cols && tr_k < nrb)
+              *reinterpret_cast<uint2 *>(codes_col + col * (uint64_t)(rows / 2) + tr_k * 8u) =
+                  col_stage[line * kColStagePitch + k];
+          }
+        }
+        __syncthreads();
+      }
     }
   }
 }
@@ -1203,15 +1264,20 @@ struct Block2dArgs {
 
 template <bool XF32, int ROUNDING, int SELECT>
 static int launch_block2d(const Block2dArgs &a, int out) {
+  // ids as the kernel counts them: sixteen tiles each, or - with the transposed packing - units
+  // of 16 x 4 tiles in whole groups of 32
   const int64_t tiles = (a.rows / 16) * (a.cols / 16);
-  const int grid = grid_for(tiles * 16, 16);
+  const int64_t units = ((a.rows / 16 + 15) / 16) * ((a.cols / 16 + 3) / 4);
+  const int64_t ids = out == kOutCodes && a.codes_col ? ((units + 31) / 32) * 32 : (tiles + 15) / 16;
+  const int grid = grid_for(ids * kThreads, 16);
   auto go = [&](auto kernel) {
     return launch(kernel, dim3(grid), dim3(kThreads), a.stream, a.x, a.alpha, a.codes, a.scales,
                   a.choice, a.codes_col, a.scales_col, a.choice_col, a.out, a.rows, a.cols,
                   a.sr_seed);
   };
-  if (out == kOutCodes) return go(k_block2d<XF32, ROUNDING, SELECT, kOutCodes>);
-  return go(k_block2d<XF32, ROUNDING, SELECT, kOutFake>);
+  if (out == kOutCodes && a.codes_col) return go(k_block2d<XF32, ROUNDING, SELECT, kOutCodes, true>);
+  if (out == kOutCodes) return go(k_block2d<XF32, ROUNDING, SELECT, kOutCodes, false>);
+  return go(k_block2d<XF32, ROUNDING, SELECT, kOutFake, false>);
 }
 
 // All 16x16-tile kernels of one (input type, rounding mode) pair.

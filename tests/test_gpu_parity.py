@@ -262,6 +262,30 @@ def test_block2d_packing_for_the_transposed_matrix(layout, select, rounding):
         assert np.array_equal(ref.dequantize_2d_columnwise(cc_ref, sc_ref, a, rows, cols), d_ref)
 
 
+def test_block2d_both_packings_past_one_round_of_the_grid():
+    """4112 x 16400: 257 x 1025 tiles, so the last row and the last column of the kernel's work
+    units (16 x 4 tiles) are ragged, and there are more units (4369) than workgroups in the
+    grid (16 per compute unit), so workgroups take a second unit."""
+    rows, cols = 4112, 16400
+    x = wl.make("c2", rows, cols)
+    xh, xd = wl.host_array(x), x.cuda()
+    alpha = B.nvfp4_46_tensor_scale(xd)
+    a = float(alpha.item())
+    c_ref, s_ref, f_ref, _ = ref.quantize_2d(xh, a)
+    cc_ref, sc_ref, fc_ref = ref.repack_2d_columnwise(c_ref, s_ref, f_ref)
+    for layout in (B.BOTH, B.COLWISE, B.ROWWISE):
+        _log(f"block2d at size: layout {layout}")
+        out = B.nvfp4_46_quantize(xd, alpha, layout=layout, block2d=1)
+        if layout & B.COLWISE:
+            assert np.array_equal(_np(out["codes_col"]), cc_ref)
+            assert np.array_equal(_np(out["scales_col"]), sc_ref)
+            assert np.array_equal(_np(out["choice_col"]), fc_ref)
+        if layout & B.ROWWISE:
+            assert np.array_equal(_np(out["codes_row"]), c_ref)
+            assert np.array_equal(_np(out["scales_row"]), s_ref)
+            assert np.array_equal(_np(out["choice_row"]), f_ref)
+
+
 def test_block2d_transpose_consistency_on_gpu():
     # under a fixed scale rule, quantizing W^T with 16x16 tiles is the transpose of quantizing W
     x = wl.make("c2", 512, 768)
