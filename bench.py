@@ -570,6 +570,17 @@ def main():
             for i in range(4):
                 B.quantize_raw(x5, p5, a5, o4["codes_row"], o4["scales_row"], None, None, None,
                                None, st)
+            # one scale per 16x16 tile on the c2 tensor: the rowwise packing alone, and with the
+            # packing for the transposed matrix from the same pass
+            ob = B.alloc_outputs(rows, cols, B.BOTH, "cuda", want_choice=False, block2d=1)
+            pr = B.make_params(rows, cols, block2d=1)
+            pb = B.make_params(rows, cols, layout=B.BOTH, block2d=1)
+            for i in range(4):
+                xs_ = sets[i % len(sets)]
+                B.quantize_raw(xs_.x, pr, xs_.alpha, ob["codes_row"], ob["scales_row"], None, None,
+                               None, None, st)
+                B.quantize_raw(xs_.x, pb, xs_.alpha, ob["codes_row"], ob["scales_row"],
+                               ob["codes_col"], ob["scales_col"], None, None, st)
         torch.cuda.synchronize()
         print("counter pass done: 3 copies of %d bytes, 6 steps" % (n * 2))
         return
