@@ -405,11 +405,13 @@ def time_other_workloads(iters=30):
     wf = xh.cuda()
     dy = wl.make("c1", 8192, 8192).cuda()
 
+    ws = B.new_workspace()       # the five tensor scales of a step: one launch each
+
     def layer_step():
-        qw = linear.quantize_weight(wf)
-        linear.fprop(xa, qw)
-        linear.dgrad(dy, qw, sr_seed=wl.C5_SR_SEED)
-        linear.wgrad(dy, xa, sr_seed=wl.C5_SR_SEED, rht_seed=wl.C5_RHT_SEED)
+        qw = linear.quantize_weight(wf, workspace=ws)
+        linear.fprop(xa, qw, workspace=ws)
+        linear.dgrad(dy, qw, sr_seed=wl.C5_SR_SEED, workspace=ws)
+        linear.wgrad(dy, xa, sr_seed=wl.C5_SR_SEED, rht_seed=wl.C5_RHT_SEED, workspace=ws)
 
     def wall(fn, n=10):
         for _ in range(2):
@@ -528,11 +530,12 @@ def main():
         xa = wl.make("c3", 8192, 8192).cuda()
         wf = wl.make("c2", dtype=torch.float32).cuda()
         dy = wl.make("c1", 8192, 8192).cuda()
+        ws = B.new_workspace()
         for _ in range(5):
-            qw = linear.quantize_weight(wf)
-            linear.fprop(xa, qw)
-            linear.dgrad(dy, qw, sr_seed=wl.C5_SR_SEED)
-            linear.wgrad(dy, xa, sr_seed=wl.C5_SR_SEED, rht_seed=wl.C5_RHT_SEED)
+            qw = linear.quantize_weight(wf, workspace=ws)
+            linear.fprop(xa, qw, workspace=ws)
+            linear.dgrad(dy, qw, sr_seed=wl.C5_SR_SEED, workspace=ws)
+            linear.wgrad(dy, xa, sr_seed=wl.C5_SR_SEED, rht_seed=wl.C5_RHT_SEED, workspace=ws)
         torch.cuda.synchronize()
         print("layer pass done: 5 steps")
         return

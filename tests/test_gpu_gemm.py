@@ -416,3 +416,13 @@ def test_linear_layer_module(block2d):
                               qw["scales_row"], qw["alpha"],
                               flags=B.GEMM_B_TILE_SCALES if block2d else 0)
     assert torch.equal(by_hand, y)
+
+    # the same step with the one-launch tensor scales (one workspace for all five)
+    ws = B.new_workspace()
+    qw2 = linear.quantize_weight(w, block2d=block2d, workspace=ws)
+    assert torch.equal(qw2["alpha"], qw["alpha"]) and torch.equal(qw2["codes_col"], qw["codes_col"])
+    assert torch.equal(linear.fprop(x, qw2, workspace=ws), y)
+    assert torch.equal(linear.dgrad(dy, qw2, sr_seed=wl.C5_SR_SEED, workspace=ws), dx)
+    assert torch.equal(linear.wgrad(dy, x, sr_seed=wl.C5_SR_SEED, rht_seed=wl.C5_RHT_SEED,
+                                    workspace=ws), dw)
+    assert not bool(ws.any())            # left zeroed
