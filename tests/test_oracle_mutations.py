@@ -36,6 +36,14 @@ MUTANTS = [
      'for (int j = 0; j < 4; ++j) a[j] = p[j] + p[j + 4];',
      'for (int j = 0; j < 4; ++j) a[j] = p[j] + p[j + 3];',
      'tests/test_oracle_block2d.py::test_tile_selection_is_by_the_tile_error[0]'),
+    ('error tree folds adjacent pairs instead of the upper onto the lower part',
+     'for (int j = 0; j < 4; ++j) a[j] = p[j] + p[j + 4];',
+     'for (int j = 0; j < 4; ++j) a[j] = p[2 * j] + p[2 * j + 1];',
+     'tests/test_oracle_order_transcriptions.py::test_squared_errors_are_added_in_the_stated_tree'),
+    ('Hadamard stages from stride eight down',
+     'for (int h = 1; h < BLOCK; h <<= 1)\n    for (int i = 0; i < BLOCK; ++i)\n      if ((i & h) == 0) {',
+     'for (int h = 8; h >= 1; h >>= 1)\n    for (int i = 0; i < BLOCK; ++i)\n      if ((i & h) == 0) {',
+     'tests/test_oracle_order_transcriptions.py::test_hadamard_stages_run_from_stride_one_up'),
     ('both candidates scaled to 4',
      'S6 = ref_block_scale(b, alpha, 6.0f);',
      'S6 = ref_block_scale(b, alpha, 4.0f);',

@@ -1,0 +1,90 @@
+"""The two fixed operation orders the oracle had to choose (the paper states neither): the tree in
+which a block's sixteen squared errors are added, and the stage order of the 16-point Hadamard
+butterflies.  Each is written here a second time, as whole-array numpy fp32 operations rather
+than the oracle's scalar loops, and compared bit for bit on inputs where the order matters; the
+same inputs are shown to tell other orders apart, so the comparison is not vacuous.  This pins
+the oracle to its stated reading of the order, not to the paper (which has no such statement).
+"""
+import numpy as np
+
+from oracle import ref
+
+F = np.float32
+
+
+def _bits(a):
+    return np.asarray(a, dtype=F).view(np.uint32)
+
+
+def _tree_of_halves(e):
+    """Each half 8 -> 4 -> 2 -> 1 by adding the upper to the lower part, then the two halves."""
+    e = np.asarray(e, dtype=F).reshape(2, 8)
+    a = e[:, :4] + e[:, 4:]
+    b = a[:, :2] + a[:, 2:]
+    c = b[:, 0] + b[:, 1]
+    return F(c[0] + c[1])
+
+
+def _sequential(e):
+    s = F(0)
+    for t in np.asarray(e, dtype=F):
+        s = F(s + t)
+    return s
+
+
+def _adjacent_pairs(e):
+    e = np.asarray(e, dtype=F)
+    while e.size > 1:
+        e = e[0::2] + e[1::2]
+    return F(e[0])
+
+
+def test_squared_errors_are_added_in_the_stated_tree():
+    rng = np.random.default_rng(4690)
+    differs_seq = differs_adj = 0
+    for trial in range(400):
+        v = (rng.standard_normal(16) * np.exp(rng.standard_normal(16))).astype(F)
+        alpha = F(np.abs(v).max() / F(1536.0))
+        for M in (6.0, 4.0):
+            S = ref.block_scale(float(np.abs(v).max()), float(alpha), M)
+            E, _, D = ref.block_with_scale(v, float(alpha), S)
+            d = D.astype(F) - v              # one fp32 subtraction per element
+            e = d * d                        # one fp32 multiplication per element
+            assert _bits(E) == _bits(_tree_of_halves(e)), (trial, M)
+            differs_seq += _bits(_sequential(e)) != _bits(E)
+            differs_adj += _bits(_adjacent_pairs(e)) != _bits(E)
+    # the inputs do distinguish this tree from the two other natural orders
+    assert differs_seq > 100 and differs_adj > 100, (differs_seq, differs_adj)
+
+
+def test_absolute_errors_use_the_same_tree():
+    rng = np.random.default_rng(4691)
+    for trial in range(200):
+        v = rng.standard_normal(16).astype(F)
+        D = (v + rng.standard_normal(16).astype(F) * F(0.1)).astype(F)
+        want = _tree_of_halves(np.abs(D - v))
+        assert _bits(ref.block_abs_metric(v, D, ref.SEL_46_MAE)) == _bits(want), trial
+
+
+def _butterflies(v, strides):
+    v = np.asarray(v, dtype=F).copy()
+    for h in strides:
+        g = v.reshape(16 // (2 * h), 2, h)
+        top, bottom = g[:, 0, :].copy(), g[:, 1, :].copy()
+        g[:, 0, :] = top + bottom
+        g[:, 1, :] = top - bottom
+        v = g.reshape(16)
+    return v * F(0.25)
+
+
+def test_hadamard_stages_run_from_stride_one_up():
+    rng = np.random.default_rng(4692)
+    differs_reversed = 0
+    for trial in range(400):
+        v = (rng.standard_normal(16) * np.exp(2 * rng.standard_normal(16))).astype(F)
+        word = int(rng.integers(0, 1 << 16))
+        signed = np.where((word >> np.arange(16)) & 1, -v, v).astype(F)
+        got = ref.rht16(v, word)
+        assert np.array_equal(_bits(got), _bits(_butterflies(signed, (1, 2, 4, 8)))), trial
+        differs_reversed += not np.array_equal(_bits(got), _bits(_butterflies(signed, (8, 4, 2, 1))))
+    assert differs_reversed > 100, differs_reversed
