@@ -286,6 +286,48 @@ def test_block2d_both_packings_past_one_round_of_the_grid():
             assert np.array_equal(_np(out["choice_row"]), f_ref)
 
 
+def _sweep_cases_2d(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        cases.append(dict(
+            rows=int(rng.integers(1, 80)) * 16, cols=int(rng.integers(1, 120)) * 16,
+            layout=int(rng.choice([B.ROWWISE, B.COLWISE, B.BOTH], p=[0.2, 0.2, 0.6])),
+            rounding=int(rng.choice([B.RTN, B.SR, B.SR_AFTER_RTN_SELECT])),
+            select=int(rng.choice([B.SEL_46_MSE, B.SEL_FORCE6, B.SEL_FORCE4, B.SEL_46_MAE,
+                                   B.SEL_46_ABSMAX], p=[0.4, 0.1, 0.1, 0.2, 0.2])),
+            name=str(rng.choice(["c1", "c2", "c3", "c5"])), f32=bool(rng.integers(0, 2))))
+    return cases
+
+
+def check_case_2d(c, seed, tag):
+    _log(f"2d sweep {tag}: {c}")
+    x = wl.make(c["name"], c["rows"], c["cols"], seed=seed,
+                dtype=torch.float32 if c["f32"] else torch.bfloat16)
+    xh, xd = wl.host_array(x), x.cuda()
+    alpha = B.nvfp4_46_tensor_scale(xd)
+    a = float(alpha.item())
+    kw = dict(rounding=c["rounding"], select=c["select"], sr_seed=SR_SEED)
+    c_ref, s_ref, f_ref, _ = ref.quantize_2d(xh, a, **kw)
+    out = B.nvfp4_46_quantize(xd, alpha, layout=c["layout"], block2d=1, **kw)
+    if c["layout"] & B.ROWWISE:
+        assert np.array_equal(_np(out["codes_row"]), c_ref), tag
+        assert np.array_equal(_np(out["scales_row"]), s_ref), tag
+        assert np.array_equal(_np(out["choice_row"]), f_ref), tag
+    if c["layout"] & B.COLWISE:
+        cc_ref, sc_ref, fc_ref = ref.repack_2d_columnwise(c_ref, s_ref, f_ref)
+        assert np.array_equal(_np(out["codes_col"]), cc_ref), tag
+        assert np.array_equal(_np(out["scales_col"]), sc_ref), tag
+        assert np.array_equal(_np(out["choice_col"]), fc_ref), tag
+
+
+def test_seeded_sweep_of_block2d_shapes_and_options():
+    """Thirty drawn combinations of tile-grid shape (ragged against the kernel's 16 x 4-tile work
+    units), packing(s), rounding, rule and input type, each compared element by element."""
+    for i, c in enumerate(_sweep_cases_2d(30, 4647)):
+        check_case_2d(c, 9500 + i, f"2d-{i}")
+
+
 def test_block2d_transpose_consistency_on_gpu():
     # under a fixed scale rule, quantizing W^T with 16x16 tiles is the transpose of quantizing W
     x = wl.make("c2", 512, 768)
