@@ -44,6 +44,10 @@ MUTANTS = [
      'for (int h = 1; h < BLOCK; h <<= 1)\n    for (int i = 0; i < BLOCK; ++i)\n      if ((i & h) == 0) {',
      'for (int h = 8; h >= 1; h >>= 1)\n    for (int i = 0; i < BLOCK; ++i)\n      if ((i & h) == 0) {',
      'tests/test_oracle_order_transcriptions.py::test_hadamard_stages_run_from_stride_one_up'),
+    ('tile error adds the row errors one after the other',
+     'E[m] = error_sum(rowerr);',
+     '{ float sum = 0.0f; for (int r = 0; r < BLOCK; ++r) sum += rowerr[r]; E[m] = sum; }',
+     'tests/test_oracle_order_transcriptions.py::test_tile_errors_are_the_row_errors_in_the_same_tree'),
     ('both candidates scaled to 4',
      'S6 = ref_block_scale(b, alpha, 6.0f);',
      'S6 = ref_block_scale(b, alpha, 4.0f);',
