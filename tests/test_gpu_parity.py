@@ -328,6 +328,38 @@ def test_seeded_sweep_of_block2d_shapes_and_options():
         check_case_2d(c, 9500 + i, f"2d-{i}")
 
 
+def test_block2d_tiles_within_a_few_steps_of_a_tie():
+    """Tiles whose two candidates' errors cross between two adjacent fp32 values of one element
+    (tests/_near_ties.py), eighteen steps around each crossing, one tile each, under one common
+    alpha: the estimates cannot decide these, so the kernel's defined-error path and the order
+    in which sixteen lanes add their row errors decide them; choices must equal the oracle's."""
+    from tests._near_ties import STEPS, crossings
+    from tests.test_oracle_order_transcriptions import _tree_of_halves
+    alpha = float(np.float32(1.0) / np.float32(1536.0))
+    tiles = []
+    for t, r, c, first, _, _, _ in crossings(400, 4694, _tree_of_halves, alpha=alpha):
+        for step in STEPS:
+            tile = t.copy()
+            tile[r, c] = np.uint32(first + step).view(np.float32)
+            tiles.append(tile)
+    n = len(tiles) // 16 * 16
+    assert n >= 256, n
+    x = np.block([[tiles[16 * i + j] for j in range(16)] for i in range(n // 16)])   # [n][256]
+    _log(f"near-tie tiles: {n} tiles, tensor {x.shape}")
+    c_ref, s_ref, f_ref, _ = ref.quantize_2d(x, alpha)
+    assert 0.2 < f_ref.mean() < 0.8                       # they do go both ways
+    xd = torch.from_numpy(x).cuda()
+    ad = torch.tensor([alpha], dtype=torch.float32, device="cuda")
+    for layout in (B.ROWWISE, B.BOTH):
+        out = B.nvfp4_46_quantize(xd, ad, layout=layout, block2d=1)
+        assert np.array_equal(_np(out["choice_row"]), f_ref)
+        assert np.array_equal(_np(out["scales_row"]), s_ref)
+        assert np.array_equal(_np(out["codes_row"]), c_ref)
+    cc_ref, sc_ref, fc_ref = ref.repack_2d_columnwise(c_ref, s_ref, f_ref)
+    assert np.array_equal(_np(out["choice_col"]), fc_ref)
+    assert np.array_equal(_np(out["codes_col"]), cc_ref)
+
+
 def test_block2d_transpose_consistency_on_gpu():
     # under a fixed scale rule, quantizing W^T with 16x16 tiles is the transpose of quantizing W
     x = wl.make("c2", 512, 768)

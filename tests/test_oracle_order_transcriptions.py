@@ -8,6 +8,7 @@ the oracle to its stated reading of the order, not to the paper (which has no su
 import numpy as np
 
 from oracle import ref
+from tests._near_ties import STEPS, crossings
 
 F = np.float32
 
@@ -90,76 +91,27 @@ def test_hadamard_stages_run_from_stride_one_up():
     assert differs_reversed > 100, differs_reversed
 
 
-def _tile_errors(t, alpha, S, tree):
-    rowerr = np.array([ref.block_with_scale(t[r], alpha, S)[0] for r in range(16)], dtype=F)
-    return rowerr, tree(rowerr)
-
-
 def test_tile_errors_are_the_row_errors_in_the_same_tree():
     """16x16 tiles (fp32 input): one element of a tile is moved, one fp32 step at a time, through
-    a point where the two candidates' tile errors cross; around the crossing the oracle's
-    choice must be `tree(row errors of 4) < tree(row errors of 6)` at every step, and adding
-    the sixteen row errors one after the other would choose differently at some of them."""
-    rng = np.random.default_rng(4693)
-    crossings = steps_checked = sequential_differs = 0
-    for trial in range(500):
-        # magnitudes U^2.2: the distribution on which a tile's two candidates come out about even
-        t = (np.sign(rng.standard_normal((16, 16))) * rng.random((16, 16)) ** 2.2).astype(F)
-        alpha = ref.tensor_scale(t)
-        b = float(np.abs(t).max())
-        S6, S4 = ref.block_scale(b, alpha, 6.0), ref.block_scale(b, alpha, 4.0)
-        err6, _ = _tile_errors(t, alpha, S6, _tree_of_halves)
-        err4, _ = _tile_errors(t, alpha, S4, _tree_of_halves)
-
-        def at(r, c, pattern):
-            """Row errors, their difference and (r, c)'s two dequantized values with the
-            element at (r, c) set to the fp32 value of this bit pattern."""
-            row = t[r].copy()
-            row[c] = np.uint32(pattern).view(F)
-            e6, e4 = err6.copy(), err4.copy()
-            e6[r], _, d6 = ref.block_with_scale(row, alpha, S6)
-            e4[r], _, d4 = ref.block_with_scale(row, alpha, S4)
-            gap = float(_tree_of_halves(e4)) - float(_tree_of_halves(e6))
-            return e6, e4, gap, (float(d6[c]), float(d4[c]))
-
-        found = None
-        for r, c in rng.integers(0, 16, (8, 2)):
-            r, c = int(r), int(c)
-            if not 0.02 * b < abs(t[r, c]) < 0.6 * b:      # not the maximum, not negligible
-                continue
-            # 48 samples over [v/2, 3v/2]; a sign change of the difference between two samples
-            # that round to the same codes is a continuous crossing
-            prev = None
-            for k in range(48):
-                pattern = int(F(t[r, c] * F(0.5 + k / 47.0)).view(np.uint32))
-                _, _, g, dq = at(r, c, pattern)
-                if prev and prev[2] == dq and g != 0 and prev[1] != 0 and (g < 0) != (prev[1] < 0):
-                    found = (r, c, prev[0], pattern)
-                    break
-                prev = (pattern, g, dq)
-            if found:
-                break
-        if not found:
-            continue
-        r, c, lo, hi = found
-        if lo > hi:                      # a negative element: its patterns run the other way
-            lo, hi = hi, lo
-        g_lo = at(r, c, lo)[2]
-        while hi - lo > 1:
-            mid = (lo + hi) // 2
-            g = at(r, c, mid)[2]
-            if g != 0 and (g < 0) == (g_lo < 0):
-                lo = mid
-            else:
-                hi = mid
-        crossings += 1
-        for pattern in range(lo - 3, lo + 5):
-            e6, e4, _, _ = at(r, c, pattern)
+    a point where the two candidates' tile errors cross (tests/_near_ties.py); around the
+    crossing the oracle's choice must be `tree(row errors of 4) < tree(row errors of 6)` at every
+    step, and adding the sixteen row errors one after the other would choose differently at some
+    of them."""
+    n_crossings = steps_checked = sequential_differs = 0
+    fours = []
+    for t, r, c, first, alpha, S6, S4 in crossings(500, 4693, _tree_of_halves):
+        n_crossings += 1
+        for step in STEPS:
+            pattern = first + step
             tile = t.copy()
             tile[r, c] = np.uint32(pattern).view(F)
             assert ref.tensor_scale(tile) == alpha
+            e6 = np.array([ref.block_with_scale(tile[k], alpha, S6)[0] for k in range(16)], dtype=F)
+            e4 = np.array([ref.block_with_scale(tile[k], alpha, S4)[0] for k in range(16)], dtype=F)
             choice = int(ref.quantize_2d(tile, alpha)[2][0, 0])
-            assert choice == int(_tree_of_halves(e4) < _tree_of_halves(e6)), (trial, pattern)
+            assert choice == int(_tree_of_halves(e4) < _tree_of_halves(e6)), (r, c, pattern)
             sequential_differs += choice != int(_sequential(e4) < _sequential(e6))
             steps_checked += 1
-    assert crossings >= 20 and sequential_differs >= 5, (crossings, steps_checked, sequential_differs)
+            fours.append(choice)
+    assert n_crossings >= 20 and sequential_differs >= 20, (n_crossings, steps_checked, sequential_differs)
+    assert 0.25 < np.mean(fours) < 0.75, np.mean(fours)      # the steps do go both ways
