@@ -328,6 +328,42 @@ def test_seeded_sweep_of_block2d_shapes_and_options():
         check_case_2d(c, 9500 + i, f"2d-{i}")
 
 
+def test_blocks_within_a_few_steps_of_a_tie():
+    """1x16 blocks (fp32 input) whose two candidates' errors cross within a few fp32 steps of one
+    element (tests/_near_ties.py), fourteen steps around each crossing, under one alpha: the
+    estimates cannot decide these, the kernels' defined-error path has to, in the stated order
+    of additions.  Rowwise, and the same blocks laid along columns."""
+    from tests._near_ties import BLOCK_STEPS, block_crossings
+    from tests.test_oracle_order_transcriptions import _tree_of_halves
+    alpha = float(np.float32(1.0) / np.float32(1536.0))
+    blocks = []
+    for v, i, first, _, _ in block_crossings(800, 4696, _tree_of_halves, alpha):
+        for step in BLOCK_STEPS:
+            w = v.copy()
+            w[i] = np.uint32(first + step).view(np.float32)
+            blocks.append(w)
+    n = len(blocks) // 256 * 256
+    assert n >= 2048, n
+    x = np.stack(blocks[:n]).reshape(n // 16, 256)            # 16 blocks per row
+    _log(f"near-tie blocks: {n} blocks, tensor {x.shape}")
+    ad = torch.tensor([alpha], dtype=torch.float32, device="cuda")
+    c_ref, s_ref, f_ref = ref.quantize(x, alpha)
+    assert 0.25 < f_ref.mean() < 0.75
+    out = B.nvfp4_46_quantize(torch.from_numpy(x).cuda(), ad)
+    assert np.array_equal(_np(out["choice_row"]), f_ref)
+    assert np.array_equal(_np(out["scales_row"]), s_ref)
+    assert np.array_equal(_np(out["codes_row"]), c_ref)
+    # the same blocks along columns: x^T, quantized columnwise and in both orientations at once
+    xt = np.ascontiguousarray(x.T)                            # [256][n/16]: rows % 16 == 0
+    c_ref, s_ref, f_ref = ref.quantize(xt, alpha, layout=ref.COLWISE)
+    assert 0.25 < f_ref.mean() < 0.75
+    for layout in (B.COLWISE, B.BOTH):
+        out = B.nvfp4_46_quantize(torch.from_numpy(xt).cuda(), ad, layout=layout)
+        assert np.array_equal(_np(out["choice_col"]), f_ref)
+        assert np.array_equal(_np(out["scales_col"]), s_ref)
+        assert np.array_equal(_np(out["codes_col"]), c_ref)
+
+
 def test_block2d_tiles_within_a_few_steps_of_a_tie():
     """Tiles whose two candidates' errors cross between two adjacent fp32 values of one element
     (tests/_near_ties.py), eighteen steps around each crossing, one tile each, under one common

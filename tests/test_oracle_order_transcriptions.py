@@ -8,7 +8,7 @@ the oracle to its stated reading of the order, not to the paper (which has no su
 import numpy as np
 
 from oracle import ref
-from tests._near_ties import STEPS, crossings
+from tests._near_ties import BLOCK_STEPS, STEPS, block_crossings, crossings
 
 F = np.float32
 
@@ -115,3 +115,28 @@ def test_tile_errors_are_the_row_errors_in_the_same_tree():
             fours.append(choice)
     assert n_crossings >= 20 and sequential_differs >= 20, (n_crossings, steps_checked, sequential_differs)
     assert 0.25 < np.mean(fours) < 0.75, np.mean(fours)      # the steps do go both ways
+
+
+def test_blocks_within_a_few_steps_of_a_tie_are_decided_by_the_stated_tree():
+    """The same for 1x16 blocks: around a crossing of E4 and E6 the oracle's choice is the strict
+    comparison of the two trees of squared errors, where sequential sums would differ."""
+    alpha = float(F(1.0) / F(1536.0))
+    n = sequential_differs = 0
+    fours = []
+    for v, i, first, S6, S4 in block_crossings(600, 4695, _tree_of_halves, alpha):
+        n += 1
+        for step in BLOCK_STEPS:
+            w = v.copy()
+            w[i] = np.uint32(first + step).view(F)
+            e = {}
+            for M, S in ((6, S6), (4, S4)):
+                _, _, D = ref.block_with_scale(w, alpha, S)
+                d = D.astype(F) - w
+                e[M] = d * d
+            got = ref.quantize_block(w, alpha)
+            assert (got["S"], got["four"]) in ((S6, 0), (S4, 1))
+            assert got["four"] == int(_tree_of_halves(e[4]) < _tree_of_halves(e[6])), (n, step)
+            sequential_differs += got["four"] != int(_sequential(e[4]) < _sequential(e[6]))
+            fours.append(got["four"])
+    assert n >= 100 and sequential_differs >= 20, (n, sequential_differs)
+    assert 0.25 < np.mean(fours) < 0.75, np.mean(fours)
