@@ -72,11 +72,12 @@ def crossings(n_trials, seed, tree, alpha=None):
 BLOCK_STEPS = (-64, -16, -4, -3, -2, -1, 0, 1, 2, 3, 4, 5, 16, 64)
 
 
-def block_crossings(n_trials, seed, tree, alpha):
+def block_crossings(n_trials, seed, tree, alpha, select=None):
     """The same for one block of sixteen values under the tensor scale alpha: yields
     (block, i, first_pattern, S6, S4); block[i] set to the patterns first_pattern + BLOCK_STEPS
     walks across a crossing of the two candidates' block errors (here one fp32 step of the
-    element moves an error by about one last bit, so the crossing is a few steps wide)."""
+    element moves an error by about one last bit, so the crossing is a few steps wide).
+    `select` None: squared errors; ref.SEL_46_MAE: sums of absolute errors."""
     rng = np.random.default_rng(seed)
     for trial in range(n_trials):
         v = (np.sign(rng.standard_normal(16)) * rng.random(16) ** 2.2).astype(F)
@@ -89,6 +90,8 @@ def block_crossings(n_trials, seed, tree, alpha):
             w[i] = np.uint32(pattern).view(F)
             E6, _, d6 = ref.block_with_scale(w, alpha, S6)
             E4, _, d4 = ref.block_with_scale(w, alpha, S4)
+            if select is not None:
+                E6, E4 = ref.block_abs_metric(w, d6, select), ref.block_abs_metric(w, d4, select)
             return float(E4) - float(E6), (float(d6[i]), float(d4[i]))
 
         found = None

@@ -328,16 +328,19 @@ def test_seeded_sweep_of_block2d_shapes_and_options():
         check_case_2d(c, 9500 + i, f"2d-{i}")
 
 
-def test_blocks_within_a_few_steps_of_a_tie():
+@pytest.mark.parametrize("select", [B.SEL_46_MSE, B.SEL_46_MAE])
+def test_blocks_within_a_few_steps_of_a_tie(select):
     """1x16 blocks (fp32 input) whose two candidates' errors cross within a few fp32 steps of one
     element (tests/_near_ties.py), fourteen steps around each crossing, under one alpha: the
-    estimates cannot decide these, the kernels' defined-error path has to, in the stated order
-    of additions.  Rowwise, and the same blocks laid along columns."""
+    squared-error estimates cannot decide these, the kernels' defined-error path has to, in the
+    stated order of additions (the absolute-error rule is always evaluated as defined, in the
+    same order).  Rowwise, and the same blocks laid along columns."""
     from tests._near_ties import BLOCK_STEPS, block_crossings
     from tests.test_oracle_order_transcriptions import _tree_of_halves
     alpha = float(np.float32(1.0) / np.float32(1536.0))
     blocks = []
-    for v, i, first, _, _ in block_crossings(800, 4696, _tree_of_halves, alpha):
+    metric = None if select == B.SEL_46_MSE else ref.SEL_46_MAE
+    for v, i, first, _, _ in block_crossings(800, 4696, _tree_of_halves, alpha, metric):
         for step in BLOCK_STEPS:
             w = v.copy()
             w[i] = np.uint32(first + step).view(np.float32)
@@ -347,18 +350,18 @@ def test_blocks_within_a_few_steps_of_a_tie():
     x = np.stack(blocks[:n]).reshape(n // 16, 256)            # 16 blocks per row
     _log(f"near-tie blocks: {n} blocks, tensor {x.shape}")
     ad = torch.tensor([alpha], dtype=torch.float32, device="cuda")
-    c_ref, s_ref, f_ref = ref.quantize(x, alpha)
+    c_ref, s_ref, f_ref = ref.quantize(x, alpha, select=select)
     assert 0.25 < f_ref.mean() < 0.75
-    out = B.nvfp4_46_quantize(torch.from_numpy(x).cuda(), ad)
+    out = B.nvfp4_46_quantize(torch.from_numpy(x).cuda(), ad, select=select)
     assert np.array_equal(_np(out["choice_row"]), f_ref)
     assert np.array_equal(_np(out["scales_row"]), s_ref)
     assert np.array_equal(_np(out["codes_row"]), c_ref)
     # the same blocks along columns: x^T, quantized columnwise and in both orientations at once
     xt = np.ascontiguousarray(x.T)                            # [256][n/16]: rows % 16 == 0
-    c_ref, s_ref, f_ref = ref.quantize(xt, alpha, layout=ref.COLWISE)
+    c_ref, s_ref, f_ref = ref.quantize(xt, alpha, layout=ref.COLWISE, select=select)
     assert 0.25 < f_ref.mean() < 0.75
     for layout in (B.COLWISE, B.BOTH):
-        out = B.nvfp4_46_quantize(torch.from_numpy(xt).cuda(), ad, layout=layout)
+        out = B.nvfp4_46_quantize(torch.from_numpy(xt).cuda(), ad, layout=layout, select=select)
         assert np.array_equal(_np(out["choice_col"]), f_ref)
         assert np.array_equal(_np(out["scales_col"]), s_ref)
         assert np.array_equal(_np(out["codes_col"]), c_ref)
