@@ -286,6 +286,15 @@ def test_block2d_both_packings_past_one_round_of_the_grid():
             assert np.array_equal(_np(out["choice_row"]), f_ref)
 
 
+@pytest.mark.parametrize("shape", [(16, 16), (16, 80), (272, 16), (32, 48), (64, 64)])
+def test_block2d_smallest_shapes_in_every_packing(shape):
+    """One tile, one row of tiles, one column of tiles, and less than one of the kernel's
+    16 x 4-tile work units in either direction."""
+    for layout in (B.ROWWISE, B.COLWISE, B.BOTH):
+        check_case_2d(dict(name="c2", rows=shape[0], cols=shape[1], layout=layout, rounding=B.RTN,
+                           select=B.SEL_46_MSE, f32=False), 9400, f"2d-small-{shape}-{layout}")
+
+
 def _sweep_cases_2d(n, seed):
     rng = np.random.default_rng(seed)
     cases = []
