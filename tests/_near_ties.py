@@ -72,36 +72,41 @@ def crossings(n_trials, seed, tree, alpha=None):
 BLOCK_STEPS = (-64, -16, -4, -3, -2, -1, 0, 1, 2, 3, 4, 5, 16, 64)
 
 
-def block_crossings(n_trials, seed, tree, alpha, select=None):
+def block_crossings(n_trials, seed, tree, alpha, select=None, rounding=ref.RTN, uniforms=None,
+                    samples=48, elements=8):
     """The same for one block of sixteen values under the tensor scale alpha: yields
     (block, i, first_pattern, S6, S4); block[i] set to the patterns first_pattern + BLOCK_STEPS
     walks across a crossing of the two candidates' block errors (here one fp32 step of the
     element moves an error by about one last bit, so the crossing is a few steps wide).
-    `select` None: squared errors; ref.SEL_46_MAE: sums of absolute errors."""
+    `select` None: squared errors; ref.SEL_46_MAE: sums of absolute errors.  With stochastic
+    rounding, `uniforms(k)` gives the sixteen uniforms of the k-th block yielded (they belong
+    to its place in the caller's tensor); a failed search tries again for the same place."""
     rng = np.random.default_rng(seed)
+    yielded = 0
     for trial in range(n_trials):
         v = (np.sign(rng.standard_normal(16)) * rng.random(16) ** 2.2).astype(F)
         v *= F(2.0) ** int(rng.integers(-8, 9))
         b = float(np.abs(v).max())
         S6, S4 = ref.block_scale(b, alpha, 6.0), ref.block_scale(b, alpha, 4.0)
+        u = None if uniforms is None else uniforms(yielded)
 
         def at(i, pattern):
             w = v.copy()
             w[i] = np.uint32(pattern).view(F)
-            E6, _, d6 = ref.block_with_scale(w, alpha, S6)
-            E4, _, d4 = ref.block_with_scale(w, alpha, S4)
+            E6, _, d6 = ref.block_with_scale(w, alpha, S6, rounding, u)
+            E4, _, d4 = ref.block_with_scale(w, alpha, S4, rounding, u)
             if select is not None:
                 E6, E4 = ref.block_abs_metric(w, d6, select), ref.block_abs_metric(w, d4, select)
             return float(E4) - float(E6), (float(d6[i]), float(d4[i]))
 
         found = None
-        for i in rng.permutation(16)[:8]:
+        for i in rng.permutation(16)[:elements]:
             i = int(i)
             if not 0.02 * b < abs(v[i]) < 0.6 * b:
                 continue
             prev = None
-            for k in range(48):
-                pattern = int(F(v[i] * F(0.5 + k / 47.0)).view(np.uint32))
+            for k in range(samples):
+                pattern = int(F(v[i] * F(0.5 + k / (samples - 1.0))).view(np.uint32))
                 g, dq = at(i, pattern)
                 if prev and prev[2] == dq and g != 0 and prev[1] != 0 and (g < 0) != (prev[1] < 0):
                     found = (i, prev[0], pattern)
@@ -122,4 +127,5 @@ def block_crossings(n_trials, seed, tree, alpha, select=None):
                 lo = mid
             else:
                 hi = mid
+        yielded += 1
         yield v, i, lo, S6, S4

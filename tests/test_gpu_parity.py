@@ -376,6 +376,39 @@ def test_blocks_within_a_few_steps_of_a_tie(select):
         assert np.array_equal(_np(out["codes_col"]), c_ref)
 
 
+def test_stochastically_rounded_blocks_within_a_step_of_a_tie():
+    """The same with stochastic rounding: every block is built for its own place in the tensor
+    (its uniforms are those of its elements' indices) so that its two stochastically rounded
+    candidates' errors cross between two adjacent fp32 values of one element; the element sits
+    on one side or the other of the crossing, alternating."""
+    from tests._near_ties import block_crossings
+    from tests.test_oracle_order_transcriptions import _tree_of_halves
+    alpha = float(np.float32(1.0) / np.float32(1536.0))
+    cols = 256
+
+    def uniforms(k):                      # block k -> row k // 16, columns 16 (k % 16) ...
+        g0 = (k // 16) * cols + 16 * (k % 16)
+        return np.array([ref.sr_uniform(SR_SEED, g0 + j) for j in range(16)], np.float32)
+
+    blocks = []
+    for v, i, first, _, _ in block_crossings(6000, 4697, _tree_of_halves, alpha, None, ref.SR, uniforms,
+                                             samples=24, elements=4):
+        w = v.copy()
+        w[i] = np.uint32(first + (-1, 0, 1, 2)[len(blocks) % 4]).view(np.float32)
+        blocks.append(w)
+        if len(blocks) == 512:
+            break
+    assert len(blocks) == 512
+    x = np.stack(blocks).reshape(32, cols)
+    c_ref, s_ref, f_ref = ref.quantize(x, alpha, rounding=ref.SR, sr_seed=SR_SEED)
+    assert 0.25 < f_ref.mean() < 0.75
+    ad = torch.tensor([alpha], dtype=torch.float32, device="cuda")
+    out = B.nvfp4_46_quantize(torch.from_numpy(x).cuda(), ad, rounding=B.SR, sr_seed=SR_SEED)
+    assert np.array_equal(_np(out["choice_row"]), f_ref)
+    assert np.array_equal(_np(out["scales_row"]), s_ref)
+    assert np.array_equal(_np(out["codes_row"]), c_ref)
+
+
 def test_block2d_tiles_within_a_few_steps_of_a_tie():
     """Tiles whose two candidates' errors cross between two adjacent fp32 values of one element
     (tests/_near_ties.py), eighteen steps around each crossing, one tile each, under one common
